@@ -1,0 +1,132 @@
+"""Pins for the oracle's group norms, group-lasso gradient and zero-group detection (CPU only)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(shape, seed):
+    return np.random.Generator(np.random.PCG64(seed)).standard_normal(shape)
+
+
+def _golden():
+    out = {}
+    with open(os.path.join(GOLDEN, "group_lasso_2x1x2.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            k, *v = line.split()
+            out[k] = np.array([float(t) for t in v])
+    return out
+
+
+def test_golden_hand_example():
+    g = _golden()
+    w = np.array([[3.0, 0.0], [4.0, 0.0]]).reshape(2, 1, 1, 2)
+    on, inn = oracle.group_norms(w)
+    assert np.array_equal(on, g["out_norm"]) and np.array_equal(inn, g["in_norm"])
+    assert on.sum() + inn.sum() == g["penalty"][0]
+    grad = oracle.group_lasso_grad(w, on, inn, 0.5, 3, np.zeros_like(w))
+    np.testing.assert_allclose(grad.reshape(-1), g["grad"], rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("shape", [(5, 3, 3, 7), (8, 1, 1, 3), (3, 7, 7, 2)])
+def test_norms_match_numpy_linalg(shape):
+    w = _rand(shape, 1)
+    on, inn = oracle.group_norms(w)
+    K, C = shape[0], shape[-1]
+    np.testing.assert_allclose(on, np.linalg.norm(w.reshape(K, -1), axis=1), rtol=1e-14)
+    np.testing.assert_allclose(inn, np.linalg.norm(w.reshape(-1, C), axis=0), rtol=1e-14)
+    # every weight sits in exactly one group of each kind
+    fro2 = float(np.sum(w * w))
+    assert abs(np.sum(on ** 2) - fro2) < 1e-12 * fro2
+    assert abs(np.sum(inn ** 2) - fro2) < 1e-12 * fro2
+
+
+def test_grad_closed_form_per_group():
+    w = _rand((6, 3, 3, 5), 2)
+    on, inn = oracle.group_norms(w)
+    lam = 0.37
+    z = np.zeros_like(w)
+    g_out = oracle.group_lasso_grad(w, on, inn, lam, 1, z)
+    g_in = oracle.group_lasso_grad(w, on, inn, lam, 2, z)
+    g_both = oracle.group_lasso_grad(w, on, inn, lam, 3, z)
+    for k in range(6):
+        np.testing.assert_allclose(g_out[k], lam * w[k] / np.linalg.norm(w[k]), rtol=1e-13)
+        # with only output groups, each filter's gradient has L2 norm exactly lambda
+        assert abs(np.linalg.norm(g_out[k]) - lam) < 1e-13
+    for c in range(5):
+        np.testing.assert_allclose(g_in[..., c], lam * w[..., c] / np.linalg.norm(w[..., c]), rtol=1e-13)
+    np.testing.assert_allclose(g_both, g_out + g_in, rtol=1e-13)
+    assert np.array_equal(oracle.group_lasso_grad(w, on, inn, lam, 0, z), z)
+
+
+def test_grad_accumulates_onto_dw():
+    w = _rand((4, 1, 1, 3), 3)
+    dw0 = _rand((4, 1, 1, 3), 4)
+    on, inn = oracle.group_norms(w)
+    g = oracle.group_lasso_grad(w, on, inn, 0.1, 3, np.zeros_like(w))
+    np.testing.assert_allclose(oracle.group_lasso_grad(w, on, inn, 0.1, 3, dw0), dw0 + g, rtol=1e-14)
+
+
+def test_grad_matches_finite_differences_of_penalty():
+    w = _rand((4, 3, 3, 3), 5)
+    lam = 1e-2
+
+    def penalty(v):
+        on, inn = oracle.group_norms(v)
+        return lam * (on.sum() + inn.sum())
+
+    on, inn = oracle.group_norms(w)
+    g = oracle.group_lasso_grad(w, on, inn, lam, 3, np.zeros_like(w))
+    rng = np.random.Generator(np.random.PCG64(6))
+    eps = 1e-6
+    for _ in range(25):
+        i = tuple(rng.integers(0, d) for d in w.shape)
+        wp, wm = w.copy(), w.copy()
+        wp[i] += eps
+        wm[i] -= eps
+        fd = (penalty(wp) - penalty(wm)) / (2 * eps)
+        assert abs(fd - g[i]) < 1e-8
+
+
+def test_euler_identity_and_scale_invariance():
+    w = _rand((5, 3, 3, 4), 7)
+    lam = 0.2
+    on, inn = oracle.group_norms(w)
+    g = oracle.group_lasso_grad(w, on, inn, lam, 3, np.zeros_like(w))
+    # penalty is homogeneous of degree 1: <w, grad> = lambda * penalty
+    assert abs(np.sum(w * g) - lam * (on.sum() + inn.sum())) < 1e-12
+    on2, in2 = oracle.group_norms(3.5 * w)
+    np.testing.assert_allclose(on2, 3.5 * on, rtol=1e-14)
+    g2 = oracle.group_lasso_grad(3.5 * w, on2, in2, lam, 3, np.zeros_like(w))
+    np.testing.assert_allclose(g2, g, rtol=1e-13)
+
+
+def test_zero_groups_get_zero_gradient_and_are_detected():
+    w = _rand((6, 3, 3, 5), 8)
+    w[2] = 0.0
+    w[..., 4] = 0.0
+    on, inn = oracle.group_norms(w)
+    assert on[2] == 0.0 and inn[4] == 0.0
+    g = oracle.group_lasso_grad(w, on, inn, 1.0, 3, np.zeros_like(w))
+    assert np.all(g[2] == 0.0) and np.all(g[..., 4] == 0.0)
+    assert np.all(np.isfinite(g))
+    zo, zi = oracle.zero_groups(on, 1e-6), oracle.zero_groups(inn, 1e-6)
+    assert zo.tolist() == [0, 0, 1, 0, 0, 0] and zi.tolist() == [0, 0, 0, 0, 1]
+
+
+def test_zero_groups_threshold_is_strict():
+    n = np.array([0.0, 1e-4, 0.99e-4, 1.01e-4, 5.0])
+    assert oracle.zero_groups(n, 1e-4).tolist() == [1, 0, 1, 0, 0]
+    assert oracle.zero_groups(n, 0.0).tolist() == [0, 0, 0, 0, 0]
+    assert oracle.zero_groups(n, -1.0).tolist() == [0, 0, 0, 0, 0]
+    # L2 norm is never below the largest magnitude in the group, so a norm test prunes no more
+    # than the paper's max-abs wording (Sec. 4.2) and both agree on exactly-zero groups
+    w = _rand((4, 3, 3, 4), 9) * 1e-4
+    on, _ = oracle.group_norms(w)
+    assert np.all(on >= np.abs(w).reshape(4, -1).max(axis=1))
