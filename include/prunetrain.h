@@ -1,0 +1,149 @@
+/*
+ * prunetrain.h - C ABI of the MI355X (gfx950) PruneTrain conv-layer hot path.
+ *
+ * One training step of a convolution layer (forward, input gradient, weight gradient), the
+ * channel-granular group-lasso regulariser (group norms and its gradient), and the periodic
+ * reconfiguration pieces (zero-group detection, channel-edge reconciliation, compaction plan and
+ * the compaction gathers), as the paper states them: Sec. 2.1 and Alg. 1 (ForwardProp / BackProp),
+ * Eq. 4 (weight gradient), Eq. 1-2 (group lasso), Sec. 4.1 (threshold zeroing), Sec. 4.2
+ * (adjacent-layer intersection, channel union, state carry-over at reconfiguration).
+ *
+ * Conventions
+ *  - Every pointer named in a call is DEVICE memory owned by the caller unless the comment says
+ *    "host".  The library never allocates, frees or retains memory and never synchronises: all
+ *    work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream) and
+ *    buffers must stay valid until the stream has executed the call.
+ *  - Layouts: activations NHWC  x[N][H][W][x_cpitch], y[N][P][Q][y_cpitch];
+ *             weights     KRSC  w[K][R][S][w_cpitch].
+ *    A `*_cpitch` is the physical length, in elements, of the innermost (channel) axis; it is
+ *    >= the logical channel count.  Elements between the logical count and the pitch are never
+ *    read as data and are never written.  Pitches that are multiples of 8 elements (16 bytes of
+ *    bf16) select the vectorised kernels; any other pitch takes a slower element-wise path with
+ *    identical results.
+ *  - bf16 tensors are passed as uint16_t bit patterns (IEEE bfloat16, round-to-nearest-even on
+ *    conversion from fp32).  Convolutions multiply bf16 inputs and accumulate in fp32.
+ *  - Outputs are fully overwritten (logical elements only) except where a call says it accumulates.
+ *    Inputs and outputs must not alias.
+ *  - Every call returns a pt_status.  Argument errors are detected on the host before anything is
+ *    enqueued.  No exception crosses this boundary.
+ */
+#ifndef PRUNETRAIN_H
+#define PRUNETRAIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pt_status {
+    PT_OK = 0,
+    PT_ERR_NULL = -1,        /* a required pointer is NULL */
+    PT_ERR_SHAPE = -2,       /* inconsistent descriptor: zero/negative extent, P/Q mismatch, pitch < extent */
+    PT_ERR_WORKSPACE = -3,   /* workspace smaller than the matching *_workspace_bytes() */
+    PT_ERR_UNSUPPORTED = -4, /* valid but outside this build's limits (see each call) */
+    PT_ERR_LAUNCH = -5,      /* a HIP call failed; pt_last_hip_error() holds its code */
+    PT_ERR_EMPTY = -6        /* reserved: a keep mask with no survivors (layer removal is the caller's job) */
+} pt_status;
+
+/* Convolution problem: cross-correlation with zero padding, dilation 1, one group, no bias.
+ * P = (H + 2*pad_h - R)/stride_h + 1, Q likewise; the call checks them. */
+typedef struct pt_conv_desc {
+    uint32_t struct_size; /* sizeof(pt_conv_desc), checked */
+    int32_t N, H, W, C;   /* input  x[N][H][W][C] */
+    int32_t K, R, S;      /* filter w[K][R][S][C] */
+    int32_t stride_h, stride_w, pad_h, pad_w;
+    int32_t P, Q;         /* output y[N][P][Q][K] */
+    int32_t x_cpitch;     /* channel pitch of x and dx (>= C) */
+    int32_t y_cpitch;     /* channel pitch of y and dy (>= K) */
+    int32_t w_cpitch;     /* channel pitch of w (bf16) and of dw (fp32) (>= C) */
+} pt_conv_desc;
+
+/* Library version (major*10000 + minor*100 + patch) and the last failing HIP error code (0 if none). */
+int32_t pt_version(void);
+int32_t pt_last_hip_error(void);
+
+/* ---- convolution: Sec. 2.1, Alg. 1 ForwardProp / BackProp, Eq. 4 ---------------------------- */
+
+/* Host-only: bytes of workspace each convolution call needs for this descriptor (may be 0). */
+int32_t pt_conv_fwd_workspace_bytes(const pt_conv_desc* d, size_t* bytes);
+int32_t pt_conv_bwd_data_workspace_bytes(const pt_conv_desc* d, size_t* bytes);
+int32_t pt_conv_bwd_weight_workspace_bytes(const pt_conv_desc* d, size_t* bytes);
+
+/* y[n,p,q,k] = sum_{r,s,c} x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c] * w[k,r,s,c].
+ * x, w bf16; y bf16 (fp32 accumulator rounded once). ws: device scratch of ws_bytes (256-byte aligned). */
+int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, uint16_t* y, void* ws,
+                    size_t ws_bytes, void* stream);
+
+/* dx = adjoint of the forward map in x applied to dy:
+ * dx[n,h,w,c] = sum over (p,q,k,r,s) with p*stride_h - pad_h + r == h, q*stride_w - pad_w + s == w
+ *               of dy[n,p,q,k] * w[k,r,s,c].   dy, w bf16; dx bf16, every logical element written
+ * (zeros where no output pixel reads the input pixel). */
+int32_t pt_conv_bwd_data(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* w, uint16_t* dx, void* ws,
+                         size_t ws_bytes, void* stream);
+
+/* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c]  (Eq. 4;
+ * plain sum over the mini-batch).  x, dy bf16; dw fp32 [K][R][S][w_cpitch].  The reduction is split
+ * over workgroups into ws and combined in a fixed order: results are run-to-run identical. */
+int32_t pt_conv_bwd_weight(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, float* dw, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/* ---- group lasso: Eq. 1-2 ------------------------------------------------------------------- */
+
+/* Channel-group L2 norms of one layer's fp32 master weights w[K][RS][w_cpitch], RS = R*S:
+ *   out_norm[k] = ||w[k,:,:]||_2 (filter k), in_norm[c] = ||w[:,:,c]||_2 (input channel c).
+ * If w_shadow is not NULL it receives the bf16 copy of w (same shape and pitch) that the
+ * convolutions consume, produced from the same single read of w.
+ * Limits: C <= 16384.  Deterministic (fixed reduction order). */
+int32_t pt_group_norms_workspace_bytes(int32_t K, int32_t RS, int32_t C, size_t* bytes);
+int32_t pt_group_norms(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, float* out_norm,
+                       float* in_norm, uint16_t* w_shadow, void* ws, size_t ws_bytes, void* stream);
+
+/* Adds the gradient of lambda * (sum_k out_norm[k] + sum_c in_norm[c]) onto dw (accumulates):
+ *   dw[k,rs,c] += lambda * w[k,rs,c] * (a / out_norm[k] + b / in_norm[c]),
+ * a = flags bit 0 (regularise output groups), b = flags bit 1 (regularise input groups; clear it for
+ * the network's first convolution, whose input groups are exempt).  A group whose norm is exactly 0
+ * contributes 0.  dw has the shape and pitch of w. */
+#define PT_LASSO_OUT 1u
+#define PT_LASSO_IN 2u
+int32_t pt_group_lasso_grad(const float* w, const float* out_norm, const float* in_norm, float lambda,
+                            uint32_t flags, float* dw, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch,
+                            void* stream);
+
+/* ---- reconfiguration: Sec. 4.1-4.2 ---------------------------------------------------------- */
+
+/* zero[g] = (norms[g] < thr) ? 1 : 0, compared in fp32; thr <= 0 marks nothing. n may be 0. */
+int32_t pt_zero_groups(const float* norms, int32_t n, float thr, uint8_t* zero, void* stream);
+
+/* One channel edge: the output dimension of n_prod producer convolutions and the input dimension of
+ * n_cons consumer convolutions must stay equal.  keep[j] = 0 only when channel j is zero in EVERY
+ * producer's output mask and EVERY consumer's input mask (adjacent-layer intersection for 1+1,
+ * channel union for a residual stage).  producer_zero / consumer_zero are HOST arrays of device
+ * pointers to n-element masks; n_prod + n_cons must be in [1, 64]. */
+int32_t pt_reconcile_edge(const uint8_t* const* producer_zero, int32_t n_prod, const uint8_t* const* consumer_zero,
+                          int32_t n_cons, int32_t n, uint8_t* keep, void* stream);
+
+/* idx[0 .. *n_keep) = ascending positions j with keep[j] != 0 (exclusive prefix sum of the mask);
+ * idx must hold n entries; *n_keep_dev is written on the device (read it after synchronising). */
+int32_t pt_compact_plan(const uint8_t* keep, int32_t n, int32_t* idx, int32_t* n_keep_dev, void* stream);
+
+/* w_out[k'][rs][c'] = w[idxK[k']][rs][idxC[c']] for fp32 tensors (weights, their momentum).  A NULL index
+ * list is the identity on that axis (then Kp == K / Cp == C).  Index values must lie inside the source. */
+int32_t pt_compact_weights(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, const int32_t* idxK,
+                           int32_t Kp, const int32_t* idxC, int32_t Cp, float* w_out, int32_t out_cpitch,
+                           void* stream);
+
+/* out[j'] = v[idx[j']] for per-channel vectors (bias, normalisation scale/shift/statistics, momentum);
+ * elem_bytes in {1, 2, 4, 8}. n_keep may be 0. */
+int32_t pt_compact_vector(const void* v, int32_t elem_bytes, const int32_t* idx, int32_t n_keep, void* out,
+                          void* stream);
+
+/* out[pix][c'] = x[pix][idx[c']] for bf16 NHWC activations with `pixels` = N*H*W rows. */
+int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const int32_t* idx,
+                        int32_t Cp, uint16_t* out, int32_t out_cpitch, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,195 @@
+"""Thin ctypes binding of libprunetrain.so: same names as include/prunetrain.h without the pt_ prefix.
+
+Argument marshalling only.  Tensors are torch tensors on the GPU (torch is used for device memory
+and streams, nothing else); every step of the path runs inside the HIP library.  There is no CPU
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libprunetrain.so")
+_lib = None
+
+PT_OK = 0
+STATUS = {0: "PT_OK", -1: "PT_ERR_NULL", -2: "PT_ERR_SHAPE", -3: "PT_ERR_WORKSPACE", -4: "PT_ERR_UNSUPPORTED",
+          -5: "PT_ERR_LAUNCH", -6: "PT_ERR_EMPTY"}
+LASSO_OUT, LASSO_IN = 1, 2
+
+EXPORTS = [
+    "pt_version", "pt_last_hip_error",
+    "pt_conv_fwd_workspace_bytes", "pt_conv_bwd_data_workspace_bytes", "pt_conv_bwd_weight_workspace_bytes",
+    "pt_conv_fwd", "pt_conv_bwd_data", "pt_conv_bwd_weight",
+    "pt_group_norms_workspace_bytes", "pt_group_norms", "pt_group_lasso_grad",
+    "pt_zero_groups", "pt_reconcile_edge", "pt_compact_plan",
+    "pt_compact_weights", "pt_compact_vector", "pt_compact_nhwc",
+]
+
+
+class PruneTrainError(RuntimeError):
+    def __init__(self, call: str, status: int):
+        self.status = status
+        hip = lib().pt_last_hip_error() if status == -5 else 0
+        super().__init__(f"{call}: {STATUS.get(status, status)}" + (f" (hip error {hip})" if hip else ""))
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_int32) for n in (
+        "N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "P", "Q",
+        "x_cpitch", "y_cpitch", "w_cpitch")]
+
+
+def lib() -> C.CDLL:
+    """The loaded HIP library; loading failure is fatal (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            raise ImportError(f"{_SO} is not built: run `python -m paper_1901_09290_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no CPU fallback")
+        _lib = C.CDLL(_SO)
+        vp, i32, i64, u32, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_float, C.c_size_t
+        dp = C.POINTER(ConvDesc)
+        sig = {
+            "pt_version": [], "pt_last_hip_error": [],
+            "pt_conv_fwd_workspace_bytes": [dp, C.POINTER(sz)],
+            "pt_conv_bwd_data_workspace_bytes": [dp, C.POINTER(sz)],
+            "pt_conv_bwd_weight_workspace_bytes": [dp, C.POINTER(sz)],
+            "pt_conv_fwd": [dp, vp, vp, vp, vp, sz, vp],
+            "pt_conv_bwd_data": [dp, vp, vp, vp, vp, sz, vp],
+            "pt_conv_bwd_weight": [dp, vp, vp, vp, vp, sz, vp],
+            "pt_group_norms_workspace_bytes": [i32, i32, i32, C.POINTER(sz)],
+            "pt_group_norms": [vp, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
+            "pt_group_lasso_grad": [vp, vp, vp, f32, u32, vp, i32, i32, i32, i32, vp],
+            "pt_zero_groups": [vp, i32, f32, vp, vp],
+            "pt_reconcile_edge": [C.POINTER(vp), i32, C.POINTER(vp), i32, i32, vp, vp],
+            "pt_compact_plan": [vp, i32, vp, vp, vp],
+            "pt_compact_weights": [vp, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp],
+            "pt_compact_vector": [vp, i32, vp, i32, vp, vp],
+            "pt_compact_nhwc": [vp, i64, i32, i32, vp, i32, vp, i32, vp],
+        }
+        for name, args in sig.items():
+            fn = getattr(_lib, name)
+            fn.argtypes = args
+            fn.restype = i32
+    return _lib
+
+
+def _ck(name: str, rc: int) -> None:
+    if rc != PT_OK:
+        raise PruneTrainError(name, rc)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    return getattr(stream, "cuda_stream", stream) or None
+
+
+def conv_desc(N, H, W, Cc, K, R, S, stride, pad, x_cpitch=None, y_cpitch=None, w_cpitch=None) -> ConvDesc:
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    return ConvDesc(C.sizeof(ConvDesc), N, H, W, Cc, K, R, S, stride, stride, pad, pad, P, Q,
+                    x_cpitch or Cc, y_cpitch or K, w_cpitch or Cc)
+
+
+def desc_of(spec, x_cpitch=None, y_cpitch=None, w_cpitch=None) -> ConvDesc:
+    return conv_desc(spec.N, spec.H, spec.W, spec.C, spec.K, spec.R, spec.S, spec.stride, spec.pad,
+                     x_cpitch, y_cpitch, w_cpitch)
+
+
+def version() -> int:
+    return lib().pt_version()
+
+
+def _ws_bytes(fn: str, d: ConvDesc) -> int:
+    n = C.c_size_t(0)
+    _ck(fn, getattr(lib(), fn)(C.byref(d), C.byref(n)))
+    return n.value
+
+
+def conv_fwd_workspace_bytes(d: ConvDesc) -> int:
+    return _ws_bytes("pt_conv_fwd_workspace_bytes", d)
+
+
+def conv_bwd_data_workspace_bytes(d: ConvDesc) -> int:
+    return _ws_bytes("pt_conv_bwd_data_workspace_bytes", d)
+
+
+def conv_bwd_weight_workspace_bytes(d: ConvDesc) -> int:
+    return _ws_bytes("pt_conv_bwd_weight_workspace_bytes", d)
+
+
+def _ws(ws):
+    return (None, 0) if ws is None else (ws.data_ptr(), ws.numel() * ws.element_size())
+
+
+def conv_fwd(d: ConvDesc, x, w, y, ws=None, stream=None) -> None:
+    p, n = _ws(ws)
+    _ck("pt_conv_fwd", lib().pt_conv_fwd(C.byref(d), _ptr(x), _ptr(w), _ptr(y), p, n, _stream(stream)))
+
+
+def conv_bwd_data(d: ConvDesc, dy, w, dx, ws=None, stream=None) -> None:
+    p, n = _ws(ws)
+    _ck("pt_conv_bwd_data", lib().pt_conv_bwd_data(C.byref(d), _ptr(dy), _ptr(w), _ptr(dx), p, n, _stream(stream)))
+
+
+def conv_bwd_weight(d: ConvDesc, x, dy, dw, ws=None, stream=None) -> None:
+    p, n = _ws(ws)
+    _ck("pt_conv_bwd_weight",
+        lib().pt_conv_bwd_weight(C.byref(d), _ptr(x), _ptr(dy), _ptr(dw), p, n, _stream(stream)))
+
+
+def group_norms_workspace_bytes(K: int, RS: int, Cc: int) -> int:
+    n = C.c_size_t(0)
+    _ck("pt_group_norms_workspace_bytes", lib().pt_group_norms_workspace_bytes(K, RS, Cc, C.byref(n)))
+    return n.value
+
+
+def group_norms(w, K, RS, Cc, w_cpitch, out_norm, in_norm, w_shadow=None, ws=None, stream=None) -> None:
+    p, n = _ws(ws)
+    _ck("pt_group_norms", lib().pt_group_norms(_ptr(w), K, RS, Cc, w_cpitch, _ptr(out_norm), _ptr(in_norm),
+                                               _ptr(w_shadow), p, n, _stream(stream)))
+
+
+def group_lasso_grad(w, out_norm, in_norm, lam: float, flags: int, dw, K, RS, Cc, w_cpitch, stream=None) -> None:
+    _ck("pt_group_lasso_grad", lib().pt_group_lasso_grad(_ptr(w), _ptr(out_norm), _ptr(in_norm), lam, flags, _ptr(dw),
+                                                         K, RS, Cc, w_cpitch, _stream(stream)))
+
+
+def zero_groups(norms, n: int, thr: float, zero, stream=None) -> None:
+    _ck("pt_zero_groups", lib().pt_zero_groups(_ptr(norms), n, thr, _ptr(zero), _stream(stream)))
+
+
+def reconcile_edge(producer_zero: Sequence, consumer_zero: Sequence, n: int, keep, stream=None) -> None:
+    pa = (C.c_void_p * max(1, len(producer_zero)))(*[t.data_ptr() for t in producer_zero])
+    ca = (C.c_void_p * max(1, len(consumer_zero)))(*[t.data_ptr() for t in consumer_zero])
+    _ck("pt_reconcile_edge", lib().pt_reconcile_edge(pa if len(producer_zero) else None, len(producer_zero),
+                                                     ca if len(consumer_zero) else None, len(consumer_zero), n,
+                                                     _ptr(keep), _stream(stream)))
+
+
+def compact_plan(keep, n: int, idx, n_keep_dev, stream=None) -> None:
+    _ck("pt_compact_plan", lib().pt_compact_plan(_ptr(keep), n, _ptr(idx), _ptr(n_keep_dev), _stream(stream)))
+
+
+def compact_weights(w, K, RS, Cc, w_cpitch, idxK, Kp, idxC, Cp, w_out, out_cpitch, stream=None) -> None:
+    _ck("pt_compact_weights", lib().pt_compact_weights(_ptr(w), K, RS, Cc, w_cpitch, _ptr(idxK), Kp, _ptr(idxC), Cp,
+                                                       _ptr(w_out), out_cpitch, _stream(stream)))
+
+
+def compact_vector(v, elem_bytes: int, idx, n_keep: int, out, stream=None) -> None:
+    _ck("pt_compact_vector", lib().pt_compact_vector(_ptr(v), elem_bytes, _ptr(idx), n_keep, _ptr(out),
+                                                     _stream(stream)))
+
+
+def compact_nhwc(x, pixels: int, Cc: int, x_cpitch: int, idx, Cp: int, out, out_cpitch: int, stream=None) -> None:
+    _ck("pt_compact_nhwc", lib().pt_compact_nhwc(_ptr(x), pixels, Cc, x_cpitch, _ptr(idx), Cp, _ptr(out), out_cpitch,
+                                                 _stream(stream)))

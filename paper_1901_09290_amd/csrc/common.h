@@ -1,0 +1,44 @@
+// Shared host/device helpers of the HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "prunetrain.h"
+
+namespace pt {
+
+constexpr int kWave = 64;
+
+// Records the last failing HIP error for pt_last_hip_error().
+void set_hip_error(hipError_t e);
+
+inline int32_t launch_status() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_hip_error(e);
+        return PT_ERR_LAUNCH;
+    }
+    return PT_OK;
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Exact floor(m / d) for m*d < 2^32 with magic = floor(2^32 / d) + 1 (computed on the host).
+__device__ __forceinline__ uint32_t fast_div(uint32_t m, uint32_t magic) { return __umulhi(m, magic); }
+inline uint32_t make_magic(uint32_t d) { return (uint32_t)((((uint64_t)1) << 32) / d + 1); }
+
+}  // namespace pt

@@ -1,0 +1,207 @@
+// Reconfiguration kernels (Sec. 4.1-4.2): zero-group detection, channel-edge reconciliation,
+// compaction plan (prefix sum over the keep mask) and the compaction gathers.  All integer/byte
+// results are exact; the gathers are pure data movement and HBM-bound.
+#include "common.h"
+
+namespace pt {
+
+__global__ void k_zero_groups(const float* __restrict__ norms, int n, float thr, uint8_t* __restrict__ zero) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) zero[i] = norms[i] < thr ? 1 : 0;
+}
+
+constexpr int kMaxEdgeMembers = 64;
+struct EdgeMasks {
+    const uint8_t* m[kMaxEdgeMembers];
+    int count;
+};
+
+// keep[j] = 0 iff channel j is flagged zero by every member of the edge.
+__global__ void k_reconcile_edge(EdgeMasks e, int n, uint8_t* __restrict__ keep) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    uint8_t all_zero = 1;
+    for (int a = 0; a < e.count; ++a) all_zero &= (e.m[a][j] != 0);
+    keep[j] = all_zero ? 0 : 1;
+}
+
+// Single workgroup, 1024 threads: chunked exclusive scan with wavefront ballots.
+__global__ __launch_bounds__(1024) void k_compact_plan(const uint8_t* __restrict__ keep, int n, int* __restrict__ idx,
+                                                       int* __restrict__ n_keep) {
+    __shared__ int wave_tot[16];
+    __shared__ int base_s;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (tid == 0) base_s = 0;
+    __syncthreads();
+    for (int j0 = 0; j0 < n; j0 += 1024) {
+        const int j = j0 + tid;
+        const bool k = (j < n) && keep[j] != 0;
+        const unsigned long long b = __ballot(k);
+        const int pre = __popcll(b & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_tot[wv] = __popcll(b);
+        __syncthreads();
+        int off = base_s;
+        for (int a = 0; a < wv; ++a) off += wave_tot[a];
+        if (k) idx[off + pre] = j;
+        __syncthreads();
+        if (tid == 0) {
+            int t = 0;
+            for (int a = 0; a < 16; ++a) t += wave_tot[a];
+            base_s += t;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) *n_keep = base_s;
+}
+
+// One thread per output element group of 4 consecutive c'.
+__global__ void k_compact_weights(const float* __restrict__ w, int RS, int cpitch, const int* __restrict__ idxK,
+                                  const int* __restrict__ idxC, int Cp, int out_cpitch, int64_t out_rows,
+                                  float* __restrict__ out) {
+    const int cq = (Cp + 3) >> 2;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= out_rows * cq) return;
+    const int64_t row = t / cq;          // k' * RS + rs
+    const int c0 = (int)(t - row * cq) * 4;
+    const int64_t kp = row / RS;
+    const int rs = (int)(row - kp * RS);
+    const int64_t k = idxK ? idxK[kp] : kp;
+    const float* src = w + (k * RS + rs) * (int64_t)cpitch;
+    float* dst = out + row * (int64_t)out_cpitch + c0;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int c = c0 + e;
+        v[e] = (c < Cp) ? src[idxC ? idxC[c] : c] : 0.f;
+    }
+    if (c0 + 3 < Cp && (out_cpitch & 3) == 0 && (((uintptr_t)out & 15) == 0)) {
+        *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (c0 + e < Cp) dst[e] = v[e];
+    }
+}
+
+template <typename T>
+__global__ void k_compact_vector(const T* __restrict__ v, const int* __restrict__ idx, int n_keep, T* __restrict__ out) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < n_keep) out[j] = v[idx[j]];
+}
+
+// Activation gather along the innermost axis.  One thread produces 8 consecutive output channels of
+// one pixel (a 16-byte store when aligned).
+__global__ void k_compact_nhwc(const uint16_t* __restrict__ x, int64_t pixels, int x_cpitch,
+                               const int* __restrict__ idx, int Cp, uint16_t* __restrict__ out, int out_cpitch,
+                               int vec_ok) {
+    const int cv = (Cp + 7) >> 3;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= pixels * cv) return;
+    const int64_t pix = t / cv;
+    const int c0 = (int)(t - pix * cv) * 8;
+    const uint16_t* src = x + pix * (int64_t)x_cpitch;
+    uint16_t* dst = out + pix * (int64_t)out_cpitch + c0;
+    uint16_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (c0 + e < Cp) ? src[idx[c0 + e]] : (uint16_t)0;
+    if (vec_ok && c0 + 7 < Cp) {
+        uint4 o;
+        o.x = v[0] | ((uint32_t)v[1] << 16);
+        o.y = v[2] | ((uint32_t)v[3] << 16);
+        o.z = v[4] | ((uint32_t)v[5] << 16);
+        o.w = v[6] | ((uint32_t)v[7] << 16);
+        *reinterpret_cast<uint4*>(dst) = o;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (c0 + e < Cp) dst[e] = v[e];
+    }
+}
+
+}  // namespace pt
+
+using namespace pt;
+
+extern "C" int32_t pt_zero_groups(const float* norms, int32_t n, float thr, uint8_t* zero, void* stream) {
+    if (n < 0) return PT_ERR_SHAPE;
+    if (n == 0) return PT_OK;
+    if (!norms || !zero) return PT_ERR_NULL;
+    hipLaunchKernelGGL(k_zero_groups, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, norms, n, thr, zero);
+    return launch_status();
+}
+
+extern "C" int32_t pt_reconcile_edge(const uint8_t* const* producer_zero, int32_t n_prod,
+                                     const uint8_t* const* consumer_zero, int32_t n_cons, int32_t n, uint8_t* keep,
+                                     void* stream) {
+    if (n < 0 || n_prod < 0 || n_cons < 0 || n_prod + n_cons < 1) return PT_ERR_SHAPE;
+    if (n_prod + n_cons > kMaxEdgeMembers) return PT_ERR_UNSUPPORTED;
+    if ((n_prod > 0 && !producer_zero) || (n_cons > 0 && !consumer_zero)) return PT_ERR_NULL;
+    EdgeMasks e;
+    e.count = 0;
+    for (int a = 0; a < n_prod; ++a) {
+        if (!producer_zero[a]) return PT_ERR_NULL;
+        e.m[e.count++] = producer_zero[a];
+    }
+    for (int a = 0; a < n_cons; ++a) {
+        if (!consumer_zero[a]) return PT_ERR_NULL;
+        e.m[e.count++] = consumer_zero[a];
+    }
+    for (int a = e.count; a < kMaxEdgeMembers; ++a) e.m[a] = nullptr;
+    if (n == 0) return PT_OK;
+    if (!keep) return PT_ERR_NULL;
+    hipLaunchKernelGGL(k_reconcile_edge, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, e, n, keep);
+    return launch_status();
+}
+
+extern "C" int32_t pt_compact_plan(const uint8_t* keep, int32_t n, int32_t* idx, int32_t* n_keep_dev, void* stream) {
+    if (n < 0) return PT_ERR_SHAPE;
+    if (!n_keep_dev || (n > 0 && (!keep || !idx))) return PT_ERR_NULL;
+    hipLaunchKernelGGL(k_compact_plan, dim3(1), dim3(1024), 0, (hipStream_t)stream, keep, n, idx, n_keep_dev);
+    return launch_status();
+}
+
+extern "C" int32_t pt_compact_weights(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch,
+                                      const int32_t* idxK, int32_t Kp, const int32_t* idxC, int32_t Cp, float* w_out,
+                                      int32_t out_cpitch, void* stream) {
+    if (!w || !w_out) return PT_ERR_NULL;
+    if (K <= 0 || RS <= 0 || C <= 0 || Kp <= 0 || Cp <= 0 || w_cpitch < C || out_cpitch < Cp) return PT_ERR_SHAPE;
+    if ((!idxK && Kp != K) || (!idxC && Cp != C) || Kp > K || Cp > C) return PT_ERR_SHAPE;
+    const int64_t out_rows = (int64_t)Kp * RS;
+    const int64_t work = out_rows * ((Cp + 3) / 4);
+    const int64_t nblk = ceil_div(work, 256);
+    if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_compact_weights, dim3((unsigned)nblk), dim3(256), 0, (hipStream_t)stream, w, RS, w_cpitch, idxK,
+                       idxC, Cp, out_cpitch, out_rows, w_out);
+    return launch_status();
+}
+
+extern "C" int32_t pt_compact_vector(const void* v, int32_t elem_bytes, const int32_t* idx, int32_t n_keep, void* out,
+                                     void* stream) {
+    if (n_keep < 0) return PT_ERR_SHAPE;
+    if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8) return PT_ERR_UNSUPPORTED;
+    if (n_keep == 0) return PT_OK;
+    if (!v || !idx || !out) return PT_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 g((n_keep + 255) / 256), b(256);
+    switch (elem_bytes) {
+        case 1: hipLaunchKernelGGL(k_compact_vector<uint8_t>, g, b, 0, st, (const uint8_t*)v, idx, n_keep, (uint8_t*)out); break;
+        case 2: hipLaunchKernelGGL(k_compact_vector<uint16_t>, g, b, 0, st, (const uint16_t*)v, idx, n_keep, (uint16_t*)out); break;
+        case 4: hipLaunchKernelGGL(k_compact_vector<uint32_t>, g, b, 0, st, (const uint32_t*)v, idx, n_keep, (uint32_t*)out); break;
+        default: hipLaunchKernelGGL(k_compact_vector<uint64_t>, g, b, 0, st, (const uint64_t*)v, idx, n_keep, (uint64_t*)out); break;
+    }
+    return launch_status();
+}
+
+extern "C" int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const int32_t* idx,
+                                   int32_t Cp, uint16_t* out, int32_t out_cpitch, void* stream) {
+    if (pixels < 0 || C <= 0 || Cp <= 0 || Cp > C || x_cpitch < C || out_cpitch < Cp) return PT_ERR_SHAPE;
+    if (pixels == 0) return PT_OK;
+    if (!x || !idx || !out) return PT_ERR_NULL;
+    const int64_t work = pixels * ((Cp + 7) / 8);
+    const int64_t nblk = ceil_div(work, 256);
+    if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
+    const int vec_ok = (out_cpitch % 8 == 0) && (((uintptr_t)out & 15) == 0);
+    hipLaunchKernelGGL(k_compact_nhwc, dim3((unsigned)nblk), dim3(256), 0, (hipStream_t)stream, x, pixels, x_cpitch, idx,
+                       Cp, out, out_cpitch, vec_ok);
+    return launch_status();
+}

@@ -1,0 +1,96 @@
+"""Helpers for the GPU parity tests: host<->device marshalling and the error metrics.
+
+Tolerances (written here once, used by every test):
+  convolutions (bf16 in, fp32 accumulate; y/dx rounded to bf16, dw fp32):
+      max_i |gpu_i - ref_i| / (|ref_i| + rms(ref)) <= 2e-2
+  fp32 norm / lasso kernels: same formula, 1e-5
+  masks, indices, gathers: bit-exact.
+"""
+import numpy as np
+import torch
+
+from paper_1901_09290_amd import binding as B
+from paper_1901_09290_amd import workloads as wl
+
+CONV_TOL = 2e-2
+F32_TOL = 1e-5
+DEV = "cuda:0"
+
+
+def rel_err(got, ref) -> float:
+    got = np.asarray(got, dtype=np.float64).reshape(-1)
+    ref = np.asarray(ref, dtype=np.float64).reshape(-1)
+    assert got.shape == ref.shape
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms == 0.0:
+        return float(np.max(np.abs(got)))
+    return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
+
+
+def dev_bf16(a: np.ndarray, pitch=None) -> torch.Tensor:
+    """fp32 values on the bf16 grid -> device bf16 tensor; optional innermost pitch (padding = NaN so
+    that any use of padding as data poisons the result)."""
+    bits = wl.bf16_bits(a)
+    if pitch is not None and pitch != a.shape[-1]:
+        full = np.full(a.shape[:-1] + (pitch,), 0x7FC0, dtype=np.uint16)
+        full[..., : a.shape[-1]] = bits
+        bits = full
+    return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def host_bf16(t: torch.Tensor, C=None) -> np.ndarray:
+    """device bf16 tensor -> fp32 numpy (logical channels only)."""
+    bits = t.view(torch.int16).cpu().numpy().view(np.uint16)
+    v = wl.from_bf16_bits(bits).reshape(bits.shape)
+    return v if C is None else v[..., :C]
+
+
+def dev_f32(a: np.ndarray, pitch=None) -> torch.Tensor:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if pitch is not None and pitch != a.shape[-1]:
+        full = np.full(a.shape[:-1] + (pitch,), np.nan, dtype=np.float32)
+        full[..., : a.shape[-1]] = a
+        a = full
+    return torch.from_numpy(a).to(DEV)
+
+
+def empty_bf16(shape, fill=None) -> torch.Tensor:
+    t = torch.empty(shape, dtype=torch.bfloat16, device=DEV)
+    if fill is not None:
+        t.view(torch.int16).fill_(fill)
+    return t
+
+
+def workspace(nbytes: int) -> torch.Tensor:
+    return torch.empty(max(256, nbytes), dtype=torch.uint8, device=DEV)
+
+
+def pitch8(n: int) -> int:
+    return (n + 7) // 8 * 8
+
+
+def run_conv_all(spec, x, w, dy, xp=None, yp=None, wp=None):
+    """Runs fwd, bwd_data, bwd_weight through the C ABI. Returns (y, dx, dw) as fp32 numpy, logical extents.
+    Output buffers are pre-filled with a sentinel so unwritten elements are caught."""
+    xp, yp, wp = xp or spec.C, yp or spec.K, wp or spec.C
+    d = B.desc_of(spec, xp, yp, wp)
+    xd, wd, dyd = dev_bf16(x, xp), dev_bf16(w, wp), dev_bf16(dy, yp)
+    y = empty_bf16((spec.N, spec.P, spec.Q, yp), fill=0x7FC0)
+    dx = empty_bf16((spec.N, spec.H, spec.W, xp), fill=0x7FC0)
+    dw = torch.full((spec.K, spec.R, spec.S, wp), float("nan"), dtype=torch.float32, device=DEV)
+    ws = workspace(max(B.conv_fwd_workspace_bytes(d), B.conv_bwd_data_workspace_bytes(d),
+                       B.conv_bwd_weight_workspace_bytes(d)))
+    B.conv_fwd(d, xd, wd, y, ws)
+    B.conv_bwd_data(d, dyd, wd, dx, ws)
+    B.conv_bwd_weight(d, xd, dyd, dw, ws)
+    torch.cuda.synchronize()
+    # padding must be untouched (still the sentinel)
+    if yp != spec.K:
+        assert bool((y.view(torch.int16)[..., spec.K:] == 0x7FC0).all())
+    if xp != spec.C:
+        assert bool((dx.view(torch.int16)[..., spec.C:] == 0x7FC0).all())
+    if wp != spec.C:
+        assert bool(torch.isnan(dw[..., spec.C:]).all())
+    return host_bf16(y, spec.K), host_bf16(dx, spec.C), dw.cpu().numpy()[..., : spec.C]

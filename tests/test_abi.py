@@ -1,0 +1,85 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and its
+host-side argument validation answers with status codes before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1901_09290_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B._SO):
+        from paper_1901_09290_amd import build
+        build.build()
+    return B.lib()
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "prunetrain.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(pt_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_version(lib):
+    assert lib.pt_version() >= 100
+
+
+def test_workspace_queries_validate_descriptor(lib):
+    d = B.conv_desc(4, 16, 16, 16, 16, 3, 3, 1, 1)
+    assert B.conv_fwd_workspace_bytes(d) == 0
+    assert B.conv_bwd_data_workspace_bytes(d) >= 16 * 9 * 16 * 2
+    assert B.conv_bwd_weight_workspace_bytes(d) >= 0
+    bad = B.conv_desc(4, 16, 16, 16, 16, 3, 3, 1, 1)
+    bad.P = 15
+    with pytest.raises(B.PruneTrainError) as e:
+        B.conv_fwd_workspace_bytes(bad)
+    assert e.value.status == -2
+    bad = B.conv_desc(4, 16, 16, 16, 16, 3, 3, 1, 1, x_cpitch=8)
+    with pytest.raises(B.PruneTrainError):
+        B.conv_bwd_data_workspace_bytes(bad)
+    bad = B.conv_desc(4, 16, 16, 16, 16, 3, 3, 1, 1)
+    bad.struct_size = 12
+    with pytest.raises(B.PruneTrainError):
+        B.conv_bwd_weight_workspace_bytes(bad)
+    n = C.c_size_t(0)
+    assert lib.pt_conv_fwd_workspace_bytes(None, C.byref(n)) == -1
+    assert lib.pt_conv_fwd_workspace_bytes(C.byref(d), None) == -1
+    huge = B.conv_desc(1 << 14, 1 << 10, 1 << 10, 8, 8, 1, 1, 1, 0)
+    assert lib.pt_conv_fwd_workspace_bytes(C.byref(huge), C.byref(n)) == -4
+
+
+def test_null_and_shape_errors_are_reported_before_launch(lib):
+    d = B.conv_desc(1, 4, 4, 8, 8, 1, 1, 1, 0)
+    assert lib.pt_conv_fwd(C.byref(d), None, None, None, None, 0, None) == -1
+    assert lib.pt_conv_bwd_data(C.byref(d), None, None, None, None, 0, None) == -1
+    assert lib.pt_conv_bwd_weight(C.byref(d), None, None, None, None, 0, None) == -1
+    # workspace too small (non-null fake pointers are never dereferenced: validation fails first)
+    fake = C.c_void_p(256)
+    assert lib.pt_conv_bwd_data(C.byref(d), fake, fake, fake, fake, 16, None) == -3
+    assert lib.pt_group_norms(None, 1, 1, 1, 1, None, None, None, None, 0, None) == -1
+    assert lib.pt_group_norms(fake, 4, 1, 8, 4, fake, fake, None, fake, 1 << 20, None) == -2   # pitch < C
+    assert lib.pt_group_norms(fake, 4, 1, 8, 8, fake, fake, None, fake, 0, None) == -3
+    assert lib.pt_group_lasso_grad(fake, fake, fake, 0.1, 7, fake, 4, 1, 8, 8, None) == -4
+    assert lib.pt_zero_groups(None, 0, 0.0, None, None) == 0
+    assert lib.pt_zero_groups(None, 4, 0.0, None, None) == -1
+    assert lib.pt_zero_groups(None, -1, 0.0, None, None) == -2
+    assert lib.pt_reconcile_edge(None, 0, None, 0, 4, fake, None) == -2
+    assert lib.pt_compact_plan(None, 4, None, None, None) == -1
+    assert lib.pt_compact_weights(fake, 4, 1, 8, 8, None, 3, None, 8, fake, 8, None) == -2  # NULL idxK but Kp != K
+    assert lib.pt_compact_vector(fake, 3, fake, 4, fake, None) == -4
+    assert lib.pt_compact_vector(None, 4, None, 0, None, None) == 0
+    assert lib.pt_compact_nhwc(fake, 10, 8, 8, fake, 9, fake, 16, None) == -2               # Cp > C
+    assert lib.pt_compact_nhwc(None, 0, 8, 8, None, 4, None, 4, None) == 0

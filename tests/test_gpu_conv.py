@@ -1,0 +1,104 @@
+"""GPU parity: the three convolutions through the C ABI against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1901_09290_amd import workloads as wl
+from paper_1901_09290_amd.workloads import ConvSpec
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _spec(N, H, W, C, K, R, st, pad):
+    return ConvSpec("t", N, H, W, C, K, R, R, st, pad, None, None)
+
+
+def _check_full(spec, seed, xp=None, yp=None, wp=None):
+    from gpu_util import CONV_TOL, rel_err, run_conv_all
+    rng = np.random.Generator(np.random.PCG64(seed))
+    t = wl.conv_tensors(spec, rng)
+    y, dx, dw = run_conv_all(spec, t["x"], t["w"], t["dy"], xp, yp, wp)
+    s = oracle.shape_of(spec)
+    errs = (rel_err(y, oracle.conv_fwd(s, t["x"], t["w"])),
+            rel_err(dx, oracle.conv_bwd_data(s, t["dy"], t["w"])),
+            rel_err(dw, oracle.conv_bwd_weight(s, t["x"], t["dy"])))
+    assert max(errs) <= CONV_TOL, (spec, errs)
+    return errs
+
+
+def test_cfg1_single_layer():
+    from gpu_util import CONV_TOL, rel_err, run_conv_all
+    c = wl.cfg1(0)
+    spec = c["spec"]
+    y, dx, dw = run_conv_all(spec, c["x"], c["w"], c["dy"])
+    s = oracle.shape_of(spec)
+    ry, rdx, rdw = (oracle.conv_fwd(s, c["x"], c["w"]), oracle.conv_bwd_data(s, c["dy"], c["w"]),
+                    oracle.conv_bwd_weight(s, c["x"], c["dy"]))
+    assert rel_err(y, ry) <= CONV_TOL and rel_err(dx, rdx) <= CONV_TOL and rel_err(dw, rdw) <= CONV_TOL
+    # zeroed groups give exact zeros: outputs of zero filters, input gradients of zero input channels
+    assert np.all(y[..., c["zero_out"]] == 0.0)
+    assert np.all(dx[..., c["zero_in"]] == 0.0)
+
+
+SMALL = [
+    # N  H   W   C    K   R st pad    several tiles + ragged tails in every GEMM dimension
+    (2, 12, 12, 64, 64, 3, 1, 1),
+    (3, 9, 11, 24, 40, 3, 1, 1),
+    (2, 14, 14, 128, 96, 1, 1, 0),
+    (2, 15, 15, 40, 136, 3, 2, 1),
+    (2, 16, 16, 64, 128, 1, 2, 0),
+    (1, 37, 37, 8, 16, 7, 2, 3),
+    (5, 7, 7, 264, 72, 3, 1, 1),
+    (1, 20, 20, 16, 200, 1, 1, 0),
+    (1, 1, 1, 8, 8, 1, 1, 0),          # a single pixel
+    (2, 5, 5, 8, 8, 5, 1, 0),          # filter as large as the image
+    (1, 8, 8, 8, 8, 3, 3, 1),          # stride 3: parity classes with uneven tap counts
+]
+
+
+@pytest.mark.parametrize("case", SMALL)
+def test_small_layers_full_tensor(case):
+    _check_full(_spec(*case), seed=100 + sum(case))
+
+
+RAGGED = [
+    # logical C, K not multiples of 8; pitches padded to 8 (vector path with masked tails)
+    ((2, 10, 10, 37, 51, 3, 1, 1), True),
+    ((2, 12, 12, 203, 77, 1, 1, 0), True),
+    ((1, 9, 9, 19, 131, 3, 2, 1), True),
+    # same shapes stored dense: pitches are odd, element-wise path
+    ((2, 10, 10, 37, 51, 3, 1, 1), False),
+    ((1, 9, 9, 19, 131, 3, 2, 1), False),
+    ((2, 18, 18, 3, 16, 7, 2, 3), False),  # image-like 3-channel input
+]
+
+
+@pytest.mark.parametrize("case,padded", RAGGED)
+def test_ragged_channel_counts(case, padded):
+    from gpu_util import pitch8
+    spec = _spec(*case)
+    if padded:
+        _check_full(spec, 200 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C))
+    else:
+        _check_full(spec, 300 + sum(case))
+
+
+def test_results_are_run_to_run_identical():
+    from gpu_util import run_conv_all
+    spec = _spec(4, 14, 14, 72, 104, 3, 1, 1)
+    t = wl.conv_tensors(spec, np.random.Generator(np.random.PCG64(7)))
+    a = run_conv_all(spec, t["x"], t["w"], t["dy"])
+    b = run_conv_all(spec, t["x"], t["w"], t["dy"])
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+
+
+def test_cfg2_resnet32_distinct_layers_full_tensor():
+    """Every distinct layer shape of the ResNet-32-shaped stack at batch 128, whole tensors."""
+    layers, _ = wl.resnet32_layers(N=128)
+    rng_seed = 1
+    for i, (spec, _) in enumerate(wl.distinct_shapes(layers)):
+        errs = _check_full(spec, rng_seed * 1000 + i)
+        print(spec.name, spec.shape_key(), ["%.2e" % e for e in errs], flush=True)
