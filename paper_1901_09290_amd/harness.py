@@ -1,0 +1,218 @@
+"""Device-side harness: per-layer buffers in the layout the library consumes, and the call
+sequences of one training step (Alg. 1 lines ForwardProp .. BackProp, per conv layer) and of one
+reconfiguration sweep (PruneAndReconfigNetwork).  torch allocates and fills memory; every
+computation is a call into the C-ABI library through `binding`.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workloads as wl
+
+DEV = "cuda:0"
+
+
+def pitch8(n: int) -> int:
+    """Channel pitch used for every tensor: the next multiple of 8 elements (16 bytes of bf16)."""
+    return (n + 7) // 8 * 8
+
+
+def _to_dev_bf16(a: np.ndarray, pitch: int) -> torch.Tensor:
+    bits = wl.bf16_bits(a)
+    if pitch != a.shape[-1]:
+        full = np.zeros(a.shape[:-1] + (pitch,), dtype=np.uint16)
+        full[..., : a.shape[-1]] = bits
+        bits = full
+    return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def _to_dev_f32(a: np.ndarray, pitch: int) -> torch.Tensor:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if pitch != a.shape[-1]:
+        full = np.zeros(a.shape[:-1] + (pitch,), dtype=np.float32)
+        full[..., : a.shape[-1]] = a
+        a = full
+    return torch.from_numpy(a).to(DEV)
+
+
+class ConvLayer:
+    """All device buffers of one convolution layer's training step."""
+
+    def __init__(self, spec: wl.ConvSpec, gen: Optional[torch.Generator] = None,
+                 host: Optional[Dict[str, np.ndarray]] = None, w_master: Optional[np.ndarray] = None):
+        s = self.spec = spec
+        self.xp, self.yp, self.wp = pitch8(s.C), pitch8(s.K), pitch8(s.C)
+        self.desc = B.desc_of(s, self.xp, self.yp, self.wp)
+        self.RS = s.R * s.S
+        bf, f32 = torch.bfloat16, torch.float32
+        if host is not None:
+            self.x = _to_dev_bf16(host["x"], self.xp)
+            self.dy = _to_dev_bf16(host["dy"], self.yp)
+            wm = host["w"] if w_master is None else w_master
+            self.w_master = _to_dev_f32(wm, self.wp)
+        else:
+            assert gen is not None
+            self.x = torch.zeros((s.N, s.H, s.W, self.xp), dtype=bf, device=DEV)
+            self.x[..., : s.C].normal_(generator=gen)
+            self.dy = torch.zeros((s.N, s.P, s.Q, self.yp), dtype=bf, device=DEV)
+            self.dy[..., : s.K].normal_(generator=gen)
+            self.w_master = torch.zeros((s.K, s.R, s.S, self.wp), dtype=f32, device=DEV)
+            if w_master is not None:
+                self.w_master[..., : s.C] = torch.from_numpy(np.ascontiguousarray(w_master, dtype=np.float32)).to(DEV)
+            else:
+                self.w_master[..., : s.C].normal_(std=wl.he_std(s), generator=gen)
+        self.w_bf16 = torch.zeros((s.K, s.R, s.S, self.wp), dtype=bf, device=DEV)
+        self.y = torch.zeros((s.N, s.P, s.Q, self.yp), dtype=bf, device=DEV)
+        self.dx = None if s.first else torch.zeros((s.N, s.H, s.W, self.xp), dtype=bf, device=DEV)
+        self.dw = torch.zeros((s.K, s.R, s.S, self.wp), dtype=f32, device=DEV)
+        self.out_norm = torch.zeros(s.K, dtype=f32, device=DEV)
+        self.in_norm = torch.zeros(s.C, dtype=f32, device=DEV)
+        self.lasso_flags = B.LASSO_OUT | (0 if s.first else B.LASSO_IN)
+
+    def workspace_bytes(self) -> int:
+        d = self.desc
+        return max(B.conv_fwd_workspace_bytes(d), B.conv_bwd_data_workspace_bytes(d),
+                   B.conv_bwd_weight_workspace_bytes(d), B.group_norms_workspace_bytes(self.spec.K, self.RS, self.spec.C))
+
+    # --- the five calls of one training step on this layer, in Alg. 1 order -------------------- #
+    def norms(self, ws, shadow: bool = True):
+        s = self.spec
+        B.group_norms(self.w_master, s.K, self.RS, s.C, self.wp, self.out_norm, self.in_norm,
+                      self.w_bf16 if shadow else None, ws)
+
+    def fwd(self, ws):
+        B.conv_fwd(self.desc, self.x, self.w_bf16, self.y, ws)
+
+    def bwd_data(self, ws):
+        if self.dx is not None:
+            B.conv_bwd_data(self.desc, self.dy, self.w_bf16, self.dx, ws)
+
+    def bwd_weight(self, ws):
+        B.conv_bwd_weight(self.desc, self.x, self.dy, self.dw, ws)
+
+    def lasso(self, lam: float):
+        s = self.spec
+        B.group_lasso_grad(self.w_master, self.out_norm, self.in_norm, lam, self.lasso_flags, self.dw, s.K, self.RS,
+                           s.C, self.wp)
+
+    def train_step(self, ws, lam: float):
+        self.norms(ws)
+        self.fwd(ws)
+        self.bwd_data(ws)
+        self.bwd_weight(ws)
+        self.lasso(lam)
+
+    @property
+    def step_flops(self) -> int:
+        return self.spec.flops * (2 if self.spec.first else 3)
+
+
+def make_workspace(layers: Sequence[ConvLayer]) -> torch.Tensor:
+    n = max([l.workspace_bytes() for l in layers] + [256])
+    return torch.empty(n, dtype=torch.uint8, device=DEV)
+
+
+def build_network(specs: Sequence[wl.ConvSpec], seed: int) -> List[ConvLayer]:
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    return [ConvLayer(s, gen=gen) for s in specs]
+
+
+def train_step(layers: Sequence[ConvLayer], ws: torch.Tensor, lam: float) -> None:
+    for l in layers:
+        l.train_step(ws, lam)
+
+
+# ----------------------------------------------------------------------------------------------- #
+# reconfiguration sweep
+# ----------------------------------------------------------------------------------------------- #
+class ReconfigModel:
+    """Weights (+ momentum), per-channel normalisation vectors and one saved input activation per
+    layer, plus everything the sweep writes: masks, keep masks, index lists and compacted copies."""
+
+    def __init__(self, specs: Sequence[wl.ConvSpec], edges: Sequence[wl.Edge], weights: Sequence[np.ndarray],
+                 seed: int, with_activations: bool = True):
+        self.specs, self.edges = list(specs), list(edges)
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(seed)
+        f32, bf, u8, i32 = torch.float32, torch.bfloat16, torch.uint8, torch.int32
+        self.w, self.mom, self.bn, self.act = [], [], [], []
+        self.on, self.inn, self.zo, self.zi = [], [], [], []
+        for s, w in zip(self.specs, weights):
+            wp = pitch8(s.C)
+            self.w.append(_to_dev_f32(w, wp))
+            m = torch.zeros_like(self.w[-1])
+            m[..., : s.C].normal_(generator=gen)
+            self.mom.append(m)
+            self.bn.append([torch.randn(s.K, generator=gen, device=DEV, dtype=f32) for _ in range(4)])
+            if with_activations:
+                a = torch.zeros((s.N, s.H, s.W, pitch8(s.C)), dtype=bf, device=DEV)
+                a[..., : s.C].normal_(generator=gen)
+                self.act.append(a)
+            self.on.append(torch.zeros(s.K, dtype=f32, device=DEV))
+            self.inn.append(torch.zeros(s.C, dtype=f32, device=DEV))
+            self.zo.append(torch.zeros(s.K, dtype=u8, device=DEV))
+            self.zi.append(torch.zeros(s.C, dtype=u8, device=DEV))
+        self.keep = [torch.zeros(e.n, dtype=u8, device=DEV) for e in self.edges]
+        self.idx = [torch.zeros(e.n, dtype=i32, device=DEV) for e in self.edges]
+        self.counts = torch.zeros(len(self.edges), dtype=i32, device=DEV)
+        self.ws = torch.empty(max([B.group_norms_workspace_bytes(s.K, s.R * s.S, s.C) for s in self.specs] + [256]),
+                              dtype=torch.uint8, device=DEV)
+        # outputs sized for "nothing pruned"; the sweep writes the compacted tensors at their own pitch
+        self.w_out = [torch.zeros_like(t) for t in self.w]
+        self.mom_out = [torch.zeros_like(t) for t in self.mom]
+        self.bn_out = [[torch.zeros_like(v) for v in vs] for vs in self.bn]
+        self.act_out = [torch.zeros_like(t) for t in self.act]
+        self.new_counts: Optional[np.ndarray] = None
+
+    def detect(self, thr: float) -> None:
+        """group_norms + zero_groups per layer, reconcile + plan per edge (all asynchronous)."""
+        for i, s in enumerate(self.specs):
+            B.group_norms(self.w[i], s.K, s.R * s.S, s.C, pitch8(s.C), self.on[i], self.inn[i], None, self.ws)
+            B.zero_groups(self.on[i], s.K, thr, self.zo[i])
+            B.zero_groups(self.inn[i], s.C, thr, self.zi[i])
+        for e, edge in enumerate(self.edges):
+            B.reconcile_edge([self.zo[i] for i in edge.producers], [self.zi[i] for i in edge.consumers], edge.n,
+                             self.keep[e])
+            B.compact_plan(self.keep[e], edge.n, self.idx[e], self.counts[e:e + 1])
+
+    def compact(self) -> None:
+        """Reads the survivor counts (one synchronising copy), then gathers every tensor."""
+        cnt = self.counts.cpu().numpy()
+        self.new_counts = cnt
+        for i, s in enumerate(self.specs):
+            ik = self.idx[s.out_edge] if s.out_edge is not None else None
+            ic = self.idx[s.in_edge] if s.in_edge is not None else None
+            Kp = int(cnt[s.out_edge]) if s.out_edge is not None else s.K
+            Cp = int(cnt[s.in_edge]) if s.in_edge is not None else s.C
+            RS, wp, op = s.R * s.S, pitch8(s.C), pitch8(Cp)
+            B.compact_weights(self.w[i], s.K, RS, s.C, wp, ik, Kp, ic, Cp, self.w_out[i], op)
+            B.compact_weights(self.mom[i], s.K, RS, s.C, wp, ik, Kp, ic, Cp, self.mom_out[i], op)
+            if ik is not None:
+                for v, o in zip(self.bn[i], self.bn_out[i]):
+                    B.compact_vector(v, 4, ik, Kp, o)
+            if self.act and ic is not None:
+                B.compact_nhwc(self.act[i], s.N * s.H * s.W, s.C, wp, ic, Cp, self.act_out[i], op)
+
+    def sweep(self, thr: float) -> None:
+        self.detect(thr)
+        self.compact()
+
+    def algorithmic_bytes(self) -> Dict[str, int]:
+        """Bytes each kernel family must move for the last sweep (survivors read once, written once)."""
+        cnt = self.new_counts
+        out = dict(group_norms=0, compact_weights=0, compact_nhwc=0, compact_vector=0)
+        for s in self.specs:
+            Kp = int(cnt[s.out_edge]) if s.out_edge is not None else s.K
+            Cp = int(cnt[s.in_edge]) if s.in_edge is not None else s.C
+            out["group_norms"] += 4 * s.params
+            out["compact_weights"] += 2 * 2 * 4 * Kp * s.R * s.S * Cp          # weights + momentum, read + write
+            if s.out_edge is not None:
+                out["compact_vector"] += 4 * 2 * 4 * Kp
+            if self.act and s.in_edge is not None:
+                out["compact_nhwc"] += 2 * 2 * s.N * s.H * s.W * Cp
+        return out
