@@ -31,6 +31,12 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     if verbose and err.strip():
         print(err)
+    # every kernel the host code launches must have been emitted: an unresolved pt:: symbol means a
+    # kernel template silently failed to instantiate
+    nm = subprocess.run(["nm", "-C", "--undefined-only", SO], capture_output=True, text=True).stdout
+    missing = [l.strip() for l in nm.splitlines() if "pt::" in l]
+    if missing:
+        raise RuntimeError("unresolved library symbols:\n" + "\n".join(missing))
     return SO
 
 

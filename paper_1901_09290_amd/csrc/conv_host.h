@@ -1,0 +1,158 @@
+// Host-side planning of the convolution launches: descriptor checks, kernel argument construction,
+// tile-configuration choice and the split plan of the weight gradient.
+#pragma once
+
+#include "conv_kernels.h"
+
+namespace pt {
+
+inline int32_t check_desc(const pt_conv_desc* d) {
+    if (!d) return PT_ERR_NULL;
+    if (d->struct_size != sizeof(pt_conv_desc)) return PT_ERR_SHAPE;
+    if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0) return PT_ERR_SHAPE;
+    if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return PT_ERR_SHAPE;
+    if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return PT_ERR_SHAPE;
+    if (d->P != (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1) return PT_ERR_SHAPE;
+    if (d->Q != (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1) return PT_ERR_SHAPE;
+    if (d->x_cpitch < d->C || d->y_cpitch < d->K || d->w_cpitch < d->C) return PT_ERR_SHAPE;
+    // limits of the 16/32-bit pixel arithmetic inside the kernels
+    if (d->H > 16384 || d->W > 16384 || d->R > 255 || d->S > 255 || d->pad_h > 255 || d->pad_w > 255 ||
+        d->stride_h > 255 || d->stride_w > 255)
+        return PT_ERR_UNSUPPORTED;
+    const int64_t in_pix = (int64_t)d->N * d->H * d->W, out_pix = (int64_t)d->N * d->P * d->Q;
+    if (in_pix >= (1ll << 30) || out_pix >= (1ll << 30)) return PT_ERR_UNSUPPORTED;
+    const int64_t big = d->H > d->W ? d->H : d->W;  // divisors of the in-kernel pixel decompositions
+    if (in_pix * big >= (1ll << 32) || out_pix * big >= (1ll << 32)) return PT_ERR_UNSUPPORTED;
+    // 32-bit element offsets into every tensor
+    if (in_pix * d->x_cpitch >= (1ll << 31) || out_pix * d->y_cpitch >= (1ll << 31)) return PT_ERR_UNSUPPORTED;
+    if ((int64_t)d->K * d->R * d->S * d->w_cpitch >= (1ll << 31)) return PT_ERR_UNSUPPORTED;
+    if ((int64_t)d->C * d->R * d->S * round_up(d->K, 8) >= (1ll << 31)) return PT_ERR_UNSUPPORTED;
+    if ((int64_t)d->R * d->S * round_up(d->C, 8) >= (1ll << 30)) return PT_ERR_UNSUPPORTED;
+    if ((int64_t)d->R * d->S * round_up(d->K, 8) >= (1ll << 30)) return PT_ERR_UNSUPPORTED;
+    return PT_OK;
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+inline IgemmArgs make_fwd_args(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, uint16_t* y) {
+    IgemmArgs a{};
+    a.A = x; a.B = w; a.D = y;
+    a.M = d->N * d->P * d->Q;
+    a.gW = make_fastdiv((uint32_t)d->Q); a.gH = make_fastdiv((uint32_t)d->P);
+    a.srcH = d->H; a.srcW = d->W; a.apitch = d->x_cpitch;
+    a.h_mul = d->stride_h; a.h_add = -d->pad_h; a.w_mul = d->stride_w; a.w_add = -d->pad_w;
+    a.tr_step = 1; a.ts_step = 1; a.TR = d->R; a.TS = d->S;
+    a.Cred = d->C; a.CredP = (int)round_up(d->C, 8);
+    a.b_tap0 = 0; a.b_tr_stride = d->S; a.b_ts_stride = 1; a.b_taps = d->R * d->S;
+    a.bpitch = d->w_cpitch; a.Nout = d->K;
+    a.DH = d->P; a.DW = d->Q; a.d_hmul = 1; a.d_hadd = 0; a.d_wmul = 1; a.d_wadd = 0; a.dpitch = d->y_cpitch;
+    a.d_linear = 1;
+    a.d_vec = (d->y_cpitch % 4 == 0) && (((uintptr_t)y & 7) == 0);
+    a.d_vec16 = (d->y_cpitch % 8 == 0) && aligned16(y);
+    return a;
+}
+
+// One stride-parity class (ca, cb) of input pixels of the input-gradient problem: the pixels
+// h = ca + stride_h*i, w = cb + stride_w*j, reached only by taps r = r0 + stride_h*jr, s = s0 + stride_w*js.
+struct BwdClass {
+    int gH, gW, r0, s0, TR, TS;
+};
+
+inline BwdClass bwd_data_class(const pt_conv_desc* d, int ca, int cb) {
+    BwdClass c;
+    c.gH = ca < d->H ? (d->H - ca + d->stride_h - 1) / d->stride_h : 0;
+    c.gW = cb < d->W ? (d->W - cb + d->stride_w - 1) / d->stride_w : 0;
+    c.r0 = (ca + d->pad_h) % d->stride_h;
+    c.s0 = (cb + d->pad_w) % d->stride_w;
+    c.TR = c.r0 < d->R ? (d->R - c.r0 + d->stride_h - 1) / d->stride_h : 0;
+    c.TS = c.s0 < d->S ? (d->S - c.s0 + d->stride_w - 1) / d->stride_w : 0;
+    return c;
+}
+
+inline IgemmArgs make_bwd_data_args(const pt_conv_desc* d, const BwdClass& c, int ca, int cb, const uint16_t* dy,
+                                    const uint16_t* wt, uint16_t* dx) {
+    const int kpitch = (int)round_up(d->K, 8);
+    IgemmArgs a{};
+    a.A = dy; a.B = wt; a.D = dx;
+    a.M = d->N * c.gH * c.gW;
+    a.gW = make_fastdiv((uint32_t)c.gW); a.gH = make_fastdiv((uint32_t)c.gH);
+    a.srcH = d->P; a.srcW = d->Q; a.apitch = d->y_cpitch;
+    a.h_mul = 1; a.h_add = (ca + d->pad_h - c.r0) / d->stride_h;
+    a.w_mul = 1; a.w_add = (cb + d->pad_w - c.s0) / d->stride_w;
+    a.tr_step = -1; a.ts_step = -1; a.TR = c.TR; a.TS = c.TS;
+    a.Cred = d->K; a.CredP = kpitch;
+    a.b_tap0 = c.r0 * d->S + c.s0; a.b_tr_stride = d->stride_h * d->S; a.b_ts_stride = d->stride_w;
+    a.b_taps = d->R * d->S; a.bpitch = kpitch; a.Nout = d->C;
+    a.DH = d->H; a.DW = d->W; a.d_hmul = d->stride_h; a.d_hadd = ca; a.d_wmul = d->stride_w; a.d_wadd = cb;
+    a.dpitch = d->x_cpitch;
+    a.d_linear = (d->stride_h == 1 && d->stride_w == 1);
+    a.d_vec = (d->x_cpitch % 4 == 0) && (((uintptr_t)dx & 7) == 0);
+    a.d_vec16 = (d->x_cpitch % 8 == 0) && aligned16(dx);
+    return a;
+}
+
+// Kernel and tile configuration.  `vec`: all operand rows are 16-byte aligned (pitches are multiples of 8
+// elements) - then the direct global->LDS kernel is used, with a tall pixel tile for narrow outputs.
+// Unaligned pitches, and filters with more than 32 taps per launch (the direct kernel keeps one validity
+// bit per tap in a 32-bit mask), take the register-staged kernel.
+inline hipError_t launch_igemm(IgemmArgs& a, bool vec, hipStream_t st) {
+    if (!vec) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, false>(a, st);
+    if (a.TR * a.TS > 32) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, true>(a, st);
+    if (a.Nout <= 64) return launch_igemm_dl_cfg<256, 64, 4, 2, 3>(a, st);
+    return launch_igemm_dl_cfg<256, 128, 4, 2, 3>(a, st);
+}
+
+inline size_t bwd_data_ws(const pt_conv_desc* d) {
+    return (size_t)round_up((int64_t)d->C * d->R * d->S * round_up(d->K, 8) * 2, 256);
+}
+
+struct WgradPlan {
+    int splits, iters_total, iters_per_split, tiles_m, tiles_n, CP, Mtot;
+    size_t ws_bytes;
+};
+constexpr int kWgBM = 128, kWgBN = 128, kWgBK = 32;
+
+inline WgradPlan plan_wgrad(const pt_conv_desc* d) {
+    WgradPlan p;
+    p.CP = (int)round_up(d->C, 8);
+    p.Mtot = d->R * d->S * p.CP;
+    p.tiles_m = (int)ceil_div(p.Mtot, kWgBM);
+    p.tiles_n = (int)ceil_div(d->K, kWgBN);
+    const int64_t pixels = (int64_t)d->N * d->P * d->Q;
+    p.iters_total = (int)ceil_div(pixels, kWgBK);
+    const int tiles = p.tiles_m * p.tiles_n;
+    int64_t splits = ceil_div(1024, tiles);
+    const int64_t max_splits = p.iters_total / 8 > 0 ? p.iters_total / 8 : 1;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    p.iters_per_split = (int)ceil_div(p.iters_total, splits);
+    p.splits = (int)ceil_div(p.iters_total, p.iters_per_split);
+    p.ws_bytes = p.splits > 1 ? (size_t)round_up((int64_t)p.splits * d->K * p.Mtot * 4, 256) : 0;
+    return p;
+}
+
+inline WgradArgs make_wgrad_args(const pt_conv_desc* d, const WgradPlan& p, const uint16_t* x, const uint16_t* dy,
+                                 float* dw, void* ws) {
+    WgradArgs a{};
+    a.X = x; a.DY = dy;
+    a.pixels = d->N * d->P * d->Q;
+    a.Q = make_fastdiv((uint32_t)d->Q); a.P = make_fastdiv((uint32_t)d->P);
+    a.H = d->H; a.W = d->W; a.xpitch = d->x_cpitch; a.ypitch = d->y_cpitch;
+    a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
+    a.S = d->S; a.RS = d->R * d->S; a.C = d->C; a.CP = p.CP; a.Mtot = p.Mtot; a.K = d->K;
+    a.tiles_n = p.tiles_n;
+    a.iters_total = p.iters_total; a.iters_per_split = p.iters_per_split; a.splits = p.splits;
+    a.wpitch = d->w_cpitch;
+    a.direct = p.splits == 1;
+    a.OUT = a.direct ? dw : (float*)ws;
+    a.out_row_pitch = p.Mtot;
+    a.o_vec = (d->w_cpitch % 4 == 0) && aligned16(dw);
+    return a;
+}
+
+inline hipError_t launch_wgrad(WgradArgs& a, const WgradPlan&, bool vec, hipStream_t st) {
+    if (!vec) return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2, false>(a, st);
+    return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2>(a, st);
+}
+
+}  // namespace pt

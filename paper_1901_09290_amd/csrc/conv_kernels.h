@@ -1,0 +1,819 @@
+// Device kernels and launch templates of the implicit-GEMM convolutions (gfx950).
+// See conv.hip for the map from the three convolution calls onto these kernels.
+#pragma once
+
+#include <type_traits>
+
+#include "common.h"
+
+namespace pt {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// Raw 8 x bf16 load from base + off (elements).  VEC: one 16-byte load (off*2 is 16-byte aligned and all
+// 16 bytes are readable).  Otherwise eight 2-byte loads, where element e >= nvalid re-reads element 0 so
+// that nothing beyond the row's logical extent is touched.  No branches: callers clamp `off` to a
+// readable location for rows that are out of range and zero the result with mask8().
+template <bool VEC>
+__device__ __forceinline__ uint4 ldg8(const uint16_t* __restrict__ base, uint32_t off, int nvalid) {
+    if constexpr (VEC) {
+        return *reinterpret_cast<const uint4*>(base + off);
+    } else {
+        uint32_t d[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = base[off + (2 * i < nvalid ? 2 * i : 0)];
+            const uint32_t hi = base[off + (2 * i + 1 < nvalid ? 2 * i + 1 : 0)];
+            d[i] = lo | (hi << 16);
+        }
+        return make_uint4(d[0], d[1], d[2], d[3]);
+    }
+}
+
+// Per-dword masks that keep elements [0, nvalid) of an 8 x bf16 vector.
+struct Mask8 {
+    uint32_t m[4];
+};
+__device__ __forceinline__ Mask8 make_mask8(int nvalid) {
+    Mask8 k;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) k.m[i] = nvalid >= 2 * i + 2 ? 0xffffffffu : (nvalid == 2 * i + 1 ? 0xffffu : 0u);
+    return k;
+}
+__device__ __forceinline__ uint4 mask8(uint4 v, bool ok, const Mask8& k) {
+    v.x = ok ? (v.x & k.m[0]) : 0u;
+    v.y = ok ? (v.y & k.m[1]) : 0u;
+    v.z = ok ? (v.z & k.m[2]) : 0u;
+    v.w = ok ? (v.w & k.m[3]) : 0u;
+    return v;
+}
+
+// XCD-aware block remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; give
+// each XCD a contiguous range of logical tiles so tiles that share operands share an L2.
+__device__ __forceinline__ int xcd_remap(int bid, int nb) {
+    const int xcd = bid & 7, q = bid >> 3;
+    const int per = nb >> 3, rem = nb & 7;
+    return xcd * per + min(xcd, rem) + q;
+}
+
+// floor(m / d) through a host-made magic number (exact for m * d < 2^32); d == 1 has magic 0.
+struct FastDiv {
+    uint32_t d, magic;
+};
+inline FastDiv make_fastdiv(uint32_t d) { return FastDiv{d, d == 1 ? 0u : make_magic(d)}; }
+__device__ __forceinline__ uint32_t fdiv(uint32_t m, FastDiv f) { return f.d == 1 ? m : __umulhi(m, f.magic); }
+
+// ------------------------------------------------------------------------------------------- //
+// forward / input-gradient implicit GEMM
+// ------------------------------------------------------------------------------------------- //
+struct IgemmArgs {
+    const uint16_t* A;  // gathered activations (x or dy)
+    const uint16_t* B;  // weights, [Nout][b_taps][bpitch], reduction channel innermost
+    uint16_t* D;        // output activations
+    int M;              // output pixels of this launch = images * gH * gW
+    FastDiv gW, gH;     // output pixel grid per image (of this launch): width, height
+    int srcH, srcW, apitch;
+    int h_mul, h_add, w_mul, w_add;  // source coordinate of tap (0,0) for grid point (i,j)
+    int tr_step, ts_step;            // source coordinate step per tap index
+    int TR, TS;                      // taps of this launch
+    int Cred, CredP;                 // reduction channels, and rounded up to 8
+    int b_tap0, b_tr_stride, b_ts_stride, b_taps;
+    int bpitch, Nout;
+    int DH, DW, d_hmul, d_hadd, d_wmul, d_wadd, dpitch;  // destination pixel = (i*d_hmul+d_hadd, j*d_wmul+d_wadd)
+    int d_linear;                                        // destination pixel index == m
+    int nk;                                              // reduction steps of BK
+    int tiles_n;
+    int d_vec;    // 8-byte stores allowed (pitch % 4 == 0, base 8-byte aligned)
+    int d_vec16;  // 16-byte stores allowed (pitch % 8 == 0, base 16-byte aligned)
+};
+
+// VEC: every operand row is 16-byte aligned (pitches are multiples of 8 elements).
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, int MINB, bool VEC>
+__global__ __launch_bounds__(64 * WGM * WGN, MINB) void k_igemm(const IgemmArgs a) {
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int LDK = BK + 8;  // LDS row pitch in elements (16-byte pad: conflict-free 16-byte reads)
+    constexpr int KV = BK / 8;
+    constexpr int RPP = NT / KV;
+    constexpr int AP = BM / RPP, BP = BN / RPP;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int STAGE_ELEMS = (BM + BN) * LDK;
+    static_assert(AP >= 1 && BP >= 1 && TM >= 1 && TN >= 1 && BM % RPP == 0 && BN % RPP == 0, "tile config");
+    static_assert(STAGES == 1 || STAGES == 2, "stages");
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int n0 = (tile % a.tiles_n) * BN;
+    const int m0 = (tile / a.tiles_n) * BM;
+
+    // ---- loader state -------------------------------------------------------------------------
+    const int kv = tid % KV, lrow = tid / KV;
+    int c0 = kv * 8, tr = 0, ts = 0;
+    while (c0 >= a.CredP) {
+        c0 -= a.CredP;
+        if (++ts == a.TS) { ts = 0; ++tr; }
+    }
+    int a_hw[AP];    // (h0 << 16) | (w0 & 0xffff): source coordinate of tap (0,0)
+    int a_poff[AP];  // linear source pixel of tap (0,0)
+#pragma unroll
+    for (int i = 0; i < AP; ++i) {
+        const int m = m0 + lrow + i * RPP;
+        int h0 = -30000, w0 = 0, poff = 0;
+        if (m < a.M) {
+            const uint32_t row = fdiv((uint32_t)m, a.gW), gj = m - row * a.gW.d;
+            const uint32_t n = fdiv(row, a.gH), gi = row - n * a.gH.d;
+            h0 = (int)gi * a.h_mul + a.h_add;
+            w0 = (int)gj * a.w_mul + a.w_add;
+            poff = ((int)n * a.srcH + h0) * a.srcW + w0;
+        }
+        a_hw[i] = (h0 << 16) | (w0 & 0xffff);
+        a_poff[i] = poff;
+    }
+    const uint32_t b_rowlen = (uint32_t)a.b_taps * a.bpitch;
+
+    uint4 ra[AP], rb[BP];
+    bool oka[AP], okb[BP];
+    Mask8 kmask;
+    // issue the global loads of the next reduction step (raw, unmasked)
+    auto gload = [&]() {
+        const bool kok = tr < a.TR;
+        const int nvalid = kok ? a.Cred - c0 : 0;
+        kmask = make_mask8(nvalid);
+        const int dh = tr * a.tr_step, dw = ts * a.ts_step;
+        const int dpix = dh * a.srcW + dw;
+#pragma unroll
+        for (int i = 0; i < AP; ++i) {
+            const int ih = (a_hw[i] >> 16) + dh, iw = (int)(short)(a_hw[i] & 0xffff) + dw;
+            oka[i] = kok && (unsigned)ih < (unsigned)a.srcH && (unsigned)iw < (unsigned)a.srcW;
+            const uint32_t off = (uint32_t)(a_poff[i] + dpix) * (uint32_t)a.apitch + (uint32_t)c0;
+            ra[i] = ldg8<VEC>(a.A, oka[i] ? off : 0u, nvalid);
+        }
+        const uint32_t tapoff = (uint32_t)(a.b_tap0 + tr * a.b_tr_stride + ts * a.b_ts_stride) * (uint32_t)a.bpitch + c0;
+#pragma unroll
+        for (int j = 0; j < BP; ++j) {
+            const int nrow = n0 + lrow + j * RPP;
+            okb[j] = kok && nrow < a.Nout;
+            rb[j] = ldg8<VEC>(a.B, okb[j] ? (uint32_t)nrow * b_rowlen + tapoff : 0u, nvalid);
+        }
+        c0 += BK;
+        while (c0 >= a.CredP && tr < a.TR) {
+            c0 -= a.CredP;
+            if (++ts == a.TS) { ts = 0; ++tr; }
+        }
+    };
+    auto sstore = [&](int buf) {
+        uint16_t* sA = smem + buf * STAGE_ELEMS;
+        uint16_t* sB = sA + BM * LDK;
+#pragma unroll
+        for (int i = 0; i < AP; ++i)
+            *reinterpret_cast<uint4*>(&sA[(lrow + i * RPP) * LDK + kv * 8]) = mask8(ra[i], oka[i], kmask);
+#pragma unroll
+        for (int j = 0; j < BP; ++j)
+            *reinterpret_cast<uint4*>(&sB[(lrow + j * RPP) * LDK + kv * 8]) = mask8(rb[j], okb[j], kmask);
+    };
+
+    // ---- MFMA state ---------------------------------------------------------------------------
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int l32 = lane & 31, lk = (lane >> 5) * 8;
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tn][tm][v] = 0.f;
+    bool n_live[TN], m_live[TM];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) n_live[tn] = n0 + wn * WTN + tn * 32 < a.Nout;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) m_live[tm] = m0 + wm * WTM + tm * 32 < a.M;
+
+    bool all_live = true;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) all_live = all_live && n_live[tn];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) all_live = all_live && m_live[tm];
+
+    // CHECK = false: every 32x32 block of this wave is inside the output (no per-block tests)
+    auto compute = [&](int buf, auto check_tag) {
+        constexpr bool CHECK = decltype(check_tag)::value;
+        const uint16_t* sA = smem + buf * STAGE_ELEMS;
+        const uint16_t* sB = sA + BM * LDK;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fw[TN], fp[TM];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                fw[tn] = *reinterpret_cast<const bf16x8*>(&sB[(wn * WTN + tn * 32 + l32) * LDK + ks * 16 + lk]);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                fp[tm] = *reinterpret_cast<const bf16x8*>(&sA[(wm * WTM + tm * 32 + l32) * LDK + ks * 16 + lk]);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    if (!CHECK || (n_live[tn] && m_live[tm]))
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[tn], fp[tm], acc[tn][tm], 0, 0, 0);
+        }
+    };
+    // software pipeline over the reduction steps; the tile-edge test is hoisted out of the loop
+    auto main_loop = [&](auto check_tag) {
+        if constexpr (STAGES == 2) {
+            for (int kt = 0; kt < a.nk; ++kt) {
+                const int buf = kt & 1;
+                if (kt + 1 < a.nk) gload();
+                compute(buf, check_tag);
+                if (kt + 1 < a.nk) sstore(buf ^ 1);
+                __syncthreads();
+            }
+        } else {
+            for (int kt = 0; kt < a.nk; ++kt) {
+                if (kt + 1 < a.nk) gload();
+                compute(0, check_tag);
+                __syncthreads();
+                if (kt + 1 < a.nk) {
+                    sstore(0);
+                    __syncthreads();
+                }
+            }
+        }
+    };
+    gload();
+    sstore(0);
+    __syncthreads();
+    if (all_live) main_loop(std::false_type{});
+    else main_loop(std::true_type{});
+
+    // ---- epilogue: lane holds pixel (column) l32, channels 8g + 4*(lane/32) + {0..3} of each block --
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int m = m0 + wm * WTM + tm * 32 + l32;
+        if (m >= a.M) continue;
+        int64_t dpix;
+        if (a.d_linear) {
+            dpix = (int64_t)m * a.dpitch;
+        } else {
+            const uint32_t row = fdiv((uint32_t)m, a.gW), gj = m - row * a.gW.d;
+            const uint32_t n = fdiv(row, a.gH), gi = row - n * a.gH.d;
+            dpix = (((int64_t)n * a.DH + (int)gi * a.d_hmul + a.d_hadd) * a.DW + (int)gj * a.d_wmul + a.d_wadd) * a.dpitch;
+        }
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int ch = n0 + wn * WTN + tn * 32 + 8 * g + (lane >> 5) * 4;
+                if (ch >= a.Nout) continue;
+                const float v0 = acc[tn][tm][4 * g + 0], v1 = acc[tn][tm][4 * g + 1];
+                const float v2 = acc[tn][tm][4 * g + 2], v3 = acc[tn][tm][4 * g + 3];
+                uint16_t* dst = a.D + dpix + ch;
+                if (a.d_vec && ch + 3 < a.Nout) {
+                    uint2 o;
+                    o.x = pack_bf16x2(v0, v1);
+                    o.y = pack_bf16x2(v2, v3);
+                    *reinterpret_cast<uint2*>(dst) = o;
+                } else {
+                    dst[0] = f32_to_bf16(v0);
+                    if (ch + 1 < a.Nout) dst[1] = f32_to_bf16(v1);
+                    if (ch + 2 < a.Nout) dst[2] = f32_to_bf16(v2);
+                    if (ch + 3 < a.Nout) dst[3] = f32_to_bf16(v3);
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, int MINB, bool VEC = true>
+inline hipError_t launch_igemm_cfg(IgemmArgs& a, hipStream_t st) {
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr size_t lds = (size_t)STAGES * (BM + BN) * (BK + 8) * 2;
+    auto kern = k_igemm<BM, BN, BK, WGM, WGN, STAGES, MINB, VEC>;
+    static bool attr_set = false;  // one-time opt-in to more than 64 KiB of dynamic LDS
+    if (lds > 65536 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (int)ceil_div(a.M, BM);
+    a.tiles_n = (int)ceil_div(a.Nout, BN);
+    a.nk = (int)ceil_div((int64_t)a.TR * a.TS * a.CredP, BK);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * a.tiles_n), dim3(NT), lds, st, a);
+    return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------------- //
+// forward / input-gradient implicit GEMM with direct global->LDS loads (vector path)
+// ------------------------------------------------------------------------------------------- //
+// Same problem mapping as k_igemm, different data movement: 16-byte global loads land in LDS without
+// passing through registers (global_load_lds_dwordx4), so several reduction steps can be in flight
+// per workgroup at no register cost.  A wave-level load fills 1 KiB of LDS contiguously (lane l ->
+// bytes [16l, 16l+16)), i.e. 8 tile rows of BK = 64 elements; rows are unpadded and the eight 16-byte
+// chunks of a row are XOR-swizzled with ((row >> 1) & 7) so that the MFMA operand reads (16 consecutive
+// rows, same logical chunk) fall into 16 different bank groups.  The swizzle is applied on the global
+// side: the lane that owns physical chunk p of a row fetches logical chunk p ^ swz(row).
+// Taps outside the image and chunks past the channel count fetch from a 16-byte zero page; a ragged
+// channel tail inside a chunk is zeroed in LDS by the lane that loaded it, after its data has landed
+// and before the workgroup barrier.  RAGGED = the channel count is not a multiple of 64.
+__device__ __attribute__((aligned(16))) uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* glb_void_ptr;
+
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would wait for every
+// outstanding global->LDS load, which is exactly what the software pipeline must not do.  Callers
+// wait explicitly (vmcnt for landed DMA data, lgkmcnt for their own LDS writes) before calling.
+__device__ __forceinline__ void barrier_nofence() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xc07f); }  // lgkmcnt(0) only
+
+// Per-lane choice between two global addresses, kept opaque so that it stays one load instruction.
+__device__ __forceinline__ glb_void_ptr pick_ptr(bool ok, const uint16_t* p, const uint16_t* z) {
+    uint64_t v = ok ? (uint64_t)(uintptr_t)p : (uint64_t)(uintptr_t)z;
+    asm volatile("" : "+v"(v));
+    return (glb_void_ptr)(uintptr_t)v;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    // s_waitcnt immediate: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14 ; only vmcnt constrained
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED>
+__global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
+    constexpr int NW = WGM * WGN, NT = 64 * NW, BK = 64;
+    constexpr int GA = BM / 8, GB = BN / 8;    // 8-row groups = wave-level loads per stage
+    constexpr int LA = GA / NW, LB = GB / NW;  // loads per lane per stage
+    constexpr int LPT = LA + LB;
+    constexpr int STAGE_BYTES = (BM + BN) * 128;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    static_assert(NW % 2 == 0 && GA % NW == 0 && GB % NW == 0 && LA >= 1 && LB >= 1 && TM >= 1 && TN >= 1, "tile config");
+    static_assert(STAGES >= 2 && (STAGES - 2) * LPT < 64, "stages");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_b[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int n0 = (tile % a.tiles_n) * BN;
+    const int m0 = (tile / a.tiles_n) * BM;
+
+    // A reduction step is (filter tap, block of 64 reduction channels): the same for every lane, so the
+    // tap offsets and the channel base live in scalar registers.  With a ragged channel count the last
+    // block of each tap is short: only ceil(rest/16) MFMA k-steps are executed for it.
+    const int lrow = lane >> 3;                                      // row inside an 8-row group
+    const int kv = (lane & 7) ^ ((((wave & 1) << 2) | (lane >> 4)));  // logical 8-element chunk this lane fetches
+    const int kvoff = kv * 8;
+
+    // per-lane row constants: element offset of tap (0,0) + chunk, and a bit per tap: tap inside the image.
+    // Rows past the end of the problem are clamped to the last row: their results are never stored.
+    uint32_t a_off[LA], a_mask[LA];
+#pragma unroll
+    for (int j = 0; j < LA; ++j) {
+        const int m = min(m0 + (wave + NW * j) * 8 + lrow, a.M - 1);
+        const uint32_t row = fdiv((uint32_t)m, a.gW), gj = m - row * a.gW.d;
+        const uint32_t n = fdiv(row, a.gH), gi = row - n * a.gH.d;
+        const int h0 = (int)gi * a.h_mul + a.h_add, w0 = (int)gj * a.w_mul + a.w_add;
+        a_off[j] = (uint32_t)(((int)n * a.srcH + h0) * a.srcW + w0) * (uint32_t)a.apitch + (uint32_t)kvoff;
+        uint32_t mask = 0;
+        for (int r = 0; r < a.TR; ++r) {
+            const bool hok = (unsigned)(h0 + r * a.tr_step) < (unsigned)a.srcH;
+            for (int t = 0; t < a.TS; ++t) {
+                const bool ok = hok && (unsigned)(w0 + t * a.ts_step) < (unsigned)a.srcW;
+                mask |= (ok ? 1u : 0u) << (r * a.TS + t);
+            }
+        }
+        a_mask[j] = mask;
+    }
+    const uint32_t b_rowlen = (uint32_t)a.b_taps * a.bpitch;
+    uint32_t b_off[LB];
+#pragma unroll
+    for (int j = 0; j < LB; ++j) {
+        const int nrow = min(n0 + (wave + NW * j) * 8 + lrow, a.Nout - 1);
+        b_off[j] = (uint32_t)nrow * b_rowlen + (uint32_t)kvoff;
+    }
+    const uint16_t* zero_page = reinterpret_cast<const uint16_t*>(g_zero16);
+
+    int i_tr = 0, i_ts = 0, i_cb = 0;  // next step to issue (uniform)
+    int c_cb = 0;                      // channel base of the next step to compute (uniform)
+
+    auto issue = [&](int stage) {
+        uint8_t* sbase = smem_b + stage * STAGE_BYTES;
+        const int tapbit = i_tr * a.TS + i_ts;
+        // Element offsets are formed in 32-bit wrapping arithmetic (row constant + step delta): for a tap inside
+        // the image the sum is the true non-negative offset even when either part alone is "negative".
+        const uint32_t sa = (uint32_t)((i_tr * a.tr_step * a.srcW + i_ts * a.ts_step) * a.apitch + i_cb);
+        const uint32_t sb = (uint32_t)((a.b_tap0 + i_tr * a.b_tr_stride + i_ts * a.b_ts_stride) * a.bpitch + i_cb);
+        const bool chunk_ok = !RAGGED || (i_cb + kvoff < a.Cred);
+#pragma unroll
+        for (int j = 0; j < LA; ++j) {
+            const bool ok = chunk_ok && ((a_mask[j] >> tapbit) & 1u);
+            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.A + (uint32_t)(a_off[j] + sa), zero_page),
+                                             (lds_void_ptr)(sbase + (wave + NW * j) * 1024), 16, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < LB; ++j) {
+            if constexpr (RAGGED)
+                __builtin_amdgcn_global_load_lds(pick_ptr(chunk_ok, a.B + (uint32_t)(b_off[j] + sb), zero_page),
+                                                 (lds_void_ptr)(sbase + BM * 128 + (wave + NW * j) * 1024), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(uintptr_t)(a.B + (uint32_t)(b_off[j] + sb)),
+                                                 (lds_void_ptr)(sbase + BM * 128 + (wave + NW * j) * 1024), 16, 0, 0);
+        }
+        i_cb += BK;
+        if (i_cb >= a.CredP) {
+            i_cb = 0;
+            if (++i_ts == a.TS) { i_ts = 0; ++i_tr; }
+        }
+    };
+    // zero the channel tail of this lane's own vectors of `stage` (their data has landed for this wave)
+    auto fixup = [&](int stage) {
+        if constexpr (RAGGED) {
+            const int nvalid = a.Cred - (c_cb + kvoff);
+            if (nvalid > 0 && nvalid < 8) {
+                const Mask8 k = make_mask8(nvalid);
+                uint8_t* sbase = smem_b + stage * STAGE_BYTES + lane * 16;
+#pragma unroll
+                for (int j = 0; j < LA + LB; ++j) {
+                    uint4* p = reinterpret_cast<uint4*>(sbase + (j < LA ? (wave + NW * j) * 1024
+                                                                        : BM * 128 + (wave + NW * (j - LA)) * 1024));
+                    *p = mask8(*p, true, k);
+                }
+            }
+        }
+    };
+
+    // ---- MFMA state ---------------------------------------------------------------------------
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int l32 = lane & 31;
+    const int swz = (l32 >> 1) & 7;  // all operand rows of this lane are l32 (mod 32)
+    const int kc0 = lane >> 5;
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tn][tm][v] = 0.f;
+    bool n_live[TN], m_live[TM];
+    bool all_live = true;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        n_live[tn] = n0 + wn * WTN + tn * 32 < a.Nout;
+        all_live = all_live && n_live[tn];
+    }
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        m_live[tm] = m0 + wm * WTM + tm * 32 < a.M;
+        all_live = all_live && m_live[tm];
+    }
+
+    auto compute = [&](int stage, auto check_tag) {
+        constexpr bool CHECK = decltype(check_tag)::value;
+        const uint8_t* sA = smem_b + stage * STAGE_BYTES;
+        const uint8_t* sB = sA + BM * 128;
+        const int nks = RAGGED ? min(BK / 16, (a.Cred - c_cb + 15) >> 4) : BK / 16;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (RAGGED && ks >= nks) break;
+            const int pc = (((ks * 2 + kc0) ^ swz) << 4);
+            bf16x8 fw[TN], fp[TM];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                fw[tn] = *reinterpret_cast<const bf16x8*>(sB + (wn * WTN + tn * 32 + l32) * 128 + pc);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                fp[tm] = *reinterpret_cast<const bf16x8*>(sA + (wm * WTM + tm * 32 + l32) * 128 + pc);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    if (!CHECK || (n_live[tn] && m_live[tm]))
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[tn], fp[tm], acc[tn][tm], 0, 0, 0);
+        }
+        c_cb += BK;
+        if (c_cb >= a.CredP) c_cb = 0;
+    };
+
+    const int nk = a.nk;
+    auto main_loop = [&](auto check_tag) {
+        for (int kt0 = 0; kt0 < nk; kt0 += STAGES) {
+#pragma unroll
+            for (int s = 0; s < STAGES; ++s) {
+                const int kt = kt0 + s;
+                if (kt < nk) {
+                    // loads of steps kt+1 .. kt+STAGES-2 may stay in flight; near the end just drain
+                    if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * LPT>();
+                    else wait_vmcnt<0>();
+                    fixup(s);
+                    if constexpr (RAGGED) wait_lgkmcnt0();
+                    barrier_nofence();  // stage s complete for every wave; stage (s-1) free again
+                    if (kt + STAGES - 1 < nk) issue((s + STAGES - 1) % STAGES);
+                    compute(s, check_tag);
+                }
+            }
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < nk) issue(s);
+    if (all_live) main_loop(std::false_type{});
+    else main_loop(std::true_type{});
+
+    // ---- epilogue: stage the bf16 tile in LDS, then 16-byte row-contiguous stores ------------------
+    constexpr int LDC = BN + 8;  // elements
+    static_assert(BM * LDC * 2 <= 160 * 1024, "epilogue tile must fit in LDS");  // launch sizes LDS for both uses
+    uint16_t* sC = reinterpret_cast<uint16_t*>(smem_b);
+    __syncthreads();
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint2 o;
+                o.x = pack_bf16x2(acc[tn][tm][4 * g + 0], acc[tn][tm][4 * g + 1]);
+                o.y = pack_bf16x2(acc[tn][tm][4 * g + 2], acc[tn][tm][4 * g + 3]);
+                *reinterpret_cast<uint2*>(&sC[(wm * WTM + tm * 32 + l32) * LDC + wn * WTN + tn * 32 + 8 * g + (lane >> 5) * 4]) = o;
+            }
+    __syncthreads();
+    constexpr int CV = BN / 8;    // 16-byte vectors per tile row
+    constexpr int RPP = NT / CV;  // rows per pass
+    const int cv = tid % CV, r0 = tid / CV;
+    const int ch = n0 + cv * 8;
+    if (ch < a.Nout) {
+#pragma unroll 4
+        for (int r = r0; r < BM; r += RPP) {
+            const int m = m0 + r;
+            if (m >= a.M) break;
+            int64_t dpix;
+            if (a.d_linear) {
+                dpix = (int64_t)m * a.dpitch;
+            } else {
+                const uint32_t row = fdiv((uint32_t)m, a.gW), gj = m - row * a.gW.d;
+                const uint32_t n = fdiv(row, a.gH), gi = row - n * a.gH.d;
+                dpix = (((int64_t)n * a.DH + (int)gi * a.d_hmul + a.d_hadd) * a.DW + (int)gj * a.d_wmul + a.d_wadd) * a.dpitch;
+            }
+            const uint4 v = *reinterpret_cast<const uint4*>(&sC[r * LDC + cv * 8]);
+            uint16_t* dst = a.D + dpix + ch;
+            if (a.d_vec16 && ch + 7 < a.Nout) {
+                *reinterpret_cast<uint4*>(dst) = v;
+            } else {
+                const uint16_t* e = reinterpret_cast<const uint16_t*>(&v);
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (ch + i < a.Nout) dst[i] = e[i];
+            }
+        }
+    }
+#endif
+}
+
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr size_t lds_pipe = (size_t)STAGES * (BM + BN) * 128, lds_epi = (size_t)BM * (BN + 8) * 2;
+    constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
+    static_assert(lds <= 160 * 1024, "LDS capacity");
+    const bool ragged = (a.Cred % 64) != 0;  // last channel block of a tap is short and/or has a masked tail
+    const void* kern = ragged ? reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true>)
+                              : reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false>);
+    static bool attr_set[2] = {false, false};  // one-time opt-in to more than 64 KiB of dynamic LDS
+    if (lds > 65536 && !attr_set[ragged]) {
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set[ragged] = true;
+    }
+    const int tiles_m = (int)ceil_div(a.M, BM);
+    a.tiles_n = (int)ceil_div(a.Nout, BN);
+    a.nk = a.TR * a.TS * (int)ceil_div(a.CredP, 64);  // steps are (tap, block of 64 channels)
+    if (ragged)
+        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true>), dim3(tiles_m * a.tiles_n), dim3(NT), lds, st, a);
+    else
+        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, false>), dim3(tiles_m * a.tiles_n), dim3(NT), lds, st, a);
+    return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------------- //
+// weight gradient
+// ------------------------------------------------------------------------------------------- //
+struct WgradArgs {
+    const uint16_t* X;   // x[N][H][W][xpitch]
+    const uint16_t* DY;  // dy[pixels][ypitch]
+    float* OUT;          // splits > 1: partial[split][K][Mtot]; else dw[K][RS][wpitch]
+    int pixels;          // N*P*Q
+    FastDiv Q, P;
+    int H, W, xpitch, ypitch;
+    int stride_h, stride_w, pad_h, pad_w;
+    int S, RS, C, CP;    // CP = C rounded up to 8; Mtot = RS*CP
+    int Mtot, K;
+    int tiles_n;         // tiles along K
+    int iters_total, iters_per_split, splits;
+    int out_row_pitch;   // elements between consecutive k in the partial buffer (Mtot)
+    int wpitch;
+    int direct;          // 1: write dw layout directly (splits == 1)
+    int o_vec;
+};
+
+template <int BM, int BN, int BK, int WGM, int WGN, int MINB, bool VEC>
+__global__ __launch_bounds__(64 * WGM * WGN, MINB) void k_wgrad(const WgradArgs a) {
+    // LDS tiles are [pixel][channel] with a row pad of 32 elements (64 bytes): the four pixel rows a
+    // 16-lane group touches in one transpose read then fall into different banks.
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int LDM = BM + 32, LDN = BN + 32;
+    constexpr int XV = BM / 8, YV = BN / 8;  // 8-vectors per pixel row
+    constexpr int XR = NT / XV, YR = NT / YV;  // pixel rows per pass
+    constexpr int XP = BK / XR, YP = BK / YR;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int STAGE_ELEMS = BK * (LDM + LDN);
+    static_assert(XP >= 1 && YP >= 1 && TM >= 1 && TN >= 1 && BK % 16 == 0 && BK % XR == 0 && BK % YR == 0, "tile config");
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int n0 = (tile % a.tiles_n) * BN;  // k origin
+    const int m0 = (tile / a.tiles_n) * BM;  // (tap, c) origin
+    const int split = blockIdx.y;
+    const int it0 = split * a.iters_per_split;
+    const int it1 = min(a.iters_total, it0 + a.iters_per_split);
+
+    // ---- loader state: every thread keeps one fixed 8-channel column of each tile ---------------
+    const int xcv = tid % XV, xrow = tid / XV;
+    const int mrow0 = m0 + xcv * 8;
+    const int tap = mrow0 / a.CP, xc0 = mrow0 - tap * a.CP;
+    const int fr = tap / a.S, fs = tap - fr * a.S;
+    const int x_nvalid = (tap < a.RS) ? a.C - xc0 : 0;
+    const int ycv = tid % YV, yrow = tid / YV;
+    const int yk0 = n0 + ycv * 8;
+    const int y_nvalid = a.K - yk0;
+
+    const Mask8 xmask = make_mask8(x_nvalid), ymask = make_mask8(y_nvalid);
+    uint4 rx[XP], ry[YP];
+    bool okx[XP], oky[YP];
+    auto gload = [&](int it) {
+        const int pbase = it * BK;
+#pragma unroll
+        for (int i = 0; i < XP; ++i) {
+            const int pix = pbase + xrow + i * XR;
+            const uint32_t row = fdiv((uint32_t)pix, a.Q);
+            const int q = pix - (int)row * (int)a.Q.d;
+            const uint32_t n = fdiv(row, a.P);
+            const int p = (int)row - (int)n * (int)a.P.d;
+            const int ih = p * a.stride_h - a.pad_h + fr, iw = q * a.stride_w - a.pad_w + fs;
+            okx[i] = pix < a.pixels && x_nvalid > 0 && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            const uint32_t off = (uint32_t)(((int)n * a.H + ih) * a.W + iw) * (uint32_t)a.xpitch + (uint32_t)xc0;
+            rx[i] = ldg8<VEC>(a.X, okx[i] ? off : 0u, x_nvalid);
+        }
+#pragma unroll
+        for (int i = 0; i < YP; ++i) {
+            const int pix = pbase + yrow + i * YR;
+            oky[i] = pix < a.pixels && y_nvalid > 0;
+            ry[i] = ldg8<VEC>(a.DY, oky[i] ? (uint32_t)pix * (uint32_t)a.ypitch + (uint32_t)yk0 : 0u, y_nvalid);
+        }
+    };
+    auto sstore = [&](int buf) {
+        uint16_t* sX = smem + buf * STAGE_ELEMS;
+        uint16_t* sY = sX + BK * LDM;
+#pragma unroll
+        for (int i = 0; i < XP; ++i)
+            *reinterpret_cast<uint4*>(&sX[(xrow + i * XR) * LDM + xcv * 8]) = mask8(rx[i], okx[i], xmask);
+#pragma unroll
+        for (int i = 0; i < YP; ++i)
+            *reinterpret_cast<uint4*>(&sY[(yrow + i * YR) * LDN + ycv * 8]) = mask8(ry[i], oky[i], ymask);
+    };
+
+    // ---- MFMA state ---------------------------------------------------------------------------
+    const int wm = wave % WGM, wn = wave / WGM;
+    // transpose-read geometry: 16-lane group g, lane t in group; source lane t points at pixel row
+    // (t/4) and channel quad (t%4); the result is 4 consecutive pixels for channel 16*(g&1) + t.
+    const int g16 = lane >> 4, t16 = lane & 15;
+    const int tr_row = (g16 >> 1) * 8 + (t16 >> 2);     // + 4*h + ks*16
+    const int tr_col = (g16 & 1) * 16 + (t16 & 3) * 4;  // + block origin
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+    bool m_live[TM], n_live[TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) m_live[tm] = m0 + wm * WTM + tm * 32 < a.Mtot;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) n_live[tn] = n0 + wn * WTN + tn * 32 < a.K;
+
+    auto tr_read = [&](const uint16_t* base, int ld, int row, int col) -> bf16x8 {
+        typedef __attribute__((address_space(3))) s16x4* lds_p;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(base + row * ld + col));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(base + (row + 4) * ld + col));
+        s16x8 r;
+        r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+        r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+        return __builtin_bit_cast(bf16x8, r);
+    };
+
+    if (it0 < it1) {
+        gload(it0);
+        sstore(0);
+    }
+    __syncthreads();
+    bool all_live = true;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) all_live = all_live && m_live[tm];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) all_live = all_live && n_live[tn];
+    auto compute = [&](int buf, auto check_tag) {
+        constexpr bool CHECK = decltype(check_tag)::value;
+        const uint16_t* sX = smem + buf * STAGE_ELEMS;
+        const uint16_t* sY = sX + BK * LDM;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fx[TM], fy[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) fx[tm] = tr_read(sX, LDM, ks * 16 + tr_row, wm * WTM + tm * 32 + tr_col);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) fy[tn] = tr_read(sY, LDN, ks * 16 + tr_row, wn * WTN + tn * 32 + tr_col);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    if (!CHECK || (m_live[tm] && n_live[tn]))
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tm], fy[tn], acc[tm][tn], 0, 0, 0);
+        }
+    };
+    auto main_loop = [&](auto check_tag) {
+        for (int it = it0; it < it1; ++it) {
+            const int buf = (it - it0) & 1;
+            if (it + 1 < it1) gload(it + 1);
+            compute(buf, check_tag);
+            if (it + 1 < it1) sstore(buf ^ 1);
+            __syncthreads();
+        }
+    };
+    if (all_live) main_loop(std::false_type{});
+    else main_loop(std::true_type{});
+
+    // ---- epilogue: lane holds k (column) = lane%32 and rows 8g + 4*(lane/32) + {0..3} = 4 consecutive c
+    float* out = a.OUT + (a.direct ? 0 : (int64_t)split * a.K * a.out_row_pitch);
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int k = n0 + wn * WTN + tn * 32 + (lane & 31);
+        if (k >= a.K) continue;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int mrow = m0 + wm * WTM + tm * 32 + 8 * g + (lane >> 5) * 4;
+                if (mrow >= a.Mtot) continue;
+                const float v0 = acc[tm][tn][4 * g + 0], v1 = acc[tm][tn][4 * g + 1];
+                const float v2 = acc[tm][tn][4 * g + 2], v3 = acc[tm][tn][4 * g + 3];
+                if (a.direct) {
+                    const int tp = mrow / a.CP, c = mrow - tp * a.CP;  // 4 consecutive rows share a tap (CP % 8 == 0)
+                    float* dst = out + ((int64_t)k * a.RS + tp) * a.wpitch + c;
+                    if (a.o_vec && c + 3 < a.C) {
+                        *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
+                    } else {
+                        if (c < a.C) dst[0] = v0;
+                        if (c + 1 < a.C) dst[1] = v1;
+                        if (c + 2 < a.C) dst[2] = v2;
+                        if (c + 3 < a.C) dst[3] = v3;
+                    }
+                } else {
+                    *reinterpret_cast<float4*>(out + (int64_t)k * a.out_row_pitch + mrow) = make_float4(v0, v1, v2, v3);
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int MINB, bool VEC = true>
+inline hipError_t launch_wgrad_cfg(WgradArgs& a, hipStream_t st) {
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr size_t lds = (size_t)2 * BK * (BM + 32 + BN + 32) * 2;
+    auto kern = k_wgrad<BM, BN, BK, WGM, WGN, MINB, VEC>;
+    static bool attr_set = false;
+    if (lds > 65536 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (int)ceil_div(a.Mtot, BM);
+    a.tiles_n = (int)ceil_div(a.K, BN);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * a.tiles_n, a.splits), dim3(NT), lds, st, a);
+    return hipSuccess;
+}
+
+}  // namespace pt
