@@ -95,7 +95,8 @@ int32_t pt_conv_bwd_weight(const pt_conv_desc* d, const uint16_t* x, const uint1
  *   out_norm[k] = ||w[k,:,:]||_2 (filter k), in_norm[c] = ||w[:,:,c]||_2 (input channel c).
  * If w_shadow is not NULL it receives the bf16 copy of w (same shape and pitch) that the
  * convolutions consume, produced from the same single read of w.
- * Limits: C <= 16384.  Deterministic (fixed reduction order). */
+ * Limit: C <= 2048.  A 16-byte aligned w with w_cpitch % 4 == 0 takes the vectorised path.
+ * Deterministic (fixed reduction order).  ws: device scratch, 16-byte aligned. */
 int32_t pt_group_norms_workspace_bytes(int32_t K, int32_t RS, int32_t C, size_t* bytes);
 int32_t pt_group_norms(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, float* out_norm,
                        float* in_norm, uint16_t* w_shadow, void* ws, size_t ws_bytes, void* stream);
@@ -110,6 +111,31 @@ int32_t pt_group_norms(const float* w, int32_t K, int32_t RS, int32_t C, int32_t
 int32_t pt_group_lasso_grad(const float* w, const float* out_norm, const float* in_norm, float lambda,
                             uint32_t flags, float* dw, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch,
                             void* stream);
+
+/* Multi-layer forms: the regulariser of Eq. 2 runs over every layer of the network each iteration and a
+ * layer's weights are small, so all layers go into a few launches (32 layers per launch).  `layers`
+ * is a HOST array of n descriptors whose pointers are device pointers; per layer the semantics,
+ * limits and determinism are those of the single-layer calls above.  The workspace is split between
+ * the layers in array order. */
+typedef struct pt_layer_weights {
+    const float* w;      /* [K][RS][w_cpitch] fp32 master weights */
+    float* out_norm;     /* [K] */
+    float* in_norm;      /* [C] */
+    uint16_t* w_shadow;  /* NULL or bf16 [K][RS][w_cpitch] */
+    int32_t K, RS, C, w_cpitch;
+} pt_layer_weights;
+typedef struct pt_layer_lasso {
+    const float* w;         /* [K][RS][w_cpitch] */
+    const float* out_norm;  /* [K] */
+    const float* in_norm;   /* [C] */
+    float* dw;              /* [K][RS][w_cpitch], accumulated into */
+    int32_t K, RS, C, w_cpitch;
+    uint32_t flags;         /* PT_LASSO_OUT | PT_LASSO_IN */
+    uint32_t reserved;
+} pt_layer_lasso;
+int32_t pt_group_norms_batched_workspace_bytes(const pt_layer_weights* layers, int32_t n, size_t* bytes);
+int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_t n, void* ws, size_t ws_bytes, void* stream);
+int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int32_t n, float lambda, void* stream);
 
 /* ---- reconfiguration: Sec. 4.1-4.2 ---------------------------------------------------------- */
 

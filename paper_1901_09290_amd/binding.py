@@ -24,6 +24,7 @@ EXPORTS = [
     "pt_conv_fwd_workspace_bytes", "pt_conv_bwd_data_workspace_bytes", "pt_conv_bwd_weight_workspace_bytes",
     "pt_conv_fwd", "pt_conv_bwd_data", "pt_conv_bwd_weight",
     "pt_group_norms_workspace_bytes", "pt_group_norms", "pt_group_lasso_grad",
+    "pt_group_norms_batched_workspace_bytes", "pt_group_norms_batched", "pt_group_lasso_grad_batched",
     "pt_zero_groups", "pt_reconcile_edge", "pt_compact_plan",
     "pt_compact_weights", "pt_compact_vector", "pt_compact_nhwc",
 ]
@@ -40,6 +41,17 @@ class ConvDesc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_int32) for n in (
         "N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "P", "Q",
         "x_cpitch", "y_cpitch", "w_cpitch")]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("out_norm", C.c_void_p), ("in_norm", C.c_void_p), ("w_shadow", C.c_void_p),
+                ("K", C.c_int32), ("RS", C.c_int32), ("C", C.c_int32), ("w_cpitch", C.c_int32)]
+
+
+class LayerLasso(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("out_norm", C.c_void_p), ("in_norm", C.c_void_p), ("dw", C.c_void_p),
+                ("K", C.c_int32), ("RS", C.c_int32), ("C", C.c_int32), ("w_cpitch", C.c_int32),
+                ("flags", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 def lib() -> C.CDLL:
@@ -63,6 +75,9 @@ def lib() -> C.CDLL:
             "pt_group_norms_workspace_bytes": [i32, i32, i32, C.POINTER(sz)],
             "pt_group_norms": [vp, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
             "pt_group_lasso_grad": [vp, vp, vp, f32, u32, vp, i32, i32, i32, i32, vp],
+            "pt_group_norms_batched_workspace_bytes": [C.POINTER(LayerWeights), i32, C.POINTER(sz)],
+            "pt_group_norms_batched": [C.POINTER(LayerWeights), i32, vp, sz, vp],
+            "pt_group_lasso_grad_batched": [C.POINTER(LayerLasso), i32, f32, vp],
             "pt_zero_groups": [vp, i32, f32, vp, vp],
             "pt_reconcile_edge": [C.POINTER(vp), i32, C.POINTER(vp), i32, i32, vp, vp],
             "pt_compact_plan": [vp, i32, vp, vp, vp],
@@ -162,6 +177,37 @@ def group_norms(w, K, RS, Cc, w_cpitch, out_norm, in_norm, w_shadow=None, ws=Non
 def group_lasso_grad(w, out_norm, in_norm, lam: float, flags: int, dw, K, RS, Cc, w_cpitch, stream=None) -> None:
     _ck("pt_group_lasso_grad", lib().pt_group_lasso_grad(_ptr(w), _ptr(out_norm), _ptr(in_norm), lam, flags, _ptr(dw),
                                                          K, RS, Cc, w_cpitch, _stream(stream)))
+
+
+def layer_weights(w, K, RS, Cc, w_cpitch, out_norm, in_norm, w_shadow=None) -> LayerWeights:
+    return LayerWeights(_ptr(w), _ptr(out_norm), _ptr(in_norm), _ptr(w_shadow), K, RS, Cc, w_cpitch)
+
+
+def layer_lasso(w, out_norm, in_norm, dw, K, RS, Cc, w_cpitch, flags) -> LayerLasso:
+    return LayerLasso(_ptr(w), _ptr(out_norm), _ptr(in_norm), _ptr(dw), K, RS, Cc, w_cpitch, flags, 0)
+
+
+def _array(items, typ):
+    return items if isinstance(items, C.Array) else (typ * max(1, len(items)))(*items)
+
+
+def group_norms_batched_workspace_bytes(layers) -> int:
+    arr = _array(layers, LayerWeights)
+    n = C.c_size_t(0)
+    _ck("pt_group_norms_batched_workspace_bytes", lib().pt_group_norms_batched_workspace_bytes(arr, len(layers), C.byref(n)))
+    return n.value
+
+
+def group_norms_batched(layers, ws, stream=None) -> None:
+    """layers: list of LayerWeights (or a prepared ctypes array of them)."""
+    arr = _array(layers, LayerWeights)
+    p, n = _ws(ws)
+    _ck("pt_group_norms_batched", lib().pt_group_norms_batched(arr, len(layers), p, n, _stream(stream)))
+
+
+def group_lasso_grad_batched(layers, lam: float, stream=None) -> None:
+    arr = _array(layers, LayerLasso)
+    _ck("pt_group_lasso_grad_batched", lib().pt_group_lasso_grad_batched(arr, len(layers), lam, _stream(stream)))
 
 
 def zero_groups(norms, n: int, thr: float, zero, stream=None) -> None:

@@ -37,6 +37,15 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+// Two fp32 -> packed bf16x2 (lo in bits 15:0) with the hardware converter (round to nearest even).
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    f32x2_t f = {lo, hi};
+    bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, b);
+}
+
 // Exact floor(m / d) for m*d < 2^32 with magic = floor(2^32 / d) + 1 (computed on the host).
 __device__ __forceinline__ uint32_t fast_div(uint32_t m, uint32_t magic) { return __umulhi(m, magic); }
 inline uint32_t make_magic(uint32_t d) { return (uint32_t)((((uint64_t)1) << 32) / d + 1); }

@@ -98,8 +98,10 @@ inline IgemmArgs make_bwd_data_args(const pt_conv_desc* d, const BwdClass& c, in
 inline hipError_t launch_igemm(IgemmArgs& a, bool vec, hipStream_t st) {
     if (!vec) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, false>(a, st);
     if (a.TR * a.TS > 32) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, true>(a, st);
-    if (a.Nout <= 64) return launch_igemm_dl_cfg<256, 64, 4, 2, 3>(a, st);
-    return launch_igemm_dl_cfg<256, 128, 4, 2, 3>(a, st);
+    // 128x128 tiles when they still fill the chip, else 128x64 tiles (more workgroups, deeper pipeline)
+    const int64_t tiles128 = ceil_div(a.M, 128) * ceil_div(a.Nout, 128);
+    if (a.Nout <= 64 || tiles128 < 160) return launch_igemm_dl_cfg<128, 64, 4, 2, 3>(a, st);
+    return launch_igemm_dl_cfg<128, 128, 2, 4, 2>(a, st);
 }
 
 inline size_t bwd_data_ws(const pt_conv_desc* d) {

@@ -483,23 +483,30 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
         const uint8_t* sA = smem_b + stage * STAGE_BYTES;
         const uint8_t* sB = sA + BM * 128;
         const int nks = RAGGED ? min(BK / 16, (a.Cred - c_cb + 15) >> 4) : BK / 16;
+        // operand fragments are double-buffered in registers: the LDS reads of k-step ks+1 are issued
+        // before the MFMAs of k-step ks, so LDS latency hides behind the matrix pipe
+        bf16x8 fw[2][TN], fp[2][TM];
+        auto read_frags = [&](int ks, int b) {
+            const int pc = (((ks * 2 + kc0) ^ swz) << 4);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                fw[b][tn] = *reinterpret_cast<const bf16x8*>(sB + (wn * WTN + tn * 32 + l32) * 128 + pc);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                fp[b][tm] = *reinterpret_cast<const bf16x8*>(sA + (wm * WTM + tm * 32 + l32) * 128 + pc);
+        };
+        read_frags(0, 0);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             if (RAGGED && ks >= nks) break;
-            const int pc = (((ks * 2 + kc0) ^ swz) << 4);
-            bf16x8 fw[TN], fp[TM];
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                fw[tn] = *reinterpret_cast<const bf16x8*>(sB + (wn * WTN + tn * 32 + l32) * 128 + pc);
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                fp[tm] = *reinterpret_cast<const bf16x8*>(sA + (wm * WTM + tm * 32 + l32) * 128 + pc);
+            if (ks + 1 < BK / 16 && (!RAGGED || ks + 1 < nks)) read_frags(ks + 1, (ks + 1) & 1);
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
                     if (!CHECK || (n_live[tn] && m_live[tm]))
-                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[tn], fp[tm], acc[tn][tm], 0, 0, 0);
+                        acc[tn][tm] =
+                            __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][tn], fp[ks & 1][tm], acc[tn][tm], 0, 0, 0);
         }
         c_cb += BK;
         if (c_cb >= a.CredP) c_cb = 0;
@@ -542,8 +549,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 uint2 o;
-                o.x = pack_bf16x2(acc[tn][tm][4 * g + 0], acc[tn][tm][4 * g + 1]);
-                o.y = pack_bf16x2(acc[tn][tm][4 * g + 2], acc[tn][tm][4 * g + 3]);
+                o.x = cvt_pk_bf16(acc[tn][tm][4 * g + 0], acc[tn][tm][4 * g + 1]);
+                o.y = cvt_pk_bf16(acc[tn][tm][4 * g + 2], acc[tn][tm][4 * g + 3]);
                 *reinterpret_cast<uint2*>(&sC[(wm * WTM + tm * 32 + l32) * LDC + wn * WTN + tn * 32 + 8 * g + (lane >> 5) * 4]) = o;
             }
     __syncthreads();

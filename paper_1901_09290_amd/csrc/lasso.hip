@@ -2,30 +2,62 @@
 //
 // Both are HBM-bound: group_norms reads the fp32 master weights once (4 B/param, +2 B/param written
 // when the bf16 shadow is emitted); the gradient pass reads w and dw and writes dw (12 B/param).
+// A network has tens of layers whose weight tensors are small (KBs to a few MB), so every kernel here
+// is multi-tensor: up to kMaxJobs layers ride in the kernel arguments of ONE launch and a workgroup
+// finds its (layer, row chunk) from a table of first-workgroup indices.
 //
-// Thread layout (both kernels): a workgroup of 256 threads is a TY x TX grid, TX = lanes across the
-// channel axis (a power of two <= 64, so a row of TX lanes lives inside one wavefront), TY = 256/TX
-// rows in flight.  A thread keeps the same channel columns for every row it visits, so input-channel
-// (column) sums stay in registers; output-channel (row) sums are reduced across the TX lanes with
-// wavefront shuffles and then across rows through LDS.  All reductions run in a fixed order.
+// Thread layout: a workgroup of 256 threads is a TY x TX grid, TX = lanes across the channel axis (a
+// power of two <= 64, so a row of TX lanes lives inside one wavefront), TY = 256/TX rows in flight.  A
+// thread keeps the same channel columns for every row it visits, so input-channel (column) sums stay
+// in registers; output-channel (row) sums are reduced across the TX lanes with wavefront shuffles.
+// Two levels, fixed order, no atomics: a workgroup owns whole rows of a chunk and writes one
+// sum-of-squares per row and one partial per column; the finish kernel adds the R*S row sums of each
+// filter and the per-chunk column partials in ascending order.
 #include "common.h"
 
 namespace pt {
 
-constexpr int kNormThreads = 256;
-constexpr int kNormMaxRows = 2048;  // LDS row-sum slots per workgroup
-constexpr int kNormColsPerThread = 8;
+constexpr int kThreads = 256;
+constexpr int kMaxC = 2048;  // 64 lanes x (8 float4 column groups | 32 scalar column groups) per thread
+constexpr int kMaxJobs = 32;       // layers per launch (kernel-argument table)
 
-template <int VEC>
-struct VecT;
-template <>
-struct VecT<4> {
-    using type = float4;
+struct NormJob {
+    const float* w;
+    uint16_t* shadow;
+    float* rowsq;     // [K*RS] sum of squares of each (k, rs) row
+    float* colpart;   // [n_chunks][C] per-chunk column sums of squares
+    float* out_norm;
+    float* in_norm;
+    int K, RS, C, cpitch;
+    int first_block, n_chunks, rows_per_chunk, txlog2;
 };
-template <>
-struct VecT<1> {
-    using type = float;
+struct NormJobs {
+    NormJob j[kMaxJobs];
+    int n;
 };
+
+struct LassoJob {
+    const float* w;
+    const float* out_norm;
+    const float* in_norm;
+    float* dw;
+    int K, RS, C, cpitch;
+    int first_block, n_chunks, rows_per_chunk, txlog2;
+    uint32_t flags;
+    int pad;
+};
+struct LassoJobs {
+    LassoJob j[kMaxJobs];
+    int n;
+};
+
+template <typename Jobs>
+__device__ __forceinline__ int find_job(const Jobs& jobs, int block) {
+    int idx = 0;
+    for (int i = 1; i < jobs.n; ++i)
+        if (block >= jobs.j[i].first_block) idx = i;
+    return idx;
+}
 
 template <int VEC>
 __device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
@@ -37,131 +69,133 @@ __device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
     }
 }
 
-// One workgroup = filters [k0, k0 + fpb).  Writes out_norm for its filters and one row of column
-// partial sums (sum of squares per input channel over its filters) to ws_cols[block][C].
+// One workgroup = one chunk of whole rows of one layer.
 template <int VEC>
-__global__ __launch_bounds__(kNormThreads) void k_group_norms_partial(const float* __restrict__ w, int K, int RS,
-                                                                      int C, int cpitch, int fpb, int txlog2,
-                                                                      uint16_t* __restrict__ shadow,
-                                                                      float* __restrict__ out_norm,
-                                                                      float* __restrict__ ws_cols) {
-    __shared__ float rowsum[kNormMaxRows];
-    __shared__ float colred[kNormThreads * kNormColsPerThread * VEC];
+__global__ __launch_bounds__(kThreads) void k_group_norms_partial(const NormJobs jobs) {
+    constexpr int kColsPerThread = kMaxC / (64 * VEC);
+    __shared__ float colred[kThreads * VEC];
+    const int ji = find_job(jobs, blockIdx.x);
+    const NormJob& J = jobs.j[ji];
+    const int chunk = blockIdx.x - J.first_block;
     const int tid = threadIdx.x;
-    const int TX = 1 << txlog2, TY = kNormThreads >> txlog2;
-    const int tx = tid & (TX - 1), ty = tid >> txlog2;
-    const int k0 = blockIdx.x * fpb;
-    const int k1 = min(K, k0 + fpb);
-    const int nrows = (k1 - k0) * RS;
-    const size_t rowbase = (size_t)k0 * RS;
+    const int TX = 1 << J.txlog2, TY = kThreads >> J.txlog2;
+    const int tx = tid & (TX - 1), ty = tid >> J.txlog2;
+    const int64_t rows = (int64_t)J.K * J.RS;
+    const int64_t r0 = (int64_t)chunk * J.rows_per_chunk;
+    const int64_t r1 = min(rows, r0 + J.rows_per_chunk);
+    const int C = J.C, cpitch = J.cpitch;
     const int Lv = (C + VEC - 1) / VEC;
+    const float* __restrict__ w = J.w;
+    uint16_t* __restrict__ shadow = J.shadow;
 
-    for (int r = tid; r < nrows; r += kNormThreads) rowsum[r] = 0.f;
-    __syncthreads();
+    float acc[kColsPerThread][VEC];
+#pragma unroll
+    for (int j = 0; j < kColsPerThread; ++j)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[j][e] = 0.f;
 
-    for (int cbase = 0; cbase < Lv; cbase += TX * kNormColsPerThread) {
-        float acc[kNormColsPerThread][VEC];
+    for (int64_t r = r0 + ty; r < r1; r += TY) {
+        const size_t roff = (size_t)r * cpitch;
+        float rs = 0.f;
 #pragma unroll
-        for (int j = 0; j < kNormColsPerThread; ++j)
+        for (int j = 0; j < kColsPerThread; ++j) {
+            const int cg = tx + j * TX;
+            if (cg < Lv) {
+                float v[VEC];
+                load_vec<VEC>(w + roff + (size_t)cg * VEC, v);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[j][e] = 0.f;
-
-        for (int r = ty; r < nrows; r += TY) {
-            const size_t roff = (rowbase + r) * (size_t)cpitch;
-            float rs = 0.f;
-#pragma unroll
-            for (int j = 0; j < kNormColsPerThread; ++j) {
-                const int cg = cbase + tx + j * TX;
-                if (cg < Lv) {
-                    float v[VEC];
-                    load_vec<VEC>(w + roff + (size_t)cg * VEC, v);
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) {
-                        if (cg * VEC + e >= C) v[e] = 0.f;  // pitch padding is not data
-                        const float q = v[e] * v[e];
-                        acc[j][e] += q;
-                        rs += q;
-                    }
-                    if (shadow) {
-                        if constexpr (VEC == 4) {
-                            if (cg * 4 + 3 < C) {
-                                uint2 o;
-                                o.x = pack_bf16x2(v[0], v[1]);
-                                o.y = pack_bf16x2(v[2], v[3]);
-                                *reinterpret_cast<uint2*>(shadow + roff + (size_t)cg * 4) = o;
-                            } else {
-                                for (int e = 0; e < 4; ++e)
-                                    if (cg * 4 + e < C) shadow[roff + (size_t)cg * 4 + e] = f32_to_bf16(v[e]);
-                            }
+                for (int e = 0; e < VEC; ++e) {
+                    if (cg * VEC + e >= C) v[e] = 0.f;  // pitch padding is not data
+                    const float q = v[e] * v[e];
+                    acc[j][e] += q;
+                    rs += q;
+                }
+                if (shadow) {
+                    if constexpr (VEC == 4) {
+                        if (cg * 4 + 3 < C) {
+                            uint2 o;
+                            o.x = cvt_pk_bf16(v[0], v[1]);
+                            o.y = cvt_pk_bf16(v[2], v[3]);
+                            *reinterpret_cast<uint2*>(shadow + roff + (size_t)cg * 4) = o;
                         } else {
-                            shadow[roff + cg] = f32_to_bf16(v[0]);
+                            for (int e = 0; e < 4; ++e)
+                                if (cg * 4 + e < C) shadow[roff + (size_t)cg * 4 + e] = f32_to_bf16(v[e]);
                         }
+                    } else {
+                        shadow[roff + cg] = f32_to_bf16(v[0]);
                     }
                 }
             }
-            for (int off = TX >> 1; off > 0; off >>= 1) rs += __shfl_xor(rs, off);
-            if (tx == 0) rowsum[r] += rs;  // always the same thread for a given row: fixed order
         }
-
-        // column sums: across the TY row groups, in ty order
-#pragma unroll
-        for (int j = 0; j < kNormColsPerThread; ++j)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) colred[((ty * kNormColsPerThread + j) * TX + tx) * VEC + e] = acc[j][e];
-        __syncthreads();
-        const int slots = kNormColsPerThread * TX * VEC;
-        for (int f = tid; f < slots; f += kNormThreads) {
-            const int c = cbase * VEC + f;  // (j*TX + tx)*VEC + e is the column offset inside this chunk
-            if (c < C) {
-                float s = 0.f;
-                for (int y = 0; y < TY; ++y) s += colred[y * slots + f];
-                ws_cols[(size_t)blockIdx.x * C + c] = s;
-            }
-        }
-        __syncthreads();
+        for (int off = TX >> 1; off > 0; off >>= 1) rs += __shfl_xor(rs, off);
+        if (tx == 0) J.rowsq[r] = rs;
     }
 
-    for (int kk = tid; kk < k1 - k0; kk += kNormThreads) {
-        float s = 0.f;
-        for (int j = 0; j < RS; ++j) s += rowsum[kk * RS + j];
-        out_norm[k0 + kk] = sqrtf(s);
+    // column partials: across the TY row groups of the workgroup, in ty order, one column group at a time
+#pragma unroll
+    for (int j = 0; j < kColsPerThread; ++j) {
+        if (j * TX >= Lv) break;  // uniform
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) colred[(ty * TX + tx) * VEC + e] = acc[j][e];
+        __syncthreads();
+        for (int f = tid; f < TX * VEC; f += kThreads) {
+            const int c = j * TX * VEC + f;
+            if (c < C) {
+                float s = 0.f;
+                for (int y = 0; y < TY; ++y) s += colred[y * TX * VEC + f];
+                J.colpart[(size_t)chunk * C + c] = s;
+            }
+        }
     }
 }
 
-__global__ void k_group_norms_finish(const float* __restrict__ ws_cols, int nblk, int C, float* __restrict__ in_norm) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    float s = 0.f;
-    for (int b = 0; b < nblk; ++b) s += ws_cols[(size_t)b * C + c];
-    in_norm[c] = sqrtf(s);
+// One thread per group: K filters then C input channels of each job.
+__global__ __launch_bounds__(kThreads) void k_group_norms_finish(const NormJobs jobs) {
+    const int ji = blockIdx.y;
+    const NormJob& J = jobs.j[ji];
+    const int g = blockIdx.x * kThreads + threadIdx.x;
+    if (g < J.K) {
+        float s = 0.f;
+        for (int t = 0; t < J.RS; ++t) s += J.rowsq[(size_t)g * J.RS + t];
+        J.out_norm[g] = sqrtf(s);
+    } else if (g < J.K + J.C) {
+        const int c = g - J.K;
+        float s = 0.f;
+        for (int b = 0; b < J.n_chunks; ++b) s += J.colpart[(size_t)b * J.C + c];
+        J.in_norm[c] = sqrtf(s);
+    }
 }
 
 template <int VEC>
-__global__ __launch_bounds__(kNormThreads) void k_group_lasso_grad(const float* __restrict__ w,
-                                                                   const float* __restrict__ out_norm,
-                                                                   const float* __restrict__ in_norm, float lambda,
-                                                                   uint32_t flags, float* __restrict__ dw,
-                                                                   int64_t rows, int RS, int C, int cpitch,
-                                                                   int rows_per_block, int txlog2) {
+__global__ __launch_bounds__(kThreads) void k_group_lasso_grad(const LassoJobs jobs, float lambda) {
+    const int ji = find_job(jobs, blockIdx.x);
+    const LassoJob& J = jobs.j[ji];
+    const int chunk = blockIdx.x - J.first_block;
     const int tid = threadIdx.x;
-    const int TX = 1 << txlog2, TY = kNormThreads >> txlog2;
-    const int tx = tid & (TX - 1), ty = tid >> txlog2;
+    const int TX = 1 << J.txlog2, TY = kThreads >> J.txlog2;
+    const int tx = tid & (TX - 1), ty = tid >> J.txlog2;
+    const int C = J.C, cpitch = J.cpitch, RS = J.RS;
     const int Lv = (C + VEC - 1) / VEC;
-    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
-    const int64_t r1 = min(rows, r0 + rows_per_block);
-    const bool reg_out = flags & PT_LASSO_OUT, reg_in = flags & PT_LASSO_IN;
+    const int64_t rows = (int64_t)J.K * RS;
+    const int64_t r0 = (int64_t)chunk * J.rows_per_chunk;
+    const int64_t r1 = min(rows, r0 + J.rows_per_chunk);
+    const bool reg_out = J.flags & PT_LASSO_OUT, reg_in = J.flags & PT_LASSO_IN;
+    const float* __restrict__ w = J.w;
+    float* __restrict__ dw = J.dw;
 
     for (int cg = tx; cg < Lv; cg += TX) {
         float inv_in[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const int c = cg * VEC + e;
-            const float nrm = (reg_in && c < C) ? in_norm[c] : 0.f;
+            const float nrm = (reg_in && c < C) ? J.in_norm[c] : 0.f;
             inv_in[e] = nrm > 0.f ? 1.0f / nrm : 0.f;
         }
+#pragma unroll 4
         for (int64_t r = r0 + ty; r < r1; r += TY) {
             const int k = (int)(r / RS);
-            const float on = reg_out ? out_norm[k] : 0.f;
+            const float on = reg_out ? J.out_norm[k] : 0.f;
             const float inv_out = on > 0.f ? 1.0f / on : 0.f;
             const size_t off = (size_t)r * cpitch + (size_t)cg * VEC;
             float v[VEC], g[VEC];
@@ -183,87 +217,199 @@ __global__ __launch_bounds__(kNormThreads) void k_group_lasso_grad(const float* 
     }
 }
 
-static int tx_log2_for(int Lv) {
+// ---- host-side planning ---------------------------------------------------------------------- //
+struct ChunkPlan {
+    int txlog2, rows_per_chunk, n_chunks;
+};
+
+static ChunkPlan plan_chunks(int64_t rows, int C, bool vec) {
+    const int Lv = vec ? (C + 3) / 4 : C;
     int l = 0;
     while ((1 << l) < Lv && l < 6) ++l;
-    return l;
+    const int TY = kThreads >> l;
+    // about 16 K elements per workgroup, a whole number of TY-row passes
+    int64_t rpc = ceil_div(16384, C);
+    rpc = round_up(rpc, TY);
+    ChunkPlan p;
+    p.txlog2 = l;
+    p.rows_per_chunk = (int)rpc;
+    p.n_chunks = (int)ceil_div(rows, rpc);
+    return p;
 }
 
-static int norms_fpb(int K, int RS, int C) {
-    int64_t per_filter = (int64_t)RS * C;
-    int64_t fpb = 32768 / (per_filter > 0 ? per_filter : 1);
-    if (fpb < 1) fpb = 1;
-    if (fpb > kNormMaxRows / RS) fpb = kNormMaxRows / RS;
-    if (fpb < 1) fpb = 1;
-    if (fpb > K) fpb = K;
-    return (int)fpb;
+static bool norms_vec_ok(const pt_layer_weights& L) {
+    return (L.w_cpitch % 4 == 0) && (((uintptr_t)L.w & 15) == 0) && (!L.w_shadow || ((uintptr_t)L.w_shadow & 7) == 0) &&
+           L.C <= kMaxC;
+}
+
+static int32_t check_layer(const pt_layer_weights& L) {
+    if (!L.w) return PT_ERR_NULL;
+    if (L.K <= 0 || L.RS <= 0 || L.C <= 0 || L.w_cpitch < L.C) return PT_ERR_SHAPE;
+    if (L.C > kMaxC) return PT_ERR_UNSUPPORTED;  // register tile of the column sums
+    return PT_OK;
+}
+
+// Workspace of one layer: row sums + per-chunk column partials, sized for whichever loader is used.
+static size_t layer_ws_bytes(const pt_layer_weights& L) {
+    const int64_t rows = (int64_t)L.K * L.RS;
+    const ChunkPlan a = plan_chunks(rows, L.C, true), b = plan_chunks(rows, L.C, false);
+    const int n_chunks = a.n_chunks > b.n_chunks ? a.n_chunks : b.n_chunks;
+    return (size_t)round_up((rows + (int64_t)n_chunks * L.C) * 4, 256);
 }
 
 }  // namespace pt
 
 using namespace pt;
 
+extern "C" int32_t pt_group_norms_batched_workspace_bytes(const pt_layer_weights* layers, int32_t n, size_t* bytes) {
+    if (!bytes || (n > 0 && !layers)) return PT_ERR_NULL;
+    if (n < 0) return PT_ERR_SHAPE;
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        if (layers[i].K <= 0 || layers[i].RS <= 0 || layers[i].C <= 0) return PT_ERR_SHAPE;
+        total += layer_ws_bytes(layers[i]);
+    }
+    *bytes = total;
+    return PT_OK;
+}
+
+extern "C" int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_t n, void* ws, size_t ws_bytes,
+                                          void* stream) {
+    if (n < 0) return PT_ERR_SHAPE;
+    if (n == 0) return PT_OK;
+    if (!layers || !ws) return PT_ERR_NULL;
+    size_t need = 0;
+    for (int i = 0; i < n; ++i) {
+        int32_t rc = check_layer(layers[i]);
+        if (rc != PT_OK) return rc;
+        if (!layers[i].out_norm || !layers[i].in_norm) return PT_ERR_NULL;
+        need += layer_ws_bytes(layers[i]);
+    }
+    if (ws_bytes < need) return PT_ERR_WORKSPACE;
+    if (((uintptr_t)ws & 15) != 0) return PT_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    char* wsp = (char*)ws;
+    // layers are grouped by loader kind (vector / element-wise) and sent kMaxJobs at a time
+    for (int pass = 0; pass < 2; ++pass) {
+        const bool want_vec = pass == 0;
+        NormJobs jobs;
+        jobs.n = 0;
+        int blocks = 0, maxg = 0;
+        auto flush = [&]() -> int32_t {
+            if (jobs.n == 0) return PT_OK;
+            if (want_vec)
+                hipLaunchKernelGGL(k_group_norms_partial<4>, dim3(blocks), dim3(kThreads), 0, st, jobs);
+            else
+                hipLaunchKernelGGL(k_group_norms_partial<1>, dim3(blocks), dim3(kThreads), 0, st, jobs);
+            int32_t rc = launch_status();
+            if (rc != PT_OK) return rc;
+            hipLaunchKernelGGL(k_group_norms_finish, dim3((unsigned)ceil_div(maxg, kThreads), jobs.n), dim3(kThreads), 0, st,
+                               jobs);
+            jobs.n = 0;
+            blocks = 0;
+            maxg = 0;
+            return launch_status();
+        };
+        char* p = wsp;
+        for (int i = 0; i < n; ++i) {
+            const pt_layer_weights& L = layers[i];
+            const size_t bytes = layer_ws_bytes(L);
+            const bool vec = norms_vec_ok(L);
+            if (vec == want_vec) {
+                const int64_t rows = (int64_t)L.K * L.RS;
+                const ChunkPlan cp = plan_chunks(rows, L.C, vec);
+                NormJob& J = jobs.j[jobs.n++];
+                J.w = L.w; J.shadow = L.w_shadow; J.out_norm = L.out_norm; J.in_norm = L.in_norm;
+                J.rowsq = (float*)p; J.colpart = (float*)p + rows;
+                J.K = L.K; J.RS = L.RS; J.C = L.C; J.cpitch = L.w_cpitch;
+                J.first_block = blocks; J.n_chunks = cp.n_chunks; J.rows_per_chunk = cp.rows_per_chunk; J.txlog2 = cp.txlog2;
+                blocks += cp.n_chunks;
+                if (L.K + L.C > maxg) maxg = L.K + L.C;
+                if (jobs.n == kMaxJobs) {
+                    int32_t rc = flush();
+                    if (rc != PT_OK) return rc;
+                }
+            }
+            p += bytes;
+        }
+        int32_t rc = flush();
+        if (rc != PT_OK) return rc;
+    }
+    return PT_OK;
+}
+
+extern "C" int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int32_t n, float lambda, void* stream) {
+    if (n < 0) return PT_ERR_SHAPE;
+    if (n == 0) return PT_OK;
+    if (!layers) return PT_ERR_NULL;
+    for (int i = 0; i < n; ++i) {
+        const pt_layer_lasso& L = layers[i];
+        if (!L.w || !L.out_norm || !L.in_norm || !L.dw) return PT_ERR_NULL;
+        if (L.K <= 0 || L.RS <= 0 || L.C <= 0 || L.w_cpitch < L.C) return PT_ERR_SHAPE;
+        if (L.flags & ~3u) return PT_ERR_UNSUPPORTED;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    for (int pass = 0; pass < 2; ++pass) {
+        const bool want_vec = pass == 0;
+        LassoJobs jobs;
+        jobs.n = 0;
+        int blocks = 0;
+        auto flush = [&]() -> int32_t {
+            if (jobs.n == 0) return PT_OK;
+            if (want_vec)
+                hipLaunchKernelGGL(k_group_lasso_grad<4>, dim3(blocks), dim3(kThreads), 0, st, jobs, lambda);
+            else
+                hipLaunchKernelGGL(k_group_lasso_grad<1>, dim3(blocks), dim3(kThreads), 0, st, jobs, lambda);
+            jobs.n = 0;
+            blocks = 0;
+            return launch_status();
+        };
+        for (int i = 0; i < n; ++i) {
+            const pt_layer_lasso& L = layers[i];
+            const bool vec = (L.w_cpitch % 4 == 0) && (((uintptr_t)L.w & 15) == 0) && (((uintptr_t)L.dw & 15) == 0);
+            if (vec != want_vec) continue;
+            const ChunkPlan cp = plan_chunks((int64_t)L.K * L.RS, L.C, vec);
+            LassoJob& J = jobs.j[jobs.n++];
+            J.w = L.w; J.out_norm = L.out_norm; J.in_norm = L.in_norm; J.dw = L.dw;
+            J.K = L.K; J.RS = L.RS; J.C = L.C; J.cpitch = L.w_cpitch;
+            J.first_block = blocks; J.n_chunks = cp.n_chunks; J.rows_per_chunk = cp.rows_per_chunk; J.txlog2 = cp.txlog2;
+            J.flags = L.flags; J.pad = 0;
+            blocks += cp.n_chunks;
+            if (jobs.n == kMaxJobs) {
+                int32_t rc = flush();
+                if (rc != PT_OK) return rc;
+            }
+        }
+        int32_t rc = flush();
+        if (rc != PT_OK) return rc;
+    }
+    return PT_OK;
+}
+
+// ---- single-layer forms: the batched calls with one entry ------------------------------------- //
 extern "C" int32_t pt_group_norms_workspace_bytes(int32_t K, int32_t RS, int32_t C, size_t* bytes) {
     if (!bytes) return PT_ERR_NULL;
     if (K <= 0 || RS <= 0 || C <= 0) return PT_ERR_SHAPE;
-    if (RS > kNormMaxRows || C > 16384) return PT_ERR_UNSUPPORTED;
-    const int fpb = norms_fpb(K, RS, C);
-    const int64_t nblk = ceil_div(K, fpb);
-    *bytes = (size_t)round_up(nblk * (int64_t)C * 4, 256);
+    pt_layer_weights L{};
+    L.K = K; L.RS = RS; L.C = C; L.w_cpitch = C;
+    *bytes = layer_ws_bytes(L);
     return PT_OK;
 }
 
 extern "C" int32_t pt_group_norms(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, float* out_norm,
                                   float* in_norm, uint16_t* w_shadow, void* ws, size_t ws_bytes, void* stream) {
     if (!w || !out_norm || !in_norm || !ws) return PT_ERR_NULL;
-    if (K <= 0 || RS <= 0 || C <= 0 || w_cpitch < C) return PT_ERR_SHAPE;
-    size_t need = 0;
-    int32_t rc = pt_group_norms_workspace_bytes(K, RS, C, &need);
-    if (rc != PT_OK) return rc;
-    if (ws_bytes < need) return PT_ERR_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    const int fpb = norms_fpb(K, RS, C);
-    const int nblk = (int)ceil_div(K, fpb);
-    const bool vec = (w_cpitch % 4 == 0) && (((uintptr_t)w & 15) == 0) &&
-                     (!w_shadow || ((uintptr_t)w_shadow & 7) == 0);
-    float* cols = (float*)ws;
-    if (vec) {
-        const int txl = tx_log2_for((C + 3) / 4);
-        hipLaunchKernelGGL(k_group_norms_partial<4>, dim3(nblk), dim3(kNormThreads), 0, st, w, K, RS, C, w_cpitch, fpb,
-                           txl, w_shadow, out_norm, cols);
-    } else {
-        const int txl = tx_log2_for(C);
-        hipLaunchKernelGGL(k_group_norms_partial<1>, dim3(nblk), dim3(kNormThreads), 0, st, w, K, RS, C, w_cpitch, fpb,
-                           txl, w_shadow, out_norm, cols);
-    }
-    rc = launch_status();
-    if (rc != PT_OK) return rc;
-    hipLaunchKernelGGL(k_group_norms_finish, dim3((C + 255) / 256), dim3(256), 0, st, cols, nblk, C, in_norm);
-    return launch_status();
+    pt_layer_weights L{};
+    L.w = w; L.K = K; L.RS = RS; L.C = C; L.w_cpitch = w_cpitch;
+    L.out_norm = out_norm; L.in_norm = in_norm; L.w_shadow = w_shadow;
+    return pt_group_norms_batched(&L, 1, ws, ws_bytes, stream);
 }
 
 extern "C" int32_t pt_group_lasso_grad(const float* w, const float* out_norm, const float* in_norm, float lambda,
                                        uint32_t flags, float* dw, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch,
                                        void* stream) {
-    if (!w || !out_norm || !in_norm || !dw) return PT_ERR_NULL;
-    if (K <= 0 || RS <= 0 || C <= 0 || w_cpitch < C) return PT_ERR_SHAPE;
-    if (flags & ~3u) return PT_ERR_UNSUPPORTED;
-    hipStream_t st = (hipStream_t)stream;
-    const int64_t rows = (int64_t)K * RS;
-    const bool vec = (w_cpitch % 4 == 0) && (((uintptr_t)w & 15) == 0) && (((uintptr_t)dw & 15) == 0);
-    const int Lv = vec ? (C + 3) / 4 : C;
-    const int txl = tx_log2_for(Lv);
-    // about 8192 vectors per workgroup
-    int64_t rpb = ceil_div(8192, Lv);
-    const int TY = kNormThreads >> txl;
-    rpb = round_up(rpb, TY);
-    const int64_t nblk = ceil_div(rows, rpb);
-    if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
-    if (vec)
-        hipLaunchKernelGGL(k_group_lasso_grad<4>, dim3((unsigned)nblk), dim3(kNormThreads), 0, st, w, out_norm, in_norm,
-                           lambda, flags, dw, rows, RS, C, w_cpitch, (int)rpb, txl);
-    else
-        hipLaunchKernelGGL(k_group_lasso_grad<1>, dim3((unsigned)nblk), dim3(kNormThreads), 0, st, w, out_norm, in_norm,
-                           lambda, flags, dw, rows, RS, C, w_cpitch, (int)rpb, txl);
-    return launch_status();
+    pt_layer_lasso L{};
+    L.w = w; L.out_norm = out_norm; L.in_norm = in_norm; L.dw = dw;
+    L.K = K; L.RS = RS; L.C = C; L.w_cpitch = w_cpitch; L.flags = flags;
+    return pt_group_lasso_grad_batched(&L, 1, lambda, stream);
 }

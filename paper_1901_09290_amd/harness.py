@@ -78,6 +78,16 @@ class ConvLayer:
         return max(B.conv_fwd_workspace_bytes(d), B.conv_bwd_data_workspace_bytes(d),
                    B.conv_bwd_weight_workspace_bytes(d), B.group_norms_workspace_bytes(self.spec.K, self.RS, self.spec.C))
 
+    def norms_job(self, shadow: bool = True) -> B.LayerWeights:
+        s = self.spec
+        return B.layer_weights(self.w_master, s.K, self.RS, s.C, self.wp, self.out_norm, self.in_norm,
+                               self.w_bf16 if shadow else None)
+
+    def lasso_job(self) -> B.LayerLasso:
+        s = self.spec
+        return B.layer_lasso(self.w_master, self.out_norm, self.in_norm, self.dw, s.K, self.RS, s.C, self.wp,
+                             self.lasso_flags)
+
     # --- the five calls of one training step on this layer, in Alg. 1 order -------------------- #
     def norms(self, ws, shadow: bool = True):
         s = self.spec
@@ -122,6 +132,34 @@ def build_network(specs: Sequence[wl.ConvSpec], seed: int) -> List[ConvLayer]:
     return [ConvLayer(s, gen=gen) for s in specs]
 
 
+class Network:
+    """A list of conv layers plus the prepared multi-layer descriptor tables and workspaces."""
+
+    def __init__(self, layers: Sequence[ConvLayer]):
+        self.layers = list(layers)
+        self.norm_jobs = (B.LayerWeights * len(self.layers))(*[l.norms_job() for l in self.layers])
+        self.lasso_jobs = (B.LayerLasso * len(self.layers))(*[l.lasso_job() for l in self.layers])
+        self.ws_norms = torch.empty(max(256, B.group_norms_batched_workspace_bytes(self.norm_jobs)), dtype=torch.uint8,
+                                    device=DEV)
+        self.ws = make_workspace(self.layers)
+
+    def train_step(self, lam: float) -> None:
+        """Alg. 1, one iteration restricted to the conv layers: GroupLassoReg (all layers' group norms, which
+        also refreshes the bf16 weights the convolutions read), ForwardProp, BackProp (input and weight
+        gradients, last layer first), then the regulariser's gradient added onto every dW."""
+        B.group_norms_batched(self.norm_jobs, self.ws_norms)
+        for l in self.layers:
+            l.fwd(self.ws)
+        for l in reversed(self.layers):
+            l.bwd_data(self.ws)
+            l.bwd_weight(self.ws)
+        B.group_lasso_grad_batched(self.lasso_jobs, lam)
+
+    @property
+    def step_flops(self) -> int:
+        return sum(l.step_flops for l in self.layers)
+
+
 def train_step(layers: Sequence[ConvLayer], ws: torch.Tensor, lam: float) -> None:
     for l in layers:
         l.train_step(ws, lam)
@@ -160,8 +198,11 @@ class ReconfigModel:
         self.keep = [torch.zeros(e.n, dtype=u8, device=DEV) for e in self.edges]
         self.idx = [torch.zeros(e.n, dtype=i32, device=DEV) for e in self.edges]
         self.counts = torch.zeros(len(self.edges), dtype=i32, device=DEV)
-        self.ws = torch.empty(max([B.group_norms_workspace_bytes(s.K, s.R * s.S, s.C) for s in self.specs] + [256]),
-                              dtype=torch.uint8, device=DEV)
+        self.norm_jobs = (B.LayerWeights * len(self.specs))(*[
+            B.layer_weights(self.w[i], s.K, s.R * s.S, s.C, pitch8(s.C), self.on[i], self.inn[i], None)
+            for i, s in enumerate(self.specs)])
+        self.ws = torch.empty(max(256, B.group_norms_batched_workspace_bytes(self.norm_jobs)), dtype=torch.uint8,
+                              device=DEV)
         # outputs sized for "nothing pruned"; the sweep writes the compacted tensors at their own pitch
         self.w_out = [torch.zeros_like(t) for t in self.w]
         self.mom_out = [torch.zeros_like(t) for t in self.mom]
@@ -171,8 +212,8 @@ class ReconfigModel:
 
     def detect(self, thr: float) -> None:
         """group_norms + zero_groups per layer, reconcile + plan per edge (all asynchronous)."""
+        B.group_norms_batched(self.norm_jobs, self.ws)
         for i, s in enumerate(self.specs):
-            B.group_norms(self.w[i], s.K, s.R * s.S, s.C, pitch8(s.C), self.on[i], self.inn[i], None, self.ws)
             B.zero_groups(self.on[i], s.K, thr, self.zo[i])
             B.zero_groups(self.inn[i], s.C, thr, self.zi[i])
         for e, edge in enumerate(self.edges):
