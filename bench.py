@@ -3,14 +3,16 @@
 
 One *step* = one pass of the whole hot path over one batch of synthetic input:
   (1) training step at full width   - the 53 ResNet-50 convolutions at batch 64 (224x224 image):
-      per layer group_norms(+bf16 shadow), conv_fwd, conv_bwd_data, conv_bwd_weight, group_lasso_grad;
+      group norms of every layer (+ bf16 shadow weights), conv_fwd per layer, conv_bwd_data and
+      conv_bwd_weight per layer in reverse order, group-lasso gradient added to every dW;
   (2) reconfiguration sweep         - group_norms + zero_groups on every layer, reconcile + plan on
       every channel edge, then compaction of weights, momentum, normalisation vectors and the saved
-      input activations (30 % of each edge's channels zeroed on the pruned-width model);
+      input activations (a fraction of each edge's channels zeroed on the pruned-width model);
   (3) training step at pruned width - the same 53 layers at ragged widths (keep fractions U[0.4,0.9]).
 `value` = convolution FLOPs of (1)+(3) divided by the time of the whole step, inputs resident in HBM.
-
-Prints ONE JSON line on stdout.  --detail writes a per-layer table to gpurun_out/.
+The launch sequences are captured once into HIP graphs and replayed (the survivor counts the sweep
+reads back are checked on every step).  Prints ONE JSON line on stdout; --detail writes per-layer
+tables under gpurun_out/.
 """
 from __future__ import annotations
 
@@ -36,15 +38,16 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(max_seconds: float = 30.0):
+def cpu_baseline(max_seconds: float = 25.0, batch: int = 16):
     """The fp64 oracle, as it stands, on the host cores: fwd + bwd_data + bwd_weight of the full-width
-    ResNet-50 layer shapes at batch 1 (1/64 of the workload's batch), stopping after ~max_seconds."""
+    ResNet-50 layer shapes at a reduced batch, stopping after ~max_seconds."""
     import oracle
     from paper_1901_09290_amd import workloads as wl
-    layers, _ = wl.resnet50_layers(N=1)
+    layers, _ = wl.resnet50_layers(N=batch)
     rng = np.random.Generator(np.random.PCG64(2))
     flops, secs, done = 0, 0.0, 0
-    for spec, _cnt in wl.distinct_shapes(layers):
+    shapes = wl.distinct_shapes(layers)
+    for spec, _cnt in shapes:
         t = wl.conv_tensors(spec, rng)
         s = oracle.shape_of(spec)
         t0 = time.perf_counter()
@@ -57,19 +60,31 @@ def cpu_baseline(max_seconds: float = 30.0):
         done += 1
         if secs > max_seconds:
             break
-    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"fp64 nested-loop oracle, fwd+bwd_data+bwd_weight of the first {done} distinct ResNet-50 "
-                      f"layer shapes at batch 1 ({flops / 1e9:.1f} GFLOP in {secs:.1f} s)"}
+    return {"value": round(flops / secs / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"fp64 nested-loop oracle, fwd+bwd_data+bwd_weight of the first {done} of {len(shapes)} distinct "
+                      f"ResNet-50 layer shapes at batch {batch} ({flops / 1e9:.1f} GFLOP in {secs:.1f} s)"}
+
+
+def conv_bytes(spec, which: str) -> int:
+    """Algorithmic HBM bytes of one convolution pass (bf16 activations and weights, fp32 dw)."""
+    st2 = spec.stride * spec.stride if spec.R == 1 else 1      # a strided 1x1 touches 1/stride^2 of its input pixels
+    x = 2 * spec.N * spec.H * spec.W * spec.C // st2
+    y = 2 * spec.N * spec.P * spec.Q * spec.K
+    w = 2 * spec.params
+    if which == "bwd_weight":
+        return x + y + 4 * spec.params
+    return x + y + w
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--sparsity", type=float, default=0.3, help="fraction of each edge zeroed in the sweep")
-    ap.add_argument("--detail", action="store_true", help="write a per-layer table under gpurun_out/")
+    ap.add_argument("--detail", action="store_true", help="write per-layer tables under gpurun_out/")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -90,23 +105,51 @@ def main():
     full_specs, edges = wl.resnet50_layers(N=N)
     keep = wl.pruned_keep_sets(edges, seed=3)
     pruned_specs, pruned_edges = wl.with_widths(full_specs, edges, [k.size for k in keep])
-    full = hz.build_network(full_specs, seed=2)
-    pruned = hz.build_network(pruned_specs, seed=3)
-    ws = hz.make_workspace(full + pruned)
+    full = hz.Network(hz.build_network(full_specs, seed=2))
+    pruned = hz.Network(hz.build_network(pruned_specs, seed=3))
     rng = np.random.Generator(np.random.PCG64(10 + int(round(args.sparsity * 10))))
     zero_sets = wl.zeroed_channel_sets(pruned_edges, args.sparsity, rng)
     rweights = wl.network_weights(pruned_specs, pruned_edges, zero_sets, rng)
     rmodel = hz.ReconfigModel(pruned_specs, pruned_edges, rweights, seed=11)
     torch.cuda.synchronize()
-    f_full = sum(l.step_flops for l in full)
-    f_pruned = sum(l.step_flops for l in pruned)
+    f_full, f_pruned = full.step_flops, pruned.step_flops
     log(f"full: {f_full / 1e12:.3f} TFLOP/step, pruned: {f_pruned / 1e12:.3f} TFLOP/step, "
         f"mem {torch.cuda.memory_allocated() / 2**30:.1f} GiB")
 
-    def step():
-        hz.train_step(full, ws, LAMBDA)
+    # ---- eager warm-up (also the first launches that set kernel attributes) ---------------------- #
+    for _ in range(max(1, args.warmup)):
+        full.train_step(LAMBDA)
         rmodel.sweep(THRESHOLD)
-        hz.train_step(pruned, ws, LAMBDA)
+        pruned.train_step(LAMBDA)
+    torch.cuda.synchronize()
+    counts0 = rmodel.new_counts.copy()
+    expect = np.array([e.n - z.size for e, z in zip(pruned_edges, zero_sets)])
+    assert np.array_equal(counts0, expect), "survivor counts differ from the zero pattern that was planted"
+
+    use_graph = not args.no_graph
+    if use_graph:
+        side = torch.cuda.Stream()
+        g1, g2 = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g1, stream=side):
+                full.train_step(LAMBDA)
+                rmodel.detect(THRESHOLD)
+            with torch.cuda.graph(g2, stream=side):
+                rmodel.compact(counts0)
+                pruned.train_step(LAMBDA)
+        torch.cuda.synchronize()
+
+        def step():
+            g1.replay()
+            cnt = rmodel.counts.cpu().numpy()          # the sweep's one synchronising read-back
+            if not np.array_equal(cnt, counts0):
+                raise RuntimeError("survivor counts changed between steps")
+            g2.replay()
+    else:
+        def step():
+            full.train_step(LAMBDA)
+            rmodel.sweep(THRESHOLD)
+            pruned.train_step(LAMBDA)
 
     for _ in range(args.warmup):
         step()
@@ -126,8 +169,9 @@ def main():
     ms_step = e0.elapsed_time(e1) / args.steps
     value = (f_full + f_pruned) / (ms_step * 1e-3) / 1e12
 
-    # ---- per-phase and per-call timing (same launches, HIP events on the launch stream) -------- #
+    # ---- per-phase and per-family timing (same launches, HIP events on the launch stream) -------- #
     def timed(fn, reps):
+        fn()
         a, b = ev(), ev()
         a.record()
         for _ in range(reps):
@@ -136,48 +180,74 @@ def main():
         b.synchronize()
         return a.elapsed_time(b) / reps
 
-    reps = max(1, args.steps)
-    t_full = timed(lambda: hz.train_step(full, ws, LAMBDA), reps)
-    t_pruned = timed(lambda: hz.train_step(pruned, ws, LAMBDA), reps)
-    t_sweep = timed(lambda: rmodel.sweep(THRESHOLD), reps)
-    t_detect = timed(lambda: rmodel.detect(THRESHOLD), reps)
+    reps = max(3, min(10, args.steps))
+    if use_graph:
+        gf, gp, gd, gc = (torch.cuda.CUDAGraph() for _ in range(4))
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(gf, stream=side):
+                full.train_step(LAMBDA)
+            with torch.cuda.graph(gp, stream=side):
+                pruned.train_step(LAMBDA)
+            with torch.cuda.graph(gd, stream=side):
+                rmodel.detect(THRESHOLD)
+            with torch.cuda.graph(gc, stream=side):
+                rmodel.compact(counts0)
+        torch.cuda.synchronize()
+        t_full, t_pruned = timed(gf.replay, reps), timed(gp.replay, reps)
+        t_detect, t_compact = timed(gd.replay, reps), timed(gc.replay, reps)
+    else:
+        t_full = timed(lambda: full.train_step(LAMBDA), reps)
+        t_pruned = timed(lambda: pruned.train_step(LAMBDA), reps)
+        t_detect = timed(lambda: rmodel.detect(THRESHOLD), reps)
+        t_compact = timed(lambda: rmodel.compact(counts0), reps)
 
-    calls = ("norms", "fwd", "bwd_data", "bwd_weight", "lasso")
-    per = {}
+    # kernel families: every layer's call of one kind back to back between two events
+    fam = {}
     for tag, net in (("full", full), ("pruned", pruned)):
-        rows = []
-        for l in net:
-            r = {"name": l.spec.name, "shape": list(l.spec.shape_key()), "flops": l.spec.flops}
-            for c in calls:
-                fn = (lambda l=l, c=c: l.lasso(LAMBDA)) if c == "lasso" else (lambda l=l, c=c: getattr(l, c)(ws))
-                if c == "bwd_data" and l.dx is None:
-                    r[c] = 0.0
-                    continue
-                r[c] = timed(fn, 3)
-            rows.append(r)
-        per[tag] = rows
+        L = net.layers
+        fam[tag] = {
+            "fwd": timed(lambda: [l.fwd(net.ws) for l in L], 3),
+            "bwd_data": timed(lambda: [l.bwd_data(net.ws) for l in L], 3),
+            "bwd_weight": timed(lambda: [l.bwd_weight(net.ws) for l in L], 3),
+            "group_norms": timed(lambda: B.group_norms_batched(net.norm_jobs, net.ws_norms), 5),
+            "group_lasso_grad": timed(lambda: B.group_lasso_grad_batched(net.lasso_jobs, LAMBDA), 5),
+        }
+    fl = {tag: {"fwd": sum(l.spec.flops for l in net.layers),
+                "bwd_data": sum(l.spec.flops for l in net.layers if l.dx is not None),
+                "bwd_weight": sum(l.spec.flops for l in net.layers)} for tag, net in (("full", full), ("pruned", pruned))}
+    by = {tag: {k: sum(conv_bytes(l.spec, k) for l in net.layers if not (k == "bwd_data" and l.dx is None))
+                for k in ("fwd", "bwd_data", "bwd_weight")} for tag, net in (("full", full), ("pruned", pruned))}
+    params = {tag: sum(l.spec.params for l in net.layers) for tag, net in (("full", full), ("pruned", pruned))}
 
-    def conv_rate(rows, key, skip_first=False):
-        f = sum(r["flops"] for r in rows if not (skip_first and r[key] == 0.0))
-        t = sum(r[key] for r in rows)
-        return f / (t * 1e-3) / 1e12 if t > 0 else 0.0, t
-
-    # dominant kernel: the implicit-GEMM forward/input-gradient kernel (fwd + bwd_data launches)
-    ig_f = sum(r["flops"] * (1 + (r["bwd_data"] > 0)) for tag in per for r in per[tag])
-    ig_t = sum(r["fwd"] + r["bwd_data"] for tag in per for r in per[tag])
-    ig_launches = sum(1 + (r["bwd_data"] > 0) for tag in per for r in per[tag])
-    ig_rate = ig_f / (ig_t * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_igemm (conv_fwd + conv_bwd_data launches of one step)",
-                "achieved": round(ig_rate, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ig_rate / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                "avg_launch_ms": round(ig_t / ig_launches, 5), "flops_per_launch": ig_f / ig_launches}
+    # dominant kernel family of the step = the conv family with the largest time over both widths
+    tot = {k: fam["full"][k] + fam["pruned"][k] for k in ("fwd", "bwd_data", "bwd_weight")}
+    dom = max(tot, key=tot.get)
+    kernel_of = {"fwd": "k_igemm_dl (conv_fwd launches)", "bwd_data": "k_igemm_dl (conv_bwd_data launches)",
+                 "bwd_weight": "k_wgrad_dl + k_wgrad_reduce (conv_bwd_weight launches)"}
+    n_launch = sum(1 for net in (full, pruned) for l in net.layers if not (dom == "bwd_data" and l.dx is None))
+    dom_flops = fl["full"][dom] + fl["pruned"][dom]
+    dom_rate = dom_flops / (tot[dom] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": kernel_of[dom], "achieved": round(dom_rate, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(dom_rate / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": round(tot[dom] / n_launch, 5), "flops_per_launch": dom_flops / n_launch,
+                "launches_per_step": n_launch}
 
     ab = rmodel.algorithmic_bytes()
     sweep_bytes = sum(ab.values())
-    norms_bytes_full = sum(4 * l.spec.params + 2 * l.spec.params for l in full)     # read fp32, write bf16 shadow
-    norms_t_full = sum(r["norms"] for r in per["full"])
-    lasso_bytes_full = sum(12 * l.spec.params for l in full)
-    lasso_t_full = sum(r["lasso"] for r in per["full"])
+    t_sweep = t_detect + t_compact
+
+    def fam_table(tag):
+        out = {}
+        for k in ("fwd", "bwd_data", "bwd_weight"):
+            t = fam[tag][k]
+            out[k] = {"ms": round(t, 4), "tflops": round(fl[tag][k] / (t * 1e-3) / 1e12, 1),
+                      "algorithmic_GBps": round(by[tag][k] / (t * 1e-3) / 1e9, 1)}
+        tn, tl = fam[tag]["group_norms"], fam[tag]["group_lasso_grad"]
+        out["group_norms"] = {"ms": round(tn, 4), "GBps": round(6 * params[tag] / (tn * 1e-3) / 1e9, 1),
+                              "frac_hbm_peak": round(6 * params[tag] / (tn * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        out["group_lasso_grad"] = {"ms": round(tl, 4), "GBps": round(12 * params[tag] / (tl * 1e-3) / 1e9, 1),
+                                   "frac_hbm_peak": round(12 * params[tag] / (tl * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        return out
 
     out = {
         "metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -186,7 +256,7 @@ def main():
         "config": {"workload": f"ResNet-50 conv layers (53), batch {N}, 224x224, NHWC bf16: train step at full width "
                                f"(cfg3) + reconfiguration sweep at {int(args.sparsity * 100)}% zeroed groups (cfg5) + "
                                "train step at ragged pruned widths (cfg4)",
-                   "lambda": LAMBDA, "threshold": THRESHOLD},
+                   "lambda": LAMBDA, "threshold": THRESHOLD, "hip_graphs": use_graph},
         "roofline": roofline,
         "breakdown": {
             "wall_ms_per_step": round(wall_ms, 4),
@@ -196,34 +266,33 @@ def main():
                              "frac_mfma_peak": round(f_pruned / (t_pruned * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                              "flop_ratio_vs_full": round(f_pruned / f_full, 4),
                              "time_ratio_vs_full": round(t_pruned / t_full, 4)},
-            "conv_tflops_full": {c: round(conv_rate(per["full"], c)[0], 2) for c in ("fwd", "bwd_data", "bwd_weight")},
-            "conv_tflops_pruned": {c: round(conv_rate(per["pruned"], c)[0], 2)
-                                   for c in ("fwd", "bwd_data", "bwd_weight")},
-            "reconfig_sweep": {"ms": round(t_sweep, 4), "detect_ms": round(t_detect, 4),
-                               "algorithmic_MB": round(sweep_bytes / 1e6, 1),
+            "kernel_families_full": fam_table("full"),
+            "kernel_families_pruned": fam_table("pruned"),
+            "reconfig_sweep": {"ms": round(t_sweep, 4), "detect_ms": round(t_detect, 4), "compact_ms": round(t_compact, 4),
+                               "algorithmic_MB": {k: round(v / 1e6, 1) for k, v in ab.items()},
                                "GBps": round(sweep_bytes / (t_sweep * 1e-3) / 1e9, 1),
                                "frac_hbm_peak": round(sweep_bytes / (t_sweep * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
-            "group_norms_full": {"ms": round(norms_t_full, 4),
-                                 "GBps": round(norms_bytes_full / (norms_t_full * 1e-3) / 1e9, 1)},
-            "group_lasso_grad_full": {"ms": round(lasso_t_full, 4),
-                                      "GBps": round(lasso_bytes_full / (lasso_t_full * 1e-3) / 1e9, 1)},
         },
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
 
     if args.detail:
+        calls = ("fwd", "bwd_data", "bwd_weight")
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         with open(os.path.join(ROOT, "gpurun_out", "bench_detail.txt"), "w") as f:
-            for tag in per:
-                f.write(f"== {tag} ==  (ms, TFLOP/s per call)\n")
-                f.write(f"{'layer':22s} {'N,H,W,C,K,R,S,st,pad':34s} {'GF':>7s} | {'norms':>7s} {'fwd':>7s} {'TF/s':>6s} "
-                        f"{'bwd_d':>7s} {'TF/s':>6s} {'bwd_w':>7s} {'TF/s':>6s} {'lasso':>7s}\n")
-                for r in per[tag]:
-                    tf = lambda k: (r["flops"] / (r[k] * 1e-3) / 1e12) if r[k] > 0 else 0.0
-                    f.write(f"{r['name']:22s} {str(tuple(r['shape'])):34s} {r['flops'] / 1e9:7.2f} | {r['norms']:7.4f} "
-                            f"{r['fwd']:7.4f} {tf('fwd'):6.0f} {r['bwd_data']:7.4f} {tf('bwd_data'):6.0f} "
-                            f"{r['bwd_weight']:7.4f} {tf('bwd_weight'):6.0f} {r['lasso']:7.4f}\n")
+            for tag, net in (("full", full), ("pruned", pruned)):
+                f.write(f"== {tag} ==  per call, eager (includes launch latency): us, TFLOP/s, algorithmic GB/s\n")
+                for l in net.layers:
+                    row = f"{l.spec.name:18s} {str(l.spec.shape_key()):36s} {l.spec.flops / 1e9:7.2f} GF |"
+                    for c in calls:
+                        if c == "bwd_data" and l.dx is None:
+                            row += f" {'-':>8s} {'':>5s} {'':>5s} |"
+                            continue
+                        t = timed(lambda l=l, c=c: getattr(l, c)(net.ws), 3)
+                        row += (f" {t * 1e3:8.1f} {l.spec.flops / (t * 1e-3) / 1e12:5.0f} "
+                                f"{conv_bytes(l.spec, c) / (t * 1e-3) / 1e9:5.0f} |")
+                    f.write(row + "\n")
             f.write(json.dumps(out, indent=1) + "\n")
     print(json.dumps(out), flush=True)
 

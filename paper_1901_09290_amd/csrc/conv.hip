@@ -58,19 +58,40 @@ __global__ void k_zero_class(uint16_t* __restrict__ D, int64_t pixels, int gH, i
     D[((n * DH + gi * d_hmul + d_hadd) * DW + gj * d_wmul + d_wadd) * dpitch + ch] = 0;
 }
 
-// dw[k][tap][c] = sum over splits (ascending) of partial[split][k][tap*CP + c].
-__global__ void k_wgrad_reduce(const float* __restrict__ part, int splits, int K, int RS, int C, int CP, int wpitch,
-                               float* __restrict__ dw) {
+// dw[k][tap][c] = sum over splits of partial[split][k][tap*CP + c], in a fixed order: a workgroup owns
+// 64 consecutive outputs; wavefront v adds the splits v, v+8, v+16, ... (four loads in flight), and the
+// eight wavefront sums are added in ascending order.  Results do not depend on timing.
+constexpr int kReduceWaves = 8;
+__global__ __launch_bounds__(64 * kReduceWaves) void k_wgrad_reduce(const float* __restrict__ part, int splits, int K,
+                                                                     int RS, int C, int CP, int wpitch,
+                                                                     float* __restrict__ dw) {
+    __shared__ float red[kReduceWaves][64];
     const int Mtot = RS * CP;
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (int64_t)K * Mtot) return;
-    const int64_t k = t / Mtot;
-    const int mrow = (int)(t - k * Mtot);
-    const int tp = mrow / CP, c = mrow - tp * CP;
-    if (c >= C) return;
-    float s = 0.f;
-    for (int i = 0; i < splits; ++i) s += part[(int64_t)i * K * Mtot + t];
-    dw[(k * RS + tp) * wpitch + c] = s;
+    const int64_t total = (int64_t)K * Mtot;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t t = (int64_t)blockIdx.x * 64 + lane;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (t < total) {
+        int i = wave;
+        for (; i + 3 * kReduceWaves < splits; i += 4 * kReduceWaves) {
+            s0 += part[(int64_t)i * total + t];
+            s1 += part[(int64_t)(i + kReduceWaves) * total + t];
+            s2 += part[(int64_t)(i + 2 * kReduceWaves) * total + t];
+            s3 += part[(int64_t)(i + 3 * kReduceWaves) * total + t];
+        }
+        for (; i < splits; i += kReduceWaves) s0 += part[(int64_t)i * total + t];
+    }
+    red[wave][lane] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (wave == 0 && t < total) {
+        float s = 0.f;
+#pragma unroll
+        for (int v = 0; v < kReduceWaves; ++v) s += red[v][lane];
+        const int64_t k = t / Mtot;
+        const int mrow = (int)(t - k * Mtot);
+        const int tp = mrow / CP, c = mrow - tp * CP;
+        if (c < C) dw[(k * RS + tp) * wpitch + c] = s;
+    }
 }
 
 }  // namespace pt
@@ -99,7 +120,7 @@ extern "C" int32_t pt_conv_bwd_weight_workspace_bytes(const pt_conv_desc* d, siz
     if (!bytes) return PT_ERR_NULL;
     int32_t rc = check_desc(d);
     if (rc != PT_OK) return rc;
-    *bytes = plan_wgrad(d).ws_bytes;
+    *bytes = wgrad_ws(d);
     return PT_OK;
 }
 
@@ -164,21 +185,22 @@ extern "C" int32_t pt_conv_bwd_weight(const pt_conv_desc* d, const uint16_t* x, 
     int32_t rc = check_desc(d);
     if (rc != PT_OK) return rc;
     if (!x || !dy || !dw) return PT_ERR_NULL;
-    const WgradPlan p = plan_wgrad(d);
+    // the direct kernel needs 16-byte aligned rows; it keeps one tile row block per filter tap
+    const bool vec = d->x_cpitch % 8 == 0 && d->y_cpitch % 8 == 0 && aligned16(x) && aligned16(dy);
+    const WgradPlan p = plan_wgrad(d, vec);
     if (p.ws_bytes > 0 && !ws) return PT_ERR_NULL;
     if (ws_bytes < p.ws_bytes) return PT_ERR_WORKSPACE;
     if (p.ws_bytes > 0 && !aligned16(ws)) return PT_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
     WgradArgs a = make_wgrad_args(d, p, x, dy, dw, ws);
-    const bool vec = d->x_cpitch % 8 == 0 && d->y_cpitch % 8 == 0 && aligned16(x) && aligned16(dy);
     rc = hip_status(launch_wgrad(a, p, vec, st));
     if (rc != PT_OK) return rc;
     if (!a.direct) {
         const int64_t work = (int64_t)d->K * p.Mtot;
-        const int64_t nblk = ceil_div(work, 256);
+        const int64_t nblk = ceil_div(work, 64);
         if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)nblk), dim3(256), 0, st, (const float*)ws, p.splits, d->K, a.RS,
-                           d->C, p.CP, d->w_cpitch, dw);
+        hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)nblk), dim3(64 * kReduceWaves), 0, st, (const float*)ws, p.splits,
+                           d->K, a.RS, d->C, p.CP, d->w_cpitch, dw);
         rc = launch_status();
     }
     return rc;

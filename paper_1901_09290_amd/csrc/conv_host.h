@@ -108,22 +108,48 @@ inline size_t bwd_data_ws(const pt_conv_desc* d) {
     return (size_t)round_up((int64_t)d->C * d->R * d->S * round_up(d->K, 8) * 2, 256);
 }
 
+// Split plan of the weight gradient.  `dl`: the direct global->LDS kernel (one filter tap per tile row
+// block, tiles of 64 or 128 channels) is used; otherwise the register-staged kernel (flattened
+// (tap, channel) axis, fixed 128x128 tiles).
 struct WgradPlan {
-    int splits, iters_total, iters_per_split, tiles_m, tiles_n, CP, Mtot;
+    int dl, BM, BN;
+    int splits, iters_total, iters_per_split, tiles_m, tiles_n, tiles_per_tap, CP, KP, Mtot;
     size_t ws_bytes;
 };
-constexpr int kWgBM = 128, kWgBN = 128, kWgBK = 32;
+constexpr int kWgBM = 128, kWgBN = 128, kWgBK = 32;  // register-staged kernel
+constexpr int kWgDlBKP = 64;                          // direct kernel: pixels per reduction step
 
-inline WgradPlan plan_wgrad(const pt_conv_desc* d) {
+// 64-wide tiles when 128-wide ones would waste more than ~20 % of their rows
+inline int pick_tile(int n) {
+    const int64_t r128 = round_up(n, 128), r64 = round_up(n, 64);
+    return (r64 < r128 && r128 * 5 > (int64_t)n * 6) ? 64 : 128;
+}
+
+inline WgradPlan plan_wgrad(const pt_conv_desc* d, bool dl) {
     WgradPlan p;
+    p.dl = dl;
     p.CP = (int)round_up(d->C, 8);
+    p.KP = (int)round_up(d->K, 8);
     p.Mtot = d->R * d->S * p.CP;
-    p.tiles_m = (int)ceil_div(p.Mtot, kWgBM);
-    p.tiles_n = (int)ceil_div(d->K, kWgBN);
     const int64_t pixels = (int64_t)d->N * d->P * d->Q;
-    p.iters_total = (int)ceil_div(pixels, kWgBK);
+    if (dl) {
+        p.BM = pick_tile(p.CP);
+        p.BN = pick_tile(p.KP);
+        p.tiles_per_tap = (int)ceil_div(p.CP, p.BM);
+        p.tiles_m = d->R * d->S * p.tiles_per_tap;
+        p.tiles_n = (int)ceil_div(d->K, p.BN);
+        p.iters_total = (int)ceil_div(pixels, kWgDlBKP);
+    } else {
+        p.BM = kWgBM;
+        p.BN = kWgBN;
+        p.tiles_per_tap = 0;
+        p.tiles_m = (int)ceil_div(p.Mtot, kWgBM);
+        p.tiles_n = (int)ceil_div(d->K, kWgBN);
+        p.iters_total = (int)ceil_div(pixels, kWgBK);
+    }
+    // about three workgroups per CU in total, at least 8 reduction steps each
     const int tiles = p.tiles_m * p.tiles_n;
-    int64_t splits = ceil_div(1024, tiles);
+    int64_t splits = ceil_div(768, tiles);
     const int64_t max_splits = p.iters_total / 8 > 0 ? p.iters_total / 8 : 1;
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
@@ -131,6 +157,11 @@ inline WgradPlan plan_wgrad(const pt_conv_desc* d) {
     p.splits = (int)ceil_div(p.iters_total, p.iters_per_split);
     p.ws_bytes = p.splits > 1 ? (size_t)round_up((int64_t)p.splits * d->K * p.Mtot * 4, 256) : 0;
     return p;
+}
+
+inline size_t wgrad_ws(const pt_conv_desc* d) {
+    const size_t a = plan_wgrad(d, true).ws_bytes, b = plan_wgrad(d, false).ws_bytes;
+    return a > b ? a : b;
 }
 
 inline WgradArgs make_wgrad_args(const pt_conv_desc* d, const WgradPlan& p, const uint16_t* x, const uint16_t* dy,
@@ -141,8 +172,8 @@ inline WgradArgs make_wgrad_args(const pt_conv_desc* d, const WgradPlan& p, cons
     a.Q = make_fastdiv((uint32_t)d->Q); a.P = make_fastdiv((uint32_t)d->P);
     a.H = d->H; a.W = d->W; a.xpitch = d->x_cpitch; a.ypitch = d->y_cpitch;
     a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
-    a.S = d->S; a.RS = d->R * d->S; a.C = d->C; a.CP = p.CP; a.Mtot = p.Mtot; a.K = d->K;
-    a.tiles_n = p.tiles_n;
+    a.S = d->S; a.RS = d->R * d->S; a.C = d->C; a.CP = p.CP; a.KP = p.KP; a.Mtot = p.Mtot; a.K = d->K;
+    a.tiles_n = p.tiles_n; a.tiles_m = p.tiles_m; a.tiles_per_tap = p.tiles_per_tap;
     a.iters_total = p.iters_total; a.iters_per_split = p.iters_per_split; a.splits = p.splits;
     a.wpitch = d->w_cpitch;
     a.direct = p.splits == 1;
@@ -152,9 +183,16 @@ inline WgradArgs make_wgrad_args(const pt_conv_desc* d, const WgradPlan& p, cons
     return a;
 }
 
-inline hipError_t launch_wgrad(WgradArgs& a, const WgradPlan&, bool vec, hipStream_t st) {
-    if (!vec) return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2, false>(a, st);
-    return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2>(a, st);
+inline hipError_t launch_wgrad(WgradArgs& a, const WgradPlan& p, bool vec, hipStream_t st) {
+    if (!p.dl) {
+        if (!vec) return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2, false>(a, st);
+        return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2>(a, st);
+    }
+    // wave grids and pipeline depths from measurements on ResNet-50 shapes
+    if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKP, 4, 2, 2>(a, st);
+    if (p.BM == 64 && p.BN == 128) return launch_wgrad_dl_cfg<64, 128, kWgDlBKP, 2, 2, 3>(a, st);
+    if (p.BM == 128 && p.BN == 64) return launch_wgrad_dl_cfg<128, 64, kWgDlBKP, 2, 2, 3>(a, st);
+    return launch_wgrad_dl_cfg<64, 64, kWgDlBKP, 2, 2, 4>(a, st);
 }
 
 }  // namespace pt

@@ -625,6 +625,9 @@ struct WgradArgs {
     int S, RS, C, CP;    // CP = C rounded up to 8; Mtot = RS*CP
     int Mtot, K;
     int tiles_n;         // tiles along K
+    int tiles_m;         // tiles along (tap, c)
+    int tiles_per_tap;   // direct kernel: channel blocks per filter tap
+    int KP;              // K rounded up to 8
     int iters_total, iters_per_split, splits;
     int out_row_pitch;   // elements between consecutive k in the partial buffer (Mtot)
     int wpitch;
@@ -823,4 +826,197 @@ inline hipError_t launch_wgrad_cfg(WgradArgs& a, hipStream_t st) {
     return hipSuccess;
 }
 
+// ------------------------------------------------------------------------------------------- //
+// weight gradient with direct global->LDS loads (vector path)
+// ------------------------------------------------------------------------------------------- //
+// Output tile: BM input channels of ONE filter tap x BN output channels; reduction over output pixels
+// in steps of BKP.  Both tiles are pixel-major in LDS exactly as they sit in memory (a pixel row of
+// the x tile is BM channels = 2*BM bytes), filled by 16-byte global->LDS loads and read back with the
+// transpose read.  32-byte units of a row are XOR-swizzled with the pixel row so that the four pixel
+// rows a 16-lane group touches in one transpose read fall into different banks.  Pixels whose tap
+// falls outside the image, and pixels past the end, fetch from the zero page (both operands, so no
+// garbage ever meets a zero).  Channel chunks past the channel count re-read the last valid chunk:
+// they only feed accumulator rows/columns that are never stored.
+template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
+    constexpr int NW = WGM * WGN;
+    constexpr int RBX = BM * 2, RBY = BN * 2;              // bytes per pixel row
+    constexpr int CPRX = RBX / 16, CPRY = RBY / 16;        // 16-byte chunks per row
+    constexpr int RPLX = 64 / CPRX, RPLY = 64 / CPRY;      // pixel rows per wave-level load
+    constexpr int LX = BKP / RPLX / NW, LY = BKP / RPLY / NW;  // loads per lane per stage
+    constexpr int LPT = LX + LY;
+    constexpr int XBYTES = BKP * RBX, STAGE_BYTES = BKP * (RBX + RBY);
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    static_assert((RBX == 128 || RBX == 256) && (RBY == 128 || RBY == 256), "row size");
+    static_assert(NW % 2 == 0 && LX >= 1 && LY >= 1 && BKP % (RPLX * NW) == 0 && BKP % (RPLY * NW) == 0, "tile config");
+    static_assert(TM >= 1 && TN >= 1 && BKP % 16 == 0 && STAGES >= 2 && (STAGES - 2) * LPT < 64, "tile config");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_b[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int n0 = (tile % a.tiles_n) * BN;        // k origin
+    const int mt = tile / a.tiles_n;               // (tap, channel block)
+    const int tap = mt / a.tiles_per_tap;
+    const int cb = (mt - tap * a.tiles_per_tap) * BM;
+    const int fr = tap / a.S, fs = tap - fr * a.S;
+    const int split = blockIdx.y;
+    const int it0 = split * a.iters_per_split;
+    const int it1 = min(a.iters_total, it0 + a.iters_per_split);
+
+    // swizzle of the 32-byte units of a pixel row (see above); constant per lane over its loads
+    auto swz = [](int row, int rb) { return rb == 256 ? (row & 7) : ((row >> 1) & 3); };
+    // x tile: this lane's row inside a wave-level load, and the logical 8-channel chunk it fetches
+    const int xr = lane / CPRX, xpc = lane % CPRX;
+    const int xlc = ((((xpc >> 1) ^ swz(wave * RPLX + xr, RBX)) << 1) | (xpc & 1));
+    const int xc = min(cb + xlc * 8, a.CP - 8);    // clamp: chunks past the channel count are never stored
+    const int yr = lane / CPRY, ypc = lane % CPRY;
+    const int ylc = ((((ypc >> 1) ^ swz(wave * RPLY + yr, RBY)) << 1) | (ypc & 1));
+    const int yk = min(n0 + ylc * 8, a.KP - 8);
+    const uint16_t* zero_page = reinterpret_cast<const uint16_t*>(g_zero16);
+
+    auto issue = [&](int it, int stage) {
+        uint8_t* sbase = smem_b + stage * STAGE_BYTES;
+        const int pbase = it * BKP;
+#pragma unroll
+        for (int j = 0; j < LX; ++j) {
+            const int pix = pbase + (wave + NW * j) * RPLX + xr;
+            const uint32_t row = fdiv((uint32_t)pix, a.Q);
+            const int q = pix - (int)row * (int)a.Q.d;
+            const uint32_t n = fdiv(row, a.P);
+            const int p = (int)row - (int)n * (int)a.P.d;
+            const int ih = p * a.stride_h - a.pad_h + fr, iw = q * a.stride_w - a.pad_w + fs;
+            const bool ok = pix < a.pixels && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            const uint32_t off = (uint32_t)(((int)n * a.H + ih) * a.W + iw) * (uint32_t)a.xpitch + (uint32_t)xc;
+            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.X + off, zero_page),
+                                             (lds_void_ptr)(sbase + (wave + NW * j) * 1024), 16, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < LY; ++j) {
+            const int pix = pbase + (wave + NW * j) * RPLY + yr;
+            const bool ok = pix < a.pixels;
+            const uint32_t off = (uint32_t)pix * (uint32_t)a.ypitch + (uint32_t)yk;
+            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.DY + off, zero_page),
+                                             (lds_void_ptr)(sbase + XBYTES + (wave + NW * j) * 1024), 16, 0, 0);
+        }
+    };
+
+    // ---- MFMA state ---------------------------------------------------------------------------
+    const int wm = wave % WGM, wn = wave / WGM;
+    // transpose-read geometry: 16-lane group g16, lane t16; source lane t16 points at pixel row (t16 >> 2)
+    // and channel quad (t16 & 3); the result is 4 consecutive pixels for channel 16*(g16 & 1) + t16.
+    const int g16 = lane >> 4, t16 = lane & 15;
+    const int tr_row = (g16 >> 1) * 8 + (t16 >> 2);  // + 4*h + ks*16
+    const int tr_u = (g16 & 1);                       // 16-channel unit inside a 32-channel block
+    const int tr_b = (t16 & 3) * 8;                   // byte inside the unit
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+    auto tr_read = [&](const uint8_t* base, int rb, int ks, int unit0) -> bf16x8 {
+        typedef __attribute__((address_space(3))) s16x4* lds_p;
+        const int r0 = ks * 16 + tr_row, r1 = r0 + 4;
+        const int u = unit0 + tr_u;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(base + r0 * rb + ((u ^ swz(r0, rb)) << 5) + tr_b));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(base + r1 * rb + ((u ^ swz(r1, rb)) << 5) + tr_b));
+        s16x8 r;
+        r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+        r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+        return __builtin_bit_cast(bf16x8, r);
+    };
+    auto compute = [&](int stage) {
+        const uint8_t* sX = smem_b + stage * STAGE_BYTES;
+        const uint8_t* sY = sX + XBYTES;
+#pragma unroll
+        for (int ks = 0; ks < BKP / 16; ++ks) {
+            bf16x8 fx[TM], fy[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) fx[tm] = tr_read(sX, RBX, ks, (wm * WTM + tm * 32) / 16);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) fy[tn] = tr_read(sY, RBY, ks, (wn * WTN + tn * 32) / 16);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tm], fy[tn], acc[tm][tn], 0, 0, 0);
+        }
+    };
+
+    const int nk = it1 - it0;
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < nk) issue(it0 + s, s);
+    for (int kt0 = 0; kt0 < nk; kt0 += STAGES) {
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s) {
+            const int kt = kt0 + s;
+            if (kt < nk) {
+                if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * LPT>();
+                else wait_vmcnt<0>();
+                barrier_nofence();
+                if (kt + STAGES - 1 < nk) issue(it0 + kt + STAGES - 1, (s + STAGES - 1) % STAGES);
+                compute(s);
+            }
+        }
+    }
+
+    // ---- epilogue: lane holds k (column) = lane%32 and rows 8g + 4*(lane/32) + {0..3} = 4 consecutive c
+    float* out = a.OUT + (a.direct ? 0 : (int64_t)split * a.K * a.out_row_pitch);
+    const int climit = a.direct ? a.C : a.CP;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int k = n0 + wn * WTN + tn * 32 + (lane & 31);
+        if (k >= a.K) continue;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int c = cb + wm * WTM + tm * 32 + 8 * g + (lane >> 5) * 4;
+                if (c >= climit) continue;
+                const float v0 = acc[tm][tn][4 * g + 0], v1 = acc[tm][tn][4 * g + 1];
+                const float v2 = acc[tm][tn][4 * g + 2], v3 = acc[tm][tn][4 * g + 3];
+                if (a.direct) {
+                    float* dst = out + ((int64_t)k * a.RS + tap) * a.wpitch + c;
+                    if (a.o_vec && c + 3 < a.C) {
+                        *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
+                    } else {
+                        dst[0] = v0;
+                        if (c + 1 < a.C) dst[1] = v1;
+                        if (c + 2 < a.C) dst[2] = v2;
+                        if (c + 3 < a.C) dst[3] = v3;
+                    }
+                } else {
+                    // CP is a multiple of 8 and c of 4: the four rows stay inside this tap's block
+                    *reinterpret_cast<float4*>(out + (int64_t)k * a.out_row_pitch + tap * a.CP + c) = make_float4(v0, v1, v2, v3);
+                }
+            }
+        }
+    }
+#endif
+}
+
+template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES>
+inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr size_t lds = (size_t)STAGES * BKP * (BM + BN) * 2;
+    static_assert(lds <= 160 * 1024, "LDS capacity");
+    auto kern = k_wgrad_dl<BM, BN, BKP, WGM, WGN, STAGES>;
+    static bool attr_set = false;
+    if (lds > 65536 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n, a.splits), dim3(NT), lds, st, a);
+    return hipSuccess;
+}
+
 }  // namespace pt
+

@@ -221,9 +221,11 @@ class ReconfigModel:
                              self.keep[e])
             B.compact_plan(self.keep[e], edge.n, self.idx[e], self.counts[e:e + 1])
 
-    def compact(self) -> None:
-        """Reads the survivor counts (one synchronising copy), then gathers every tensor."""
-        cnt = self.counts.cpu().numpy()
+    def compact(self, cnt: Optional[np.ndarray] = None) -> None:
+        """Gathers every tensor with the planned index lists.  The survivor counts size the outputs: they
+        are read back here (one synchronising copy) unless the caller already holds them."""
+        if cnt is None:
+            cnt = self.counts.cpu().numpy()
         self.new_counts = cnt
         for i, s in enumerate(self.specs):
             ik = self.idx[s.out_edge] if s.out_edge is not None else None
