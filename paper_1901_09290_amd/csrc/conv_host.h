@@ -47,6 +47,7 @@ inline IgemmArgs make_fwd_args(const pt_conv_desc* d, const uint16_t* x, const u
     a.bpitch = d->w_cpitch; a.Nout = d->K;
     a.DH = d->P; a.DW = d->Q; a.d_hmul = 1; a.d_hadd = 0; a.d_wmul = 1; a.d_wadd = 0; a.dpitch = d->y_cpitch;
     a.d_linear = 1;
+    a.fold = 0; a.TSm = d->S; a.Creal = d->C; a.Cfold = make_fastdiv((uint32_t)a.CredP);
     a.d_vec = (d->y_cpitch % 4 == 0) && (((uintptr_t)y & 7) == 0);
     a.d_vec16 = (d->y_cpitch % 8 == 0) && aligned16(y);
     return a;
@@ -86,6 +87,7 @@ inline IgemmArgs make_bwd_data_args(const pt_conv_desc* d, const BwdClass& c, in
     a.DH = d->H; a.DW = d->W; a.d_hmul = d->stride_h; a.d_hadd = ca; a.d_wmul = d->stride_w; a.d_wadd = cb;
     a.dpitch = d->x_cpitch;
     a.d_linear = (d->stride_h == 1 && d->stride_w == 1);
+    a.fold = 0; a.TSm = c.TS; a.Creal = d->K; a.Cfold = make_fastdiv((uint32_t)kpitch);
     a.d_vec = (d->x_cpitch % 4 == 0) && (((uintptr_t)dx & 7) == 0);
     a.d_vec16 = (d->x_cpitch % 8 == 0) && aligned16(dx);
     return a;
@@ -93,11 +95,21 @@ inline IgemmArgs make_bwd_data_args(const pt_conv_desc* d, const BwdClass& c, in
 
 // Kernel and tile configuration.  `vec`: all operand rows are 16-byte aligned (pitches are multiples of 8
 // elements) - then the direct global->LDS kernel is used, with a tall pixel tile for narrow outputs.
-// Unaligned pitches, and filters with more than 32 taps per launch (the direct kernel keeps one validity
-// bit per tap in a 32-bit mask), take the register-staged kernel.
+// Unaligned pitches, and filters with more than 64 taps per launch (the direct kernel keeps one validity
+// bit per tap in a 64-bit mask), take the register-staged kernel.
 inline hipError_t launch_igemm(IgemmArgs& a, bool vec, hipStream_t st) {
     if (!vec) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, false>(a, st);
-    if (a.TR * a.TS > 32) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, true>(a, st);
+    // Small dense channel counts (an image-like input): fold the S taps of a filter row into one run
+    if (a.CredP < 64 && a.TS > 1 && a.ts_step == 1 && a.apitch == a.CredP && a.bpitch == a.CredP && a.b_ts_stride == 1 &&
+        a.TR * a.TS <= 64) {
+        a.fold = 1;
+        a.TSm = a.TS;
+        a.Creal = a.Cred;
+        a.Cfold = make_fastdiv((uint32_t)a.CredP);
+        a.Cred = a.CredP = a.TS * a.CredP;
+        a.TS = 1;
+    }
+    if (a.TR * a.TSm > 64) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, true>(a, st);
     // 128x128 tiles when they still fill the chip, else 128x64 tiles (more workgroups, deeper pipeline)
     const int64_t tiles128 = ceil_div(a.M, 128) * ceil_div(a.Nout, 128);
     if (a.Nout <= 64 || tiles128 < 160) return launch_igemm_dl_cfg<128, 64, 4, 2, 3>(a, st);
@@ -112,7 +124,7 @@ inline size_t bwd_data_ws(const pt_conv_desc* d) {
 // block, tiles of 64 or 128 channels) is used; otherwise the register-staged kernel (flattened
 // (tap, channel) axis, fixed 128x128 tiles).
 struct WgradPlan {
-    int dl, BM, BN;
+    int dl, fold, BM, BN;
     int splits, iters_total, iters_per_split, tiles_m, tiles_n, tiles_per_tap, CP, KP, Mtot;
     size_t ws_bytes;
 };
@@ -132,11 +144,13 @@ inline WgradPlan plan_wgrad(const pt_conv_desc* d, bool dl) {
     p.KP = (int)round_up(d->K, 8);
     p.Mtot = d->R * d->S * p.CP;
     const int64_t pixels = (int64_t)d->N * d->P * d->Q;
+    p.fold = dl && p.CP < 64 && d->S > 1 && d->x_cpitch == p.CP && d->w_cpitch == p.CP;
     if (dl) {
-        p.BM = pick_tile(p.CP);
+        const int run = p.fold ? d->S * p.CP : p.CP;  // contiguous elements of one tile row block
+        p.BM = pick_tile(run);
         p.BN = pick_tile(p.KP);
-        p.tiles_per_tap = (int)ceil_div(p.CP, p.BM);
-        p.tiles_m = d->R * d->S * p.tiles_per_tap;
+        p.tiles_per_tap = (int)ceil_div(run, p.BM);
+        p.tiles_m = (p.fold ? d->R : d->R * d->S) * p.tiles_per_tap;
         p.tiles_n = (int)ceil_div(d->K, p.BN);
         p.iters_total = (int)ceil_div(pixels, kWgDlBKP);
     } else {
@@ -173,7 +187,7 @@ inline WgradArgs make_wgrad_args(const pt_conv_desc* d, const WgradPlan& p, cons
     a.H = d->H; a.W = d->W; a.xpitch = d->x_cpitch; a.ypitch = d->y_cpitch;
     a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
     a.S = d->S; a.RS = d->R * d->S; a.C = d->C; a.CP = p.CP; a.KP = p.KP; a.Mtot = p.Mtot; a.K = d->K;
-    a.tiles_n = p.tiles_n; a.tiles_m = p.tiles_m; a.tiles_per_tap = p.tiles_per_tap;
+    a.tiles_n = p.tiles_n; a.tiles_m = p.tiles_m; a.tiles_per_tap = p.tiles_per_tap; a.fold = p.fold;
     a.iters_total = p.iters_total; a.iters_per_split = p.iters_per_split; a.splits = p.splits;
     a.wpitch = d->w_cpitch;
     a.direct = p.splits == 1;

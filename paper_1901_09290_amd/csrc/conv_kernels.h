@@ -80,6 +80,12 @@ struct IgemmArgs {
     int tr_step, ts_step;            // source coordinate step per tap index
     int TR, TS;                      // taps of this launch
     int Cred, CredP;                 // reduction channels, and rounded up to 8
+    // Folded small-channel mode (direct kernel only): when a pixel holds fewer than 64 padded channels and
+    // pixels are dense (pitch == padded channels), the S taps of a filter row are one contiguous run of
+    // S*Cfold elements in both operands, so a reduction step covers several taps.  Then TS == 1,
+    // Cred == CredP == S*Cfold, TSm == S taps per row in the validity mask, Creal real channels per tap.
+    int fold, TSm, Creal;
+    FastDiv Cfold;
     int b_tap0, b_tr_stride, b_ts_stride, b_taps;
     int bpitch, Nout;
     int DH, DW, d_hmul, d_hadd, d_wmul, d_wadd, dpitch;  // destination pixel = (i*d_hmul+d_hadd, j*d_wmul+d_wadd)
@@ -377,7 +383,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 
     // per-lane row constants: element offset of tap (0,0) + chunk, and a bit per tap: tap inside the image.
     // Rows past the end of the problem are clamped to the last row: their results are never stored.
-    uint32_t a_off[LA], a_mask[LA];
+    uint32_t a_off[LA];
+    uint64_t a_mask[LA];  // bit (r * TSm + s): tap (r, s) of this row lies inside the image
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
         const int m = min(m0 + (wave + NW * j) * 8 + lrow, a.M - 1);
@@ -385,12 +392,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
         const uint32_t n = fdiv(row, a.gH), gi = row - n * a.gH.d;
         const int h0 = (int)gi * a.h_mul + a.h_add, w0 = (int)gj * a.w_mul + a.w_add;
         a_off[j] = (uint32_t)(((int)n * a.srcH + h0) * a.srcW + w0) * (uint32_t)a.apitch + (uint32_t)kvoff;
-        uint32_t mask = 0;
+        uint64_t mask = 0;
         for (int r = 0; r < a.TR; ++r) {
             const bool hok = (unsigned)(h0 + r * a.tr_step) < (unsigned)a.srcH;
-            for (int t = 0; t < a.TS; ++t) {
+            for (int t = 0; t < a.TSm; ++t) {
                 const bool ok = hok && (unsigned)(w0 + t * a.ts_step) < (unsigned)a.srcW;
-                mask |= (ok ? 1u : 0u) << (r * a.TS + t);
+                mask |= (uint64_t)(ok ? 1u : 0u) << (r * a.TSm + t);
             }
         }
         a_mask[j] = mask;
@@ -409,12 +416,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 
     auto issue = [&](int stage) {
         uint8_t* sbase = smem_b + stage * STAGE_BYTES;
-        const int tapbit = i_tr * a.TS + i_ts;
         // Element offsets are formed in 32-bit wrapping arithmetic (row constant + step delta): for a tap inside
         // the image the sum is the true non-negative offset even when either part alone is "negative".
         const uint32_t sa = (uint32_t)((i_tr * a.tr_step * a.srcW + i_ts * a.ts_step) * a.apitch + i_cb);
         const uint32_t sb = (uint32_t)((a.b_tap0 + i_tr * a.b_tr_stride + i_ts * a.b_ts_stride) * a.bpitch + i_cb);
         const bool chunk_ok = !RAGGED || (i_cb + kvoff < a.Cred);
+        // which tap this lane's chunk belongs to: the step's tap, or in folded mode the tap inside the run
+        const int tapbit = i_tr * a.TSm + (a.fold ? (int)fdiv((uint32_t)(i_cb + kvoff), a.Cfold) : i_ts);
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
             const bool ok = chunk_ok && ((a_mask[j] >> tapbit) & 1u);
@@ -439,8 +447,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
     // zero the channel tail of this lane's own vectors of `stage` (their data has landed for this wave)
     auto fixup = [&](int stage) {
         if constexpr (RAGGED) {
-            const int nvalid = a.Cred - (c_cb + kvoff);
-            if (nvalid > 0 && nvalid < 8) {
+            const int cpos = c_cb + kvoff;
+            const int nvalid = a.fold ? a.Creal - (cpos - (int)fdiv((uint32_t)cpos, a.Cfold) * (int)a.Cfold.d) : a.Cred - cpos;
+            if (cpos < a.Cred && nvalid < 8) {
                 const Mask8 k = make_mask8(nvalid);
                 uint8_t* sbase = smem_b + stage * STAGE_BYTES + lane * 16;
 #pragma unroll
@@ -592,7 +601,8 @@ inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
     constexpr size_t lds_pipe = (size_t)STAGES * (BM + BN) * 128, lds_epi = (size_t)BM * (BN + 8) * 2;
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
     static_assert(lds <= 160 * 1024, "LDS capacity");
-    const bool ragged = (a.Cred % 64) != 0;  // last channel block of a tap is short and/or has a masked tail
+    // last channel block of a tap is short and/or some chunk has a masked tail
+    const bool ragged = (a.Cred % 64) != 0 || (a.fold && a.Creal % 8 != 0);
     const void* kern = ragged ? reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true>)
                               : reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false>);
     static bool attr_set[2] = {false, false};  // one-time opt-in to more than 64 KiB of dynamic LDS
@@ -628,6 +638,7 @@ struct WgradArgs {
     int tiles_m;         // tiles along (tap, c)
     int tiles_per_tap;   // direct kernel: channel blocks per filter tap
     int KP;              // K rounded up to 8
+    int fold;            // direct kernel: a tile row block spans the S taps of one filter row (dense small-C pixels)
     int iters_total, iters_per_split, splits;
     int out_row_pitch;   // elements between consecutive k in the partial buffer (Mtot)
     int wpitch;
@@ -859,9 +870,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
     const int n0 = (tile % a.tiles_n) * BN;        // k origin
     const int mt = tile / a.tiles_n;               // (tap, channel block)
-    const int tap = mt / a.tiles_per_tap;
-    const int cb = (mt - tap * a.tiles_per_tap) * BM;
-    const int fr = tap / a.S, fs = tap - fr * a.S;
+    // tile row block: one filter tap (CP channels), or in folded mode one filter row (S*CP contiguous elements)
+    const int tb = mt / a.tiles_per_tap;
+    const int cb = (mt - tb * a.tiles_per_tap) * BM;
+    const int run = a.fold ? a.S * a.CP : a.CP;
+    const int fr = a.fold ? tb : tb / a.S;
     const int split = blockIdx.y;
     const int it0 = split * a.iters_per_split;
     const int it1 = min(a.iters_total, it0 + a.iters_per_split);
@@ -871,7 +884,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
     // x tile: this lane's row inside a wave-level load, and the logical 8-channel chunk it fetches
     const int xr = lane / CPRX, xpc = lane % CPRX;
     const int xlc = ((((xpc >> 1) ^ swz(wave * RPLX + xr, RBX)) << 1) | (xpc & 1));
-    const int xc = min(cb + xlc * 8, a.CP - 8);    // clamp: chunks past the channel count are never stored
+    const int xc = min(cb + xlc * 8, run - 8);     // clamp: chunks past the run are never stored
+    const int fs = a.fold ? xc / a.CP : tb - fr * a.S;   // filter column of this lane's chunk
+    const int fs_addr = a.fold ? 0 : fs;           // folded: the column offset is part of xc
     const int yr = lane / CPRY, ypc = lane % CPRY;
     const int ylc = ((((ypc >> 1) ^ swz(wave * RPLY + yr, RBY)) << 1) | (ypc & 1));
     const int yk = min(n0 + ylc * 8, a.KP - 8);
@@ -889,7 +904,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
             const int p = (int)row - (int)n * (int)a.P.d;
             const int ih = p * a.stride_h - a.pad_h + fr, iw = q * a.stride_w - a.pad_w + fs;
             const bool ok = pix < a.pixels && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-            const uint32_t off = (uint32_t)(((int)n * a.H + ih) * a.W + iw) * (uint32_t)a.xpitch + (uint32_t)xc;
+            const uint32_t off =
+                (uint32_t)(((int)n * a.H + ih) * a.W + (iw - fs + fs_addr)) * (uint32_t)a.xpitch + (uint32_t)xc;
             __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.X + off, zero_page),
                                              (lds_void_ptr)(sbase + (wave + NW * j) * 1024), 16, 0, 0);
         }
@@ -968,7 +984,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
 
     // ---- epilogue: lane holds k (column) = lane%32 and rows 8g + 4*(lane/32) + {0..3} = 4 consecutive c
     float* out = a.OUT + (a.direct ? 0 : (int64_t)split * a.K * a.out_row_pitch);
-    const int climit = a.direct ? a.C : a.CP;
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int k = n0 + wn * WTN + tn * 32 + (lane & 31);
@@ -977,12 +992,17 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
         for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int c = cb + wm * WTM + tm * 32 + 8 * g + (lane >> 5) * 4;
-                if (c >= climit) continue;
+                const int cr = cb + wm * WTM + tm * 32 + 8 * g + (lane >> 5) * 4;  // row inside the run
+                if (cr >= run) continue;
+                // CP is a multiple of 8 and cr of 4: the four rows share one tap
+                const int ts = a.fold ? cr / a.CP : 0;
+                const int c = cr - ts * a.CP;
+                const int tapi = a.fold ? tb * a.S + ts : tb;
                 const float v0 = acc[tm][tn][4 * g + 0], v1 = acc[tm][tn][4 * g + 1];
                 const float v2 = acc[tm][tn][4 * g + 2], v3 = acc[tm][tn][4 * g + 3];
                 if (a.direct) {
-                    float* dst = out + ((int64_t)k * a.RS + tap) * a.wpitch + c;
+                    if (c >= a.C) continue;
+                    float* dst = out + ((int64_t)k * a.RS + tapi) * a.wpitch + c;
                     if (a.o_vec && c + 3 < a.C) {
                         *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
                     } else {
@@ -992,8 +1012,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
                         if (c + 3 < a.C) dst[3] = v3;
                     }
                 } else {
-                    // CP is a multiple of 8 and c of 4: the four rows stay inside this tap's block
-                    *reinterpret_cast<float4*>(out + (int64_t)k * a.out_row_pitch + tap * a.CP + c) = make_float4(v0, v1, v2, v3);
+                    *reinterpret_cast<float4*>(out + (int64_t)k * a.out_row_pitch + tapi * a.CP + c) = make_float4(v0, v1, v2, v3);
                 }
             }
         }

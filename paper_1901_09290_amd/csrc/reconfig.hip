@@ -89,8 +89,8 @@ __global__ void k_compact_vector(const T* __restrict__ v, const int* __restrict_
     if (j < n_keep) out[j] = v[idx[j]];
 }
 
-// Activation gather along the innermost axis.  One thread produces 8 consecutive output channels of
-// one pixel (a 16-byte store when aligned).
+// Activation gather along the innermost axis, element-wise form (any pitch / alignment): one thread
+// produces 8 consecutive output channels of one pixel.
 __global__ void k_compact_nhwc(const uint16_t* __restrict__ x, int64_t pixels, int x_cpitch,
                                const int* __restrict__ idx, int Cp, uint16_t* __restrict__ out, int out_cpitch,
                                int vec_ok) {
@@ -115,6 +115,57 @@ __global__ void k_compact_nhwc(const uint16_t* __restrict__ x, int64_t pixels, i
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             if (c0 + e < Cp) dst[e] = v[e];
+    }
+}
+
+// Activation gather, streaming form (16-byte aligned rows on both sides).  A workgroup copies a run of
+// whole pixel rows into LDS with 16-byte loads - every source byte is read once, fully coalesced - then
+// every thread assembles 8 output channels from LDS with its eight channel indices held in registers
+// (a thread keeps the same output vector for all pixels it visits) and writes one 16-byte store.
+// Channels of the last vector past Cp are not written.
+constexpr int kGatherThreads = 256;
+__global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const uint16_t* __restrict__ x, int64_t pixels,
+                                                                      int x_cpitch, const int* __restrict__ idx, int Cp,
+                                                                      uint16_t* __restrict__ out, int out_cpitch,
+                                                                      int pix_per_chunk) {
+    extern __shared__ __attribute__((aligned(16))) uint16_t srow[];
+    const int tid = threadIdx.x;
+    const int nvec = (Cp + 7) >> 3;
+    const int ppb = kGatherThreads / nvec;       // pixels gathered per pass (nvec <= 256)
+    const int pp = tid / nvec, v = tid - pp * nvec;
+    const bool active = pp < ppb;
+    int id[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) id[e] = (active && v * 8 + e < Cp) ? idx[v * 8 + e] : 0;
+    const int nlast = Cp - v * 8;                // valid channels of this thread's vector (>= 8: all)
+    const int row16 = x_cpitch >> 3;             // 16-byte units per source row
+    const int64_t nchunks = (pixels + pix_per_chunk - 1) / pix_per_chunk;
+    for (int64_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
+        const int64_t p0 = ch * pix_per_chunk;
+        const int np = (int)min((int64_t)pix_per_chunk, pixels - p0);
+        const uint4* src = reinterpret_cast<const uint4*>(x + p0 * x_cpitch);
+        uint4* dstl = reinterpret_cast<uint4*>(srow);
+        const int n16 = np * row16;
+        for (int i = tid; i < n16; i += kGatherThreads) dstl[i] = src[i];
+        __syncthreads();
+        if (active) {
+            for (int p = pp; p < np; p += ppb) {
+                const uint16_t* r = srow + (size_t)p * x_cpitch;
+                uint4 o;
+                o.x = r[id[0]] | ((uint32_t)r[id[1]] << 16);
+                o.y = r[id[2]] | ((uint32_t)r[id[3]] << 16);
+                o.z = r[id[4]] | ((uint32_t)r[id[5]] << 16);
+                o.w = r[id[6]] | ((uint32_t)r[id[7]] << 16);
+                uint16_t* dst = out + (p0 + p) * (int64_t)out_cpitch + v * 8;
+                if (nlast >= 8) {
+                    *reinterpret_cast<uint4*>(dst) = o;
+                } else {
+                    const uint16_t* e = reinterpret_cast<const uint16_t*>(&o);
+                    for (int k = 0; k < nlast; ++k) dst[k] = e[k];
+                }
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -197,11 +248,26 @@ extern "C" int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C,
     if (pixels < 0 || C <= 0 || Cp <= 0 || Cp > C || x_cpitch < C || out_cpitch < Cp) return PT_ERR_SHAPE;
     if (pixels == 0) return PT_OK;
     if (!x || !idx || !out) return PT_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    const bool rows_aligned = (x_cpitch % 8 == 0) && (out_cpitch % 8 == 0) && (((uintptr_t)x & 15) == 0) &&
+                              (((uintptr_t)out & 15) == 0);
+    if (rows_aligned && (Cp + 7) / 8 <= kGatherThreads && (size_t)x_cpitch * 2 <= 32 * 1024) {
+        // ~32 KiB of pixel rows per LDS chunk, a multiple of the pixels gathered per pass
+        const int nvec = (Cp + 7) / 8, ppb = kGatherThreads / nvec;
+        int ppc = (int)((32 * 1024) / ((size_t)x_cpitch * 2));
+        if (ppc > ppb) ppc = ppc / ppb * ppb;
+        if (ppc < 1) ppc = 1;
+        const int64_t nchunks = ceil_div(pixels, ppc);
+        const unsigned grid = (unsigned)(nchunks < 256 * 8 ? nchunks : 256 * 8);
+        hipLaunchKernelGGL(k_compact_nhwc_lds, dim3(grid), dim3(kGatherThreads), (size_t)ppc * x_cpitch * 2, st, x, pixels,
+                           x_cpitch, idx, Cp, out, out_cpitch, ppc);
+        return launch_status();
+    }
     const int64_t work = pixels * ((Cp + 7) / 8);
     const int64_t nblk = ceil_div(work, 256);
     if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
     const int vec_ok = (out_cpitch % 8 == 0) && (((uintptr_t)out & 15) == 0);
-    hipLaunchKernelGGL(k_compact_nhwc, dim3((unsigned)nblk), dim3(256), 0, (hipStream_t)stream, x, pixels, x_cpitch, idx,
-                       Cp, out, out_cpitch, vec_ok);
+    hipLaunchKernelGGL(k_compact_nhwc, dim3((unsigned)nblk), dim3(256), 0, st, x, pixels, x_cpitch, idx, Cp, out,
+                       out_cpitch, vec_ok);
     return launch_status();
 }

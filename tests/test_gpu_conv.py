@@ -68,6 +68,11 @@ RAGGED = [
     ((2, 10, 10, 37, 51, 3, 1, 1), True),
     ((2, 12, 12, 203, 77, 1, 1, 0), True),
     ((1, 9, 9, 19, 131, 3, 2, 1), True),
+    ((2, 18, 18, 3, 16, 7, 2, 3), True),   # image-like 3-channel input, pitch 8: filter rows folded into one run
+    ((2, 30, 30, 3, 28, 7, 2, 3), True),
+    ((3, 13, 13, 5, 24, 3, 1, 1), True),
+    ((2, 11, 11, 12, 40, 5, 1, 2), True),  # pitch 16 with 12 real channels: a masked chunk inside every tap
+    ((2, 9, 9, 32, 48, 2, 1, 0), True),    # folded run of exactly 64 elements
     # same shapes stored dense: pitches are odd, element-wise path
     ((2, 10, 10, 37, 51, 3, 1, 1), False),
     ((1, 9, 9, 19, 131, 3, 2, 1), False),
