@@ -207,7 +207,7 @@ def main():
         L = net.layers
         fam[tag] = {
             "fwd": timed(lambda: [l.fwd(net.ws) for l in L], 3),
-            "bwd_data": timed(lambda: [l.bwd_data(net.ws) for l in L], 3),
+            "bwd_data": timed(lambda: [l.bwd_data_crsk() for l in L], 3),
             "bwd_weight": timed(lambda: [l.bwd_weight(net.ws) for l in L], 3),
             "group_norms": timed(lambda: B.group_norms_batched(net.norm_jobs, net.ws_norms), 5),
             "group_lasso_grad": timed(lambda: B.group_lasso_grad_batched(net.lasso_jobs, LAMBDA), 5),
@@ -226,11 +226,23 @@ def main():
                  "bwd_weight": "k_wgrad_dl + k_wgrad_reduce (conv_bwd_weight launches)"}
     n_launch = sum(1 for net in (full, pruned) for l in net.layers if not (dom == "bwd_data" and l.dx is None))
     dom_flops = fl["full"][dom] + fl["pruned"][dom]
-    dom_rate = dom_flops / (tot[dom] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": kernel_of[dom], "achieved": round(dom_rate, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(dom_rate / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                "avg_launch_ms": round(tot[dom] / n_launch, 5), "flops_per_launch": dom_flops / n_launch,
-                "launches_per_step": n_launch}
+    dom_bytes = by["full"][dom] + by["pruned"][dom]
+    dom_s = tot[dom] * 1e-3
+    # which roof bounds this family on this workload: time at the HBM peak vs time at the bf16 MFMA peak
+    t_hbm, t_mfma = dom_bytes / (PEAK_HBM_GBS * 1e9), dom_flops / (PEAK_BF16_TFLOPS * 1e12)
+    # per-layer roof: a layer cannot finish before max(its bytes at the HBM peak, its flops at the MFMA peak)
+    t_roof = sum(max(conv_bytes(l.spec, dom) / (PEAK_HBM_GBS * 1e9), l.spec.flops / (PEAK_BF16_TFLOPS * 1e12))
+                 for net in (full, pruned) for l in net.layers if not (dom == "bwd_data" and l.dx is None))
+    if t_hbm >= t_mfma:
+        ach, peak, unit, bound = dom_bytes / dom_s / 1e9, PEAK_HBM_GBS, "GB/s", "hbm"
+    else:
+        ach, peak, unit, bound = dom_flops / dom_s / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s", "mfma"
+    roofline = {"bound": bound, "kernel": kernel_of[dom], "achieved": round(ach, 2), "peak": peak, "unit": unit,
+                "frac": round(ach / peak, 4), "traffic": None,
+                "avg_launch_ms": round(tot[dom] / n_launch, 5), "launches_per_step": n_launch,
+                "bytes_per_launch": dom_bytes / n_launch, "flops_per_launch": dom_flops / n_launch,
+                "tflops": round(dom_flops / dom_s / 1e12, 2), "frac_mfma_peak": round(dom_flops / dom_s / 1e12 / PEAK_BF16_TFLOPS, 4),
+                "frac_of_per_layer_roof": round(t_roof / dom_s, 4)}
 
     ab = rmodel.algorithmic_bytes()
     sweep_bytes = sum(ab.values())
@@ -289,7 +301,8 @@ def main():
                         if c == "bwd_data" and l.dx is None:
                             row += f" {'-':>8s} {'':>5s} {'':>5s} |"
                             continue
-                        t = timed(lambda l=l, c=c: getattr(l, c)(net.ws), 3)
+                        t = timed((lambda l=l: l.bwd_data_crsk()) if c == "bwd_data" else
+                                  (lambda l=l, c=c: getattr(l, c)(net.ws)), 3)
                         row += (f" {t * 1e3:8.1f} {l.spec.flops / (t * 1e-3) / 1e12:5.0f} "
                                 f"{conv_bytes(l.spec, c) / (t * 1e-3) / 1e9:5.0f} |")
                     f.write(row + "\n")

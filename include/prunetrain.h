@@ -83,6 +83,21 @@ int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w,
 int32_t pt_conv_bwd_data(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* w, uint16_t* dx, void* ws,
                          size_t ws_bytes, void* stream);
 
+/* The input-gradient GEMM reduces over k, so it reads the filter bank with k innermost:
+ *   wt[c][r][s][k] = w[k][r][s][c], bf16, k pitch = K rounded up to a multiple of 8 (padding written as 0).
+ * pt_conv_bwd_data builds this copy in its workspace on every call.  A training step can instead convert
+ * all layers once per iteration (the weights change once per iteration) with pt_weights_to_crsk_batched -
+ * `layers` is a HOST array whose pointers are device pointers, wt 16-byte aligned - and call
+ * pt_conv_bwd_data_crsk, which has the semantics of pt_conv_bwd_data and needs no workspace. */
+typedef struct pt_layer_crsk {
+    const uint16_t* w; /* [K][RS][w_cpitch] bf16 */
+    uint16_t* wt;      /* [C][RS][round_up(K,8)] bf16 */
+    int32_t K, RS, C, w_cpitch;
+} pt_layer_crsk;
+int32_t pt_weights_to_crsk_batched(const pt_layer_crsk* layers, int32_t n, void* stream);
+int32_t pt_conv_bwd_data_crsk(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* wt, uint16_t* dx,
+                              void* stream);
+
 /* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c]  (Eq. 4;
  * plain sum over the mini-batch).  x, dy bf16; dw fp32 [K][R][S][w_cpitch].  The reduction is split
  * over workgroups into ws and combined in a fixed order: results are run-to-run identical. */
@@ -164,6 +179,52 @@ int32_t pt_compact_weights(const float* w, int32_t K, int32_t RS, int32_t C, int
  * elem_bytes in {1, 2, 4, 8}. n_keep may be 0. */
 int32_t pt_compact_vector(const void* v, int32_t elem_bytes, const int32_t* idx, int32_t n_keep, void* out,
                           void* stream);
+
+/* Multi-job forms of the four small reconfiguration steps.  A network has dozens of layers and channel
+ * edges and each step on one of them is far below a launch's fixed cost, so whole-network tables go into
+ * a handful of launches.  Every `jobs` / `edges` array is a HOST array whose pointers are device
+ * pointers (except the member lists, which are host arrays of device pointers as in pt_reconcile_edge);
+ * per job the semantics, limits and error rules are those of the single calls above.  Jobs of one call
+ * must not write overlapping memory. */
+typedef struct pt_norm_mask {
+    const float* norms; /* [n] */
+    uint8_t* zero;      /* [n] */
+    int32_t n;
+    int32_t reserved;
+} pt_norm_mask;
+int32_t pt_zero_groups_batched(const pt_norm_mask* jobs, int32_t n_jobs, float thr, void* stream);
+
+/* pt_reconcile_edge followed by pt_compact_plan on the same edge, one workgroup per edge. */
+typedef struct pt_edge_plan {
+    const uint8_t* const* producer_zero; /* host array of n_prod device pointers */
+    const uint8_t* const* consumer_zero; /* host array of n_cons device pointers */
+    int32_t n_prod, n_cons;              /* n_prod + n_cons in [1, 64] */
+    int32_t n;                           /* channels on this edge */
+    int32_t reserved;
+    uint8_t* keep;                       /* [n] */
+    int32_t* idx;                        /* [n] */
+    int32_t* n_keep_dev;                 /* device scalar */
+} pt_edge_plan;
+int32_t pt_reconcile_plan_batched(const pt_edge_plan* edges, int32_t n_edges, void* stream);
+
+typedef struct pt_gather_vector {
+    const void* v;
+    const int32_t* idx;
+    void* out;
+    int32_t n_keep;
+    int32_t elem_bytes; /* 1, 2, 4 or 8 */
+} pt_gather_vector;
+int32_t pt_compact_vector_batched(const pt_gather_vector* jobs, int32_t n_jobs, void* stream);
+
+typedef struct pt_gather_weights {
+    const float* w;      /* [K][RS][w_cpitch] */
+    const int32_t* idxK; /* NULL = identity */
+    const int32_t* idxC; /* NULL = identity */
+    float* w_out;        /* [Kp][RS][out_cpitch] */
+    int32_t K, RS, C, w_cpitch, Kp, Cp, out_cpitch;
+    int32_t reserved;
+} pt_gather_weights;
+int32_t pt_compact_weights_batched(const pt_gather_weights* jobs, int32_t n_jobs, void* stream);
 
 /* out[pix][c'] = x[pix][idx[c']] for bf16 NHWC activations with `pixels` = N*H*W rows. */
 int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const int32_t* idx,

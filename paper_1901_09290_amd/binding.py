@@ -27,6 +27,8 @@ EXPORTS = [
     "pt_group_norms_batched_workspace_bytes", "pt_group_norms_batched", "pt_group_lasso_grad_batched",
     "pt_zero_groups", "pt_reconcile_edge", "pt_compact_plan",
     "pt_compact_weights", "pt_compact_vector", "pt_compact_nhwc",
+    "pt_weights_to_crsk_batched", "pt_conv_bwd_data_crsk",
+    "pt_zero_groups_batched", "pt_reconcile_plan_batched", "pt_compact_vector_batched", "pt_compact_weights_batched",
 ]
 
 
@@ -52,6 +54,31 @@ class LayerLasso(C.Structure):
     _fields_ = [("w", C.c_void_p), ("out_norm", C.c_void_p), ("in_norm", C.c_void_p), ("dw", C.c_void_p),
                 ("K", C.c_int32), ("RS", C.c_int32), ("C", C.c_int32), ("w_cpitch", C.c_int32),
                 ("flags", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class LayerCrsk(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("wt", C.c_void_p), ("K", C.c_int32), ("RS", C.c_int32), ("C", C.c_int32),
+                ("w_cpitch", C.c_int32)]
+
+
+class NormMask(C.Structure):
+    _fields_ = [("norms", C.c_void_p), ("zero", C.c_void_p), ("n", C.c_int32), ("reserved", C.c_int32)]
+
+
+class EdgePlan(C.Structure):
+    _fields_ = [("producer_zero", C.POINTER(C.c_void_p)), ("consumer_zero", C.POINTER(C.c_void_p)),
+                ("n_prod", C.c_int32), ("n_cons", C.c_int32), ("n", C.c_int32), ("reserved", C.c_int32),
+                ("keep", C.c_void_p), ("idx", C.c_void_p), ("n_keep_dev", C.c_void_p)]
+
+
+class GatherVector(C.Structure):
+    _fields_ = [("v", C.c_void_p), ("idx", C.c_void_p), ("out", C.c_void_p), ("n_keep", C.c_int32),
+                ("elem_bytes", C.c_int32)]
+
+
+class GatherWeights(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("idxK", C.c_void_p), ("idxC", C.c_void_p), ("w_out", C.c_void_p)] + [
+        (n, C.c_int32) for n in ("K", "RS", "C", "w_cpitch", "Kp", "Cp", "out_cpitch", "reserved")]
 
 
 def lib() -> C.CDLL:
@@ -84,6 +111,12 @@ def lib() -> C.CDLL:
             "pt_compact_weights": [vp, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp],
             "pt_compact_vector": [vp, i32, vp, i32, vp, vp],
             "pt_compact_nhwc": [vp, i64, i32, i32, vp, i32, vp, i32, vp],
+            "pt_weights_to_crsk_batched": [C.POINTER(LayerCrsk), i32, vp],
+            "pt_conv_bwd_data_crsk": [dp, vp, vp, vp, vp],
+            "pt_zero_groups_batched": [C.POINTER(NormMask), i32, f32, vp],
+            "pt_reconcile_plan_batched": [C.POINTER(EdgePlan), i32, vp],
+            "pt_compact_vector_batched": [C.POINTER(GatherVector), i32, vp],
+            "pt_compact_weights_batched": [C.POINTER(GatherWeights), i32, vp],
         }
         for name, args in sig.items():
             fn = getattr(_lib, name)
@@ -239,3 +272,60 @@ def compact_vector(v, elem_bytes: int, idx, n_keep: int, out, stream=None) -> No
 def compact_nhwc(x, pixels: int, Cc: int, x_cpitch: int, idx, Cp: int, out, out_cpitch: int, stream=None) -> None:
     _ck("pt_compact_nhwc", lib().pt_compact_nhwc(_ptr(x), pixels, Cc, x_cpitch, _ptr(idx), Cp, _ptr(out), out_cpitch,
                                                  _stream(stream)))
+
+
+# ---- multi-job forms ------------------------------------------------------------------------------ #
+def norm_mask(norms, n: int, zero) -> NormMask:
+    return NormMask(_ptr(norms), _ptr(zero), n, 0)
+
+
+def zero_groups_batched(jobs, thr: float, stream=None) -> None:
+    arr = _array(jobs, NormMask)
+    _ck("pt_zero_groups_batched", lib().pt_zero_groups_batched(arr, len(jobs), thr, _stream(stream)))
+
+
+def edge_plan(producer_zero: Sequence, consumer_zero: Sequence, n: int, keep, idx, n_keep_dev) -> EdgePlan:
+    """The member pointer arrays are host arrays owned by the returned struct (kept alive with it)."""
+    pa = (C.c_void_p * max(1, len(producer_zero)))(*[t.data_ptr() for t in producer_zero])
+    ca = (C.c_void_p * max(1, len(consumer_zero)))(*[t.data_ptr() for t in consumer_zero])
+    e = EdgePlan(C.cast(pa, C.POINTER(C.c_void_p)) if len(producer_zero) else None,
+                 C.cast(ca, C.POINTER(C.c_void_p)) if len(consumer_zero) else None,
+                 len(producer_zero), len(consumer_zero), n, 0, _ptr(keep), _ptr(idx), _ptr(n_keep_dev))
+    e._keepalive = (pa, ca)
+    return e
+
+
+def reconcile_plan_batched(edges, stream=None) -> None:
+    arr = _array(edges, EdgePlan)
+    _ck("pt_reconcile_plan_batched", lib().pt_reconcile_plan_batched(arr, len(edges), _stream(stream)))
+
+
+def gather_vector(v, elem_bytes: int, idx, n_keep: int, out) -> GatherVector:
+    return GatherVector(_ptr(v), _ptr(idx), _ptr(out), n_keep, elem_bytes)
+
+
+def compact_vector_batched(jobs, stream=None) -> None:
+    arr = _array(jobs, GatherVector)
+    _ck("pt_compact_vector_batched", lib().pt_compact_vector_batched(arr, len(jobs), _stream(stream)))
+
+
+def gather_weights(w, K, RS, Cc, w_cpitch, idxK, Kp, idxC, Cp, w_out, out_cpitch) -> GatherWeights:
+    return GatherWeights(_ptr(w), _ptr(idxK), _ptr(idxC), _ptr(w_out), K, RS, Cc, w_cpitch, Kp, Cp, out_cpitch, 0)
+
+
+def compact_weights_batched(jobs, stream=None) -> None:
+    arr = _array(jobs, GatherWeights)
+    _ck("pt_compact_weights_batched", lib().pt_compact_weights_batched(arr, len(jobs), _stream(stream)))
+
+
+def layer_crsk(w, wt, K, RS, Cc, w_cpitch) -> LayerCrsk:
+    return LayerCrsk(_ptr(w), _ptr(wt), K, RS, Cc, w_cpitch)
+
+
+def weights_to_crsk_batched(layers, stream=None) -> None:
+    arr = _array(layers, LayerCrsk)
+    _ck("pt_weights_to_crsk_batched", lib().pt_weights_to_crsk_batched(arr, len(layers), _stream(stream)))
+
+
+def conv_bwd_data_crsk(d: ConvDesc, dy, wt, dx, stream=None) -> None:
+    _ck("pt_conv_bwd_data_crsk", lib().pt_conv_bwd_data_crsk(C.byref(d), _ptr(dy), _ptr(wt), _ptr(dx), _stream(stream)))

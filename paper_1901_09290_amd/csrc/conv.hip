@@ -44,6 +44,43 @@ __global__ void k_transpose_w(const uint16_t* __restrict__ w, int K, int RS, int
     }
 }
 
+// The same transposition for many layers in one launch (descriptors in the kernel arguments).
+constexpr int kMaxTransposeJobs = 64;
+struct TransposeJob {
+    const uint16_t* w;
+    uint16_t* wt;
+    int K, RS, C, wpitch, kpitch, blk0, nbx, nby;
+};
+struct TransposeJobs {
+    TransposeJob j[kMaxTransposeJobs];
+    int n;
+};
+__global__ __launch_bounds__(256) void k_transpose_w_multi(const TransposeJobs jobs) {
+    __shared__ uint16_t tile[32][33];
+    int lo = 0, hi = jobs.n - 1;  // last job whose blk0 <= blockIdx.x
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs.j[mid].blk0 <= (int)blockIdx.x) lo = mid;
+        else hi = mid - 1;
+    }
+    const TransposeJob& jb = jobs.j[lo];
+    int b = blockIdx.x - jb.blk0;
+    const int bx = b % jb.nbx;
+    b /= jb.nbx;
+    const int by = b % jb.nby, rs = b / jb.nby;
+    const int k0 = by * 32, c0 = bx * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int i = ty; i < 32; i += 8) {
+        const int k = k0 + i, c = c0 + tx;
+        tile[i][tx] = (k < jb.K && c < jb.C) ? jb.w[((int64_t)k * jb.RS + rs) * jb.wpitch + c] : (uint16_t)0;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int c = c0 + i, k = k0 + tx;
+        if (c < jb.C && k < jb.kpitch) jb.wt[((int64_t)c * jb.RS + rs) * jb.kpitch + k] = tile[tx][i];
+    }
+}
+
 // Zero the destination pixels of a stride-parity class that no output pixel reaches.  One thread clears
 // 8 channels (one 16-byte store when the rows are 16-byte aligned).
 __global__ void k_zero_class(uint16_t* __restrict__ D, int64_t pixels, int gH, int gW, int DH, int DW, int d_hmul,
@@ -152,21 +189,10 @@ extern "C" int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const u
     return hip_status(launch_igemm(a, vec, (hipStream_t)stream));
 }
 
-extern "C" int32_t pt_conv_bwd_data(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* w, uint16_t* dx,
-                                    void* ws, size_t ws_bytes, void* stream) {
-    int32_t rc = check_desc(d);
-    if (rc != PT_OK) return rc;
-    if (!dy || !w || !dx || !ws) return PT_ERR_NULL;
-    if (ws_bytes < bwd_data_ws(d)) return PT_ERR_WORKSPACE;
-    if (!aligned16(ws)) return PT_ERR_SHAPE;
-    hipStream_t st = (hipStream_t)stream;
-    const int RS = d->R * d->S;
-    const int kpitch = (int)round_up(d->K, 8);
-    uint16_t* wt = (uint16_t*)ws;
-    hipLaunchKernelGGL(k_transpose_w, dim3((unsigned)ceil_div(d->C, 32), (unsigned)ceil_div(kpitch, 32), RS), dim3(256),
-                       0, st, w, d->K, RS, d->C, d->w_cpitch, wt, kpitch);
-    rc = launch_status();
-    if (rc != PT_OK) return rc;
+// Input gradient from weights already in [C][RS][round_up(K,8)] order: one implicit GEMM per stride-parity class.
+static int32_t bwd_data_classes(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* wt, uint16_t* dx,
+                                hipStream_t st) {
+    int32_t rc = PT_OK;
     for (int ca = 0; ca < d->stride_h; ++ca) {
         for (int cb = 0; cb < d->stride_w; ++cb) {
             BwdClass c = bwd_data_class(d, ca, cb);
@@ -187,6 +213,72 @@ extern "C" int32_t pt_conv_bwd_data(const pt_conv_desc* d, const uint16_t* dy, c
         }
     }
     return PT_OK;
+}
+
+extern "C" int32_t pt_conv_bwd_data(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* w, uint16_t* dx,
+                                    void* ws, size_t ws_bytes, void* stream) {
+    int32_t rc = check_desc(d);
+    if (rc != PT_OK) return rc;
+    if (!dy || !w || !dx || !ws) return PT_ERR_NULL;
+    if (ws_bytes < bwd_data_ws(d)) return PT_ERR_WORKSPACE;
+    if (!aligned16(ws)) return PT_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    const int RS = d->R * d->S;
+    const int kpitch = (int)round_up(d->K, 8);
+    uint16_t* wt = (uint16_t*)ws;
+    hipLaunchKernelGGL(k_transpose_w, dim3((unsigned)ceil_div(d->C, 32), (unsigned)ceil_div(kpitch, 32), RS), dim3(256),
+                       0, st, w, d->K, RS, d->C, d->w_cpitch, wt, kpitch);
+    rc = launch_status();
+    if (rc != PT_OK) return rc;
+    return bwd_data_classes(d, dy, wt, dx, st);
+}
+
+extern "C" int32_t pt_conv_bwd_data_crsk(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* wt, uint16_t* dx,
+                                         void* stream) {
+    int32_t rc = check_desc(d);
+    if (rc != PT_OK) return rc;
+    if (!dy || !wt || !dx) return PT_ERR_NULL;
+    if (!aligned16(wt)) return PT_ERR_SHAPE;
+    return bwd_data_classes(d, dy, wt, dx, (hipStream_t)stream);
+}
+
+extern "C" int32_t pt_weights_to_crsk_batched(const pt_layer_crsk* layers, int32_t n, void* stream) {
+    if (n < 0) return PT_ERR_SHAPE;
+    if (n == 0) return PT_OK;
+    if (!layers) return PT_ERR_NULL;
+    for (int i = 0; i < n; ++i) {
+        const pt_layer_crsk& l = layers[i];
+        if (!l.w || !l.wt) return PT_ERR_NULL;
+        if (l.K <= 0 || l.RS <= 0 || l.C <= 0 || l.w_cpitch < l.C) return PT_ERR_SHAPE;
+        if ((int64_t)ceil_div(l.C, 32) * ceil_div(round_up(l.K, 8), 32) * l.RS > 0x3fffffff) return PT_ERR_UNSUPPORTED;
+    }
+    TransposeJobs t;
+    t.n = 0;
+    int64_t blocks = 0;
+    auto flush = [&]() -> int32_t {
+        if (t.n == 0) return PT_OK;
+        hipLaunchKernelGGL(k_transpose_w_multi, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, t);
+        t.n = 0;
+        blocks = 0;
+        return launch_status();
+    };
+    for (int i = 0; i < n; ++i) {
+        const pt_layer_crsk& l = layers[i];
+        const int kpitch = (int)round_up(l.K, 8);
+        const int nbx = (int)ceil_div(l.C, 32), nby = (int)ceil_div(kpitch, 32);
+        const int64_t nb = (int64_t)nbx * nby * l.RS;
+        if (blocks + nb > 0x3fffffff) {
+            const int32_t rc = flush();
+            if (rc != PT_OK) return rc;
+        }
+        t.j[t.n++] = TransposeJob{l.w, l.wt, l.K, l.RS, l.C, l.w_cpitch, kpitch, (int)blocks, nbx, nby};
+        blocks += nb;
+        if (t.n == kMaxTransposeJobs) {
+            const int32_t rc = flush();
+            if (rc != PT_OK) return rc;
+        }
+    }
+    return flush();
 }
 
 extern "C" int32_t pt_conv_bwd_weight(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, float* dw, void* ws,

@@ -169,6 +169,151 @@ __global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const uint1
     }
 }
 
+// ---- multi-job forms: a network has dozens of layers and edges and each of these steps is tiny, so the job
+// descriptors ride in the kernel arguments of one launch and a workgroup looks up which job it serves.
+constexpr int kMaxMaskJobs = 128;
+struct MaskJob {
+    const float* norms;
+    uint8_t* zero;
+    int n, blk0;  // blk0: first workgroup of this job
+};
+struct MaskJobs {
+    MaskJob j[kMaxMaskJobs];
+    int n;
+};
+template <typename Jobs>
+__device__ __forceinline__ int job_of_block(const Jobs& jobs, int block) {
+    int lo = 0, hi = jobs.n - 1;  // last job whose blk0 <= block
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs.j[mid].blk0 <= block) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+__global__ __launch_bounds__(256) void k_zero_groups_multi(const MaskJobs jobs, float thr) {
+    const int ji = job_of_block(jobs, blockIdx.x);
+    const MaskJob& jb = jobs.j[ji];
+    const int i = (blockIdx.x - jb.blk0) * 256 + threadIdx.x;
+    if (i < jb.n) jb.zero[i] = jb.norms[i] < thr ? 1 : 0;
+}
+
+// One workgroup per edge: keep mask from the members' zero masks, then the ascending survivor list by a
+// chunked exclusive scan (wavefront ballots), all inside the workgroup.
+constexpr int kMaxPlanEdges = 32, kMaxPlanMembers = 300;
+struct PlanEdge {
+    uint8_t* keep;
+    int* idx;
+    int* n_keep;
+    int n, m0, mcount;  // members m[m0 .. m0+mcount)
+};
+struct PlanJobs {
+    PlanEdge e[kMaxPlanEdges];
+    const uint8_t* m[kMaxPlanMembers];
+};
+__global__ __launch_bounds__(1024) void k_reconcile_plan_multi(const PlanJobs jobs) {
+    __shared__ int wave_tot[16];
+    __shared__ int base_s;
+    const PlanEdge& e = jobs.e[blockIdx.x];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (tid == 0) base_s = 0;
+    __syncthreads();
+    for (int j0 = 0; j0 < e.n; j0 += 1024) {
+        const int j = j0 + tid;
+        bool k = false;
+        if (j < e.n) {
+            uint8_t all_zero = 1;
+            for (int a = 0; a < e.mcount; ++a) all_zero &= (jobs.m[e.m0 + a][j] != 0);
+            k = !all_zero;
+            e.keep[j] = k ? 1 : 0;
+        }
+        const unsigned long long b = __ballot(k);
+        const int pre = __popcll(b & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_tot[wv] = __popcll(b);
+        __syncthreads();
+        int off = base_s;
+        for (int a = 0; a < wv; ++a) off += wave_tot[a];
+        if (k) e.idx[off + pre] = j;
+        __syncthreads();
+        if (tid == 0) {
+            int t = 0;
+            for (int a = 0; a < 16; ++a) t += wave_tot[a];
+            base_s += t;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) *e.n_keep = base_s;
+}
+
+constexpr int kMaxVecJobs = 80;
+struct VecJob {
+    const void* v;
+    const int* idx;
+    void* out;
+    int n_keep, elem_bytes, blk0, pad;
+};
+struct VecJobs {
+    VecJob j[kMaxVecJobs];
+    int n;
+};
+__global__ __launch_bounds__(256) void k_compact_vector_multi(const VecJobs jobs) {
+    const int ji = job_of_block(jobs, blockIdx.x);
+    const VecJob& jb = jobs.j[ji];
+    const int t = (blockIdx.x - jb.blk0) * 256 + threadIdx.x;
+    if (t >= jb.n_keep) return;
+    const int s = jb.idx[t];
+    switch (jb.elem_bytes) {
+        case 1: ((uint8_t*)jb.out)[t] = ((const uint8_t*)jb.v)[s]; break;
+        case 2: ((uint16_t*)jb.out)[t] = ((const uint16_t*)jb.v)[s]; break;
+        case 4: ((uint32_t*)jb.out)[t] = ((const uint32_t*)jb.v)[s]; break;
+        default: ((uint64_t*)jb.out)[t] = ((const uint64_t*)jb.v)[s]; break;
+    }
+}
+
+constexpr int kMaxWJobs = 56;
+struct WJob {
+    const float* w;
+    const int* idxK;
+    const int* idxC;
+    float* out;
+    int RS, cpitch, Cp, out_cpitch, out_rows, blk0, rows_per_blk, pad;
+};
+struct WJobs {
+    WJob j[kMaxWJobs];
+    int n;
+};
+// A workgroup gathers `rows_per_blk` consecutive output rows (k', rs) of one tensor; a thread produces 4
+// consecutive c' of a row.
+__global__ __launch_bounds__(256) void k_compact_weights_multi(const WJobs jobs) {
+    const int ji = job_of_block(jobs, blockIdx.x);
+    const WJob& jb = jobs.j[ji];
+    const int cq = (jb.Cp + 3) >> 2;
+    const int row0 = (blockIdx.x - jb.blk0) * jb.rows_per_blk;
+    const int nrow = min(jb.rows_per_blk, jb.out_rows - row0);
+    const bool vec = (jb.out_cpitch & 3) == 0 && (((uintptr_t)jb.out & 15) == 0);
+    for (int t = threadIdx.x; t < nrow * cq; t += 256) {
+        const int r = t / cq, c0 = (t - r * cq) * 4;
+        const int row = row0 + r;
+        const int kp = row / jb.RS, rs = row - kp * jb.RS;
+        const int64_t k = jb.idxK ? jb.idxK[kp] : kp;
+        const float* src = jb.w + (k * jb.RS + rs) * (int64_t)jb.cpitch;
+        float* dst = jb.out + (int64_t)row * jb.out_cpitch + c0;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int c = c0 + e;
+            v[e] = (c < jb.Cp) ? src[jb.idxC ? jb.idxC[c] : c] : 0.f;
+        }
+        if (c0 + 3 < jb.Cp && vec) {
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (c0 + e < jb.Cp) dst[e] = v[e];
+        }
+    }
+}
+
 }  // namespace pt
 
 using namespace pt;
@@ -270,4 +415,149 @@ extern "C" int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C,
     hipLaunchKernelGGL(k_compact_nhwc, dim3((unsigned)nblk), dim3(256), 0, st, x, pixels, x_cpitch, idx, Cp, out,
                        out_cpitch, vec_ok);
     return launch_status();
+}
+
+// ---- multi-job entry points ------------------------------------------------------------------------
+extern "C" int32_t pt_zero_groups_batched(const pt_norm_mask* jobs, int32_t n_jobs, float thr, void* stream) {
+    if (n_jobs < 0) return PT_ERR_SHAPE;
+    if (n_jobs == 0) return PT_OK;
+    if (!jobs) return PT_ERR_NULL;
+    for (int i = 0; i < n_jobs; ++i) {
+        if (jobs[i].n < 0) return PT_ERR_SHAPE;
+        if (jobs[i].n > 0 && (!jobs[i].norms || !jobs[i].zero)) return PT_ERR_NULL;
+    }
+    MaskJobs t;
+    t.n = 0;
+    int blocks = 0;
+    auto flush = [&]() -> int32_t {
+        if (t.n == 0) return PT_OK;
+        hipLaunchKernelGGL(k_zero_groups_multi, dim3(blocks), dim3(256), 0, (hipStream_t)stream, t, thr);
+        t.n = 0;
+        blocks = 0;
+        return launch_status();
+    };
+    for (int i = 0; i < n_jobs; ++i) {
+        if (jobs[i].n == 0) continue;
+        t.j[t.n++] = MaskJob{jobs[i].norms, jobs[i].zero, jobs[i].n, blocks};
+        blocks += (jobs[i].n + 255) / 256;
+        if (t.n == kMaxMaskJobs) {
+            const int32_t rc = flush();
+            if (rc != PT_OK) return rc;
+        }
+    }
+    return flush();
+}
+
+extern "C" int32_t pt_reconcile_plan_batched(const pt_edge_plan* edges, int32_t n_edges, void* stream) {
+    if (n_edges < 0) return PT_ERR_SHAPE;
+    if (n_edges == 0) return PT_OK;
+    if (!edges) return PT_ERR_NULL;
+    for (int i = 0; i < n_edges; ++i) {
+        const pt_edge_plan& e = edges[i];
+        if (e.n < 0 || e.n_prod < 0 || e.n_cons < 0 || e.n_prod + e.n_cons < 1) return PT_ERR_SHAPE;
+        if (e.n_prod + e.n_cons > kMaxEdgeMembers) return PT_ERR_UNSUPPORTED;
+        if ((e.n_prod > 0 && !e.producer_zero) || (e.n_cons > 0 && !e.consumer_zero) || !e.n_keep_dev) return PT_ERR_NULL;
+        if (e.n > 0 && (!e.keep || !e.idx)) return PT_ERR_NULL;
+        for (int a = 0; a < e.n_prod; ++a)
+            if (!e.producer_zero[a]) return PT_ERR_NULL;
+        for (int a = 0; a < e.n_cons; ++a)
+            if (!e.consumer_zero[a]) return PT_ERR_NULL;
+    }
+    PlanJobs t;
+    int ne = 0, nm = 0;
+    auto flush = [&]() -> int32_t {
+        if (ne == 0) return PT_OK;
+        for (int a = nm; a < kMaxPlanMembers; ++a) t.m[a] = nullptr;
+        hipLaunchKernelGGL(k_reconcile_plan_multi, dim3(ne), dim3(1024), 0, (hipStream_t)stream, t);
+        ne = nm = 0;
+        return launch_status();
+    };
+    for (int i = 0; i < n_edges; ++i) {
+        const pt_edge_plan& e = edges[i];
+        const int mc = e.n_prod + e.n_cons;
+        if (ne == kMaxPlanEdges || nm + mc > kMaxPlanMembers) {
+            const int32_t rc = flush();
+            if (rc != PT_OK) return rc;
+        }
+        t.e[ne++] = PlanEdge{e.keep, e.idx, e.n_keep_dev, e.n, nm, mc};
+        for (int a = 0; a < e.n_prod; ++a) t.m[nm++] = e.producer_zero[a];
+        for (int a = 0; a < e.n_cons; ++a) t.m[nm++] = e.consumer_zero[a];
+    }
+    return flush();
+}
+
+extern "C" int32_t pt_compact_vector_batched(const pt_gather_vector* jobs, int32_t n_jobs, void* stream) {
+    if (n_jobs < 0) return PT_ERR_SHAPE;
+    if (n_jobs == 0) return PT_OK;
+    if (!jobs) return PT_ERR_NULL;
+    for (int i = 0; i < n_jobs; ++i) {
+        const pt_gather_vector& j = jobs[i];
+        if (j.n_keep < 0) return PT_ERR_SHAPE;
+        if (j.elem_bytes != 1 && j.elem_bytes != 2 && j.elem_bytes != 4 && j.elem_bytes != 8) return PT_ERR_UNSUPPORTED;
+        if (j.n_keep > 0 && (!j.v || !j.idx || !j.out)) return PT_ERR_NULL;
+    }
+    VecJobs t;
+    t.n = 0;
+    int blocks = 0;
+    auto flush = [&]() -> int32_t {
+        if (t.n == 0) return PT_OK;
+        hipLaunchKernelGGL(k_compact_vector_multi, dim3(blocks), dim3(256), 0, (hipStream_t)stream, t);
+        t.n = 0;
+        blocks = 0;
+        return launch_status();
+    };
+    for (int i = 0; i < n_jobs; ++i) {
+        const pt_gather_vector& j = jobs[i];
+        if (j.n_keep == 0) continue;
+        t.j[t.n++] = VecJob{j.v, j.idx, j.out, j.n_keep, j.elem_bytes, blocks, 0};
+        blocks += (j.n_keep + 255) / 256;
+        if (t.n == kMaxVecJobs) {
+            const int32_t rc = flush();
+            if (rc != PT_OK) return rc;
+        }
+    }
+    return flush();
+}
+
+extern "C" int32_t pt_compact_weights_batched(const pt_gather_weights* jobs, int32_t n_jobs, void* stream) {
+    if (n_jobs < 0) return PT_ERR_SHAPE;
+    if (n_jobs == 0) return PT_OK;
+    if (!jobs) return PT_ERR_NULL;
+    for (int i = 0; i < n_jobs; ++i) {
+        const pt_gather_weights& j = jobs[i];
+        if (!j.w || !j.w_out) return PT_ERR_NULL;
+        if (j.K <= 0 || j.RS <= 0 || j.C <= 0 || j.Kp <= 0 || j.Cp <= 0 || j.w_cpitch < j.C || j.out_cpitch < j.Cp)
+            return PT_ERR_SHAPE;
+        if ((!j.idxK && j.Kp != j.K) || (!j.idxC && j.Cp != j.C) || j.Kp > j.K || j.Cp > j.C) return PT_ERR_SHAPE;
+        if ((int64_t)j.Kp * j.RS > 0x7fffffff) return PT_ERR_UNSUPPORTED;
+    }
+    WJobs t;
+    t.n = 0;
+    int64_t blocks = 0;
+    auto flush = [&]() -> int32_t {
+        if (t.n == 0) return PT_OK;
+        hipLaunchKernelGGL(k_compact_weights_multi, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, t);
+        t.n = 0;
+        blocks = 0;
+        return launch_status();
+    };
+    for (int i = 0; i < n_jobs; ++i) {
+        const pt_gather_weights& j = jobs[i];
+        const int out_rows = j.Kp * j.RS;
+        // about 4096 output elements per workgroup
+        int rpb = 4096 / (((j.Cp + 3) / 4) * 4);
+        if (rpb < 1) rpb = 1;
+        const int64_t nb = ceil_div(out_rows, rpb);
+        if (blocks + nb > 0x3fffffff) {
+            const int32_t rc = flush();
+            if (rc != PT_OK) return rc;
+        }
+        t.j[t.n++] = WJob{j.w, j.idxK, j.idxC, j.w_out, j.RS, j.w_cpitch, j.Cp, j.out_cpitch, out_rows, (int)blocks, rpb, 0};
+        blocks += nb;
+        if (t.n == kMaxWJobs) {
+            const int32_t rc = flush();
+            if (rc != PT_OK) return rc;
+        }
+    }
+    return flush();
 }

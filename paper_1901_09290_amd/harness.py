@@ -66,6 +66,8 @@ class ConvLayer:
             else:
                 self.w_master[..., : s.C].normal_(std=wl.he_std(s), generator=gen)
         self.w_bf16 = torch.zeros((s.K, s.R, s.S, self.wp), dtype=bf, device=DEV)
+        # the same weights with k innermost, for the input-gradient GEMM (refreshed once per iteration)
+        self.w_crsk = None if s.first else torch.zeros((s.C, s.R, s.S, self.yp), dtype=bf, device=DEV)
         self.y = torch.zeros((s.N, s.P, s.Q, self.yp), dtype=bf, device=DEV)
         self.dx = None if s.first else torch.zeros((s.N, s.H, s.W, self.xp), dtype=bf, device=DEV)
         self.dw = torch.zeros((s.K, s.R, s.S, self.wp), dtype=f32, device=DEV)
@@ -100,6 +102,10 @@ class ConvLayer:
     def bwd_data(self, ws):
         if self.dx is not None:
             B.conv_bwd_data(self.desc, self.dy, self.w_bf16, self.dx, ws)
+
+    def bwd_data_crsk(self):
+        if self.dx is not None:
+            B.conv_bwd_data_crsk(self.desc, self.dy, self.w_crsk, self.dx)
 
     def bwd_weight(self, ws):
         B.conv_bwd_weight(self.desc, self.x, self.dy, self.dw, ws)
@@ -142,16 +148,21 @@ class Network:
         self.ws_norms = torch.empty(max(256, B.group_norms_batched_workspace_bytes(self.norm_jobs)), dtype=torch.uint8,
                                     device=DEV)
         self.ws = make_workspace(self.layers)
+        crsk = [B.layer_crsk(l.w_bf16, l.w_crsk, l.spec.K, l.RS, l.spec.C, l.wp) for l in self.layers
+                if l.w_crsk is not None]
+        self.crsk_jobs = (B.LayerCrsk * len(crsk))(*crsk) if crsk else None
 
     def train_step(self, lam: float) -> None:
         """Alg. 1, one iteration restricted to the conv layers: GroupLassoReg (all layers' group norms, which
         also refreshes the bf16 weights the convolutions read), ForwardProp, BackProp (input and weight
         gradients, last layer first), then the regulariser's gradient added onto every dW."""
         B.group_norms_batched(self.norm_jobs, self.ws_norms)
+        if self.crsk_jobs is not None:
+            B.weights_to_crsk_batched(self.crsk_jobs)
         for l in self.layers:
             l.fwd(self.ws)
         for l in reversed(self.layers):
-            l.bwd_data(self.ws)
+            l.bwd_data_crsk()
             l.bwd_weight(self.ws)
         B.group_lasso_grad_batched(self.lasso_jobs, lam)
 
@@ -209,9 +220,25 @@ class ReconfigModel:
         self.bn_out = [[torch.zeros_like(v) for v in vs] for vs in self.bn]
         self.act_out = [torch.zeros_like(t) for t in self.act]
         self.new_counts: Optional[np.ndarray] = None
+        # whole-network job tables of the multi-job calls (built once; they hold device pointers only)
+        mask_jobs = []
+        for i, s in enumerate(self.specs):
+            mask_jobs += [B.norm_mask(self.on[i], s.K, self.zo[i]), B.norm_mask(self.inn[i], s.C, self.zi[i])]
+        self.mask_jobs = (B.NormMask * len(mask_jobs))(*mask_jobs)
+        self._edge_structs = [B.edge_plan([self.zo[i] for i in e.producers], [self.zi[i] for i in e.consumers], e.n,
+                                          self.keep[k], self.idx[k], self.counts[k:k + 1])
+                              for k, e in enumerate(self.edges)]
+        self.edge_jobs = (B.EdgePlan * len(self.edges))(*self._edge_structs)
 
     def detect(self, thr: float) -> None:
-        """group_norms + zero_groups per layer, reconcile + plan per edge (all asynchronous)."""
+        """Group norms and zero masks of every layer, then keep mask + survivor list of every edge: four
+        multi-job calls, all asynchronous."""
+        B.group_norms_batched(self.norm_jobs, self.ws)
+        B.zero_groups_batched(self.mask_jobs, thr)
+        B.reconcile_plan_batched(self.edge_jobs)
+
+    def detect_per_call(self, thr: float) -> None:
+        """The same detection through the single-tensor calls (one launch per layer / edge)."""
         B.group_norms_batched(self.norm_jobs, self.ws)
         for i, s in enumerate(self.specs):
             B.zero_groups(self.on[i], s.K, thr, self.zo[i])
@@ -221,25 +248,38 @@ class ReconfigModel:
                              self.keep[e])
             B.compact_plan(self.keep[e], edge.n, self.idx[e], self.counts[e:e + 1])
 
-    def compact(self, cnt: Optional[np.ndarray] = None) -> None:
+    def compact(self, cnt: Optional[np.ndarray] = None, per_call: bool = False) -> None:
         """Gathers every tensor with the planned index lists.  The survivor counts size the outputs: they
-        are read back here (one synchronising copy) unless the caller already holds them."""
+        are read back here (one synchronising copy) unless the caller already holds them.  Weights, momentum
+        and the per-channel vectors of all layers go through the multi-job calls; each saved activation is
+        one launch of its own."""
         if cnt is None:
             cnt = self.counts.cpu().numpy()
         self.new_counts = cnt
+        wjobs, vjobs = [], []
         for i, s in enumerate(self.specs):
             ik = self.idx[s.out_edge] if s.out_edge is not None else None
             ic = self.idx[s.in_edge] if s.in_edge is not None else None
             Kp = int(cnt[s.out_edge]) if s.out_edge is not None else s.K
             Cp = int(cnt[s.in_edge]) if s.in_edge is not None else s.C
             RS, wp, op = s.R * s.S, pitch8(s.C), pitch8(Cp)
-            B.compact_weights(self.w[i], s.K, RS, s.C, wp, ik, Kp, ic, Cp, self.w_out[i], op)
-            B.compact_weights(self.mom[i], s.K, RS, s.C, wp, ik, Kp, ic, Cp, self.mom_out[i], op)
+            if per_call:
+                B.compact_weights(self.w[i], s.K, RS, s.C, wp, ik, Kp, ic, Cp, self.w_out[i], op)
+                B.compact_weights(self.mom[i], s.K, RS, s.C, wp, ik, Kp, ic, Cp, self.mom_out[i], op)
+            else:
+                wjobs.append(B.gather_weights(self.w[i], s.K, RS, s.C, wp, ik, Kp, ic, Cp, self.w_out[i], op))
+                wjobs.append(B.gather_weights(self.mom[i], s.K, RS, s.C, wp, ik, Kp, ic, Cp, self.mom_out[i], op))
             if ik is not None:
                 for v, o in zip(self.bn[i], self.bn_out[i]):
-                    B.compact_vector(v, 4, ik, Kp, o)
+                    if per_call:
+                        B.compact_vector(v, 4, ik, Kp, o)
+                    else:
+                        vjobs.append(B.gather_vector(v, 4, ik, Kp, o))
             if self.act and ic is not None:
                 B.compact_nhwc(self.act[i], s.N * s.H * s.W, s.C, wp, ic, Cp, self.act_out[i], op)
+        if not per_call:
+            B.compact_weights_batched(wjobs)
+            B.compact_vector_batched(vjobs)
 
     def sweep(self, thr: float) -> None:
         self.detect(thr)

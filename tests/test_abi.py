@@ -83,3 +83,37 @@ def test_null_and_shape_errors_are_reported_before_launch(lib):
     assert lib.pt_compact_vector(None, 4, None, 0, None, None) == 0
     assert lib.pt_compact_nhwc(fake, 10, 8, 8, fake, 9, fake, 16, None) == -2               # Cp > C
     assert lib.pt_compact_nhwc(None, 0, 8, 8, None, 4, None, 4, None) == 0
+
+
+def test_batched_reconfiguration_calls_validate_on_the_host(lib):
+    fake = 256
+    assert lib.pt_zero_groups_batched(None, 0, 0.0, None) == 0
+    assert lib.pt_zero_groups_batched(None, 3, 0.0, None) == -1
+    assert lib.pt_zero_groups_batched(None, -1, 0.0, None) == -2
+    jobs = (B.NormMask * 2)(B.NormMask(fake, fake, 0, 0), B.NormMask(None, fake, 4, 0))
+    assert lib.pt_zero_groups_batched(jobs, 2, 0.0, None) == -1
+    jobs = (B.NormMask * 1)(B.NormMask(fake, fake, -4, 0))
+    assert lib.pt_zero_groups_batched(jobs, 1, 0.0, None) == -2
+    assert lib.pt_reconcile_plan_batched(None, 2, None) == -1
+    e = (B.EdgePlan * 1)(B.EdgePlan(None, None, 0, 0, 8, 0, fake, fake, fake))
+    assert lib.pt_reconcile_plan_batched(e, 1, None) == -2          # an edge needs at least one member
+    members = (C.c_void_p * 65)(*([fake] * 65))
+    e = (B.EdgePlan * 1)(B.EdgePlan(C.cast(members, C.POINTER(C.c_void_p)), None, 65, 0, 8, 0, fake, fake, fake))
+    assert lib.pt_reconcile_plan_batched(e, 1, None) == -4          # more than 64 members
+    assert lib.pt_compact_vector_batched(None, 1, None) == -1
+    v = (B.GatherVector * 1)(B.GatherVector(fake, fake, fake, 4, 3))
+    assert lib.pt_compact_vector_batched(v, 1, None) == -4           # element size 3
+    w = (B.GatherWeights * 1)(B.GatherWeights(fake, None, None, fake, 8, 1, 8, 8, 4, 8, 8, 0))
+    assert lib.pt_compact_weights_batched(w, 1, None) == -2          # Kp != K without an index list
+    assert lib.pt_compact_weights_batched(None, 0, None) == 0
+
+
+def test_crsk_calls_validate_on_the_host(lib):
+    fake = 256
+    assert lib.pt_weights_to_crsk_batched(None, 0, None) == 0
+    assert lib.pt_weights_to_crsk_batched(None, 2, None) == -1
+    j = (B.LayerCrsk * 1)(B.LayerCrsk(fake, fake, 8, 9, 16, 8))
+    assert lib.pt_weights_to_crsk_batched(j, 1, None) == -2          # pitch < C
+    d = B.conv_desc(1, 4, 4, 8, 8, 1, 1, 1, 0)
+    assert lib.pt_conv_bwd_data_crsk(C.byref(d), None, None, None, None) == -1
+    assert lib.pt_conv_bwd_data_crsk(C.byref(d), fake, 8, fake, None) == -2   # wt not 16-byte aligned

@@ -107,3 +107,33 @@ def test_cfg2_resnet32_distinct_layers_full_tensor():
     for i, (spec, _) in enumerate(wl.distinct_shapes(layers)):
         errs = _check_full(spec, rng_seed * 1000 + i)
         print(spec.name, spec.shape_key(), ["%.2e" % e for e in errs], flush=True)
+
+
+@pytest.mark.parametrize("case", [(2, 15, 15, 40, 136, 3, 2, 1), (2, 10, 10, 37, 51, 3, 1, 1), (2, 16, 16, 64, 128, 1, 2, 0)])
+def test_bwd_data_from_pretransposed_weights(case):
+    """pt_weights_to_crsk_batched + pt_conv_bwd_data_crsk: the transposed copy is an exact permutation
+    (k padding zero) and the input gradient is bit-identical to pt_conv_bwd_data's."""
+    import torch
+    from gpu_util import DEV, dev_bf16, empty_bf16, pitch8, workspace
+    from paper_1901_09290_amd import binding as B
+    spec = _spec(*case)
+    t = wl.conv_tensors(spec, np.random.Generator(np.random.PCG64(900 + sum(case))))
+    xp, yp, wp = pitch8(spec.C), pitch8(spec.K), pitch8(spec.C)
+    d = B.desc_of(spec, xp, yp, wp)
+    wd, dyd = dev_bf16(t["w"], wp), dev_bf16(t["dy"], yp)
+    RS = spec.R * spec.S
+    wt = torch.full((spec.C, RS, yp), float("nan"), dtype=torch.bfloat16, device=DEV)
+    other = torch.full((7, 1, 8), float("nan"), dtype=torch.bfloat16, device=DEV)   # a second job in the same launch
+    w2 = dev_bf16(np.arange(5 * 7, dtype=np.float32).reshape(5, 1, 7), 8)
+    B.weights_to_crsk_batched([B.layer_crsk(wd, wt, spec.K, RS, spec.C, wp), B.layer_crsk(w2, other, 5, 1, 7, 8)])
+    dx_a = empty_bf16((spec.N, spec.H, spec.W, xp), fill=0x7FC0)
+    dx_b = empty_bf16((spec.N, spec.H, spec.W, xp), fill=0x7FC0)
+    B.conv_bwd_data_crsk(d, dyd, wt, dx_a)
+    B.conv_bwd_data(d, dyd, wd, dx_b, workspace(B.conv_bwd_data_workspace_bytes(d)))
+    torch.cuda.synchronize()
+    want = np.zeros((spec.C, RS, yp), dtype=np.float32)
+    want[..., : spec.K] = t["w"].reshape(spec.K, RS, spec.C).transpose(2, 1, 0)
+    assert np.array_equal(wt.float().cpu().numpy(), want)
+    o = other.float().cpu().numpy()
+    assert np.array_equal(o[:, 0, :5], np.arange(35, dtype=np.float32).reshape(5, 7).T) and not o[:, 0, 5:].any()
+    assert torch.equal(dx_a.view(torch.int16), dx_b.view(torch.int16))

@@ -46,7 +46,9 @@ def _check_layer_sampled(spec, seed):
     ws = hz.make_workspace([layer])
     layer.norms(ws)          # writes the bf16 weights the convolutions read
     layer.fwd(ws)
-    layer.bwd_data(ws)
+    if layer.w_crsk is not None:   # the step converts the filter bank once and runs the workspace-free input gradient
+        B.weights_to_crsk_batched([B.layer_crsk(layer.w_bf16, layer.w_crsk, spec.K, layer.RS, spec.C, layer.wp)])
+        layer.bwd_data_crsk()
     layer.bwd_weight(ws)
     torch.cuda.synchronize()
     s = oracle.shape_of(spec)

@@ -322,3 +322,50 @@ def test_cfg1_reconfiguration_end_to_end():
     assert rel_err(y2, oracle.conv_fwd(s, c["x"], c["w"])[..., rik]) <= CONV_TOL
     assert rel_err(dx2, oracle.conv_bwd_data(s, c["dy"], c["w"])[..., ric]) <= CONV_TOL
     assert rel_err(dw2, oracle.conv_bwd_weight(s, c["x"], c["dy"])[rik][..., ric]) <= CONV_TOL
+
+
+def test_multi_job_reconfiguration_equals_single_calls_and_oracle():
+    """A small network with a residual-style shared edge, swept once through the multi-job calls and once
+    through the single-tensor calls: identical masks, plans and compacted tensors, and both equal the oracle."""
+    from paper_1901_09290_amd import harness as hz
+    specs = [
+        wl.ConvSpec("m0", 2, 12, 12, 3, 300, 3, 3, 1, 1, None, 0, first=True),
+        wl.ConvSpec("m1", 2, 12, 12, 300, 37, 1, 1, 1, 0, 0, 1),
+        wl.ConvSpec("m2", 2, 12, 12, 37, 300, 3, 3, 1, 1, 1, 0),
+        wl.ConvSpec("m3", 2, 12, 12, 300, 1100, 1, 1, 1, 0, 0, 2),
+        wl.ConvSpec("m4", 2, 12, 12, 1100, 9, 1, 1, 1, 0, 2, None),
+    ]
+    edges = [wl.Edge("e0", 300, [0, 2], [1, 3]), wl.Edge("e1", 37, [1], [2]), wl.Edge("e2", 1100, [3], [4])]
+    rng = np.random.Generator(np.random.PCG64(77))
+    zero_sets = wl.zeroed_channel_sets(edges, 0.35, rng)
+    weights = wl.network_weights(specs, edges, zero_sets, rng)
+    a = hz.ReconfigModel(specs, edges, weights, seed=8)
+    b = hz.ReconfigModel(specs, edges, weights, seed=8)
+    a.detect(1e-6)
+    a.compact()
+    b.detect_per_call(1e-6)
+    b.compact(per_call=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(a.new_counts, b.new_counts)
+    assert a.new_counts.tolist() == [e.n - z.size for e, z in zip(edges, zero_sets)]
+    for ta, tb in zip(a.keep + a.zo + a.zi + a.w_out + a.mom_out + a.act_out + [v for vs in a.bn_out for v in vs],
+                      b.keep + b.zo + b.zi + b.w_out + b.mom_out + b.act_out + [v for vs in b.bn_out for v in vs]):
+        assert torch.equal(ta, tb)
+    for e in range(len(edges)):
+        n = int(a.new_counts[e])
+        keep = np.ones(edges[e].n, dtype=np.uint8)
+        keep[zero_sets[e]] = 0
+        assert np.array_equal(a.keep[e].cpu().numpy(), keep)
+        assert np.array_equal(a.idx[e].cpu().numpy()[:n], oracle.compact_plan(keep))
+        assert np.array_equal(b.idx[e].cpu().numpy()[:n], oracle.compact_plan(keep))
+    for i, s in enumerate(specs):
+        ik = oracle.compact_plan(a.keep[s.out_edge].cpu().numpy()) if s.out_edge is not None else None
+        ic = oracle.compact_plan(a.keep[s.in_edge].cpu().numpy()) if s.in_edge is not None else None
+        Kp = s.K if ik is None else ik.size
+        Cp = s.C if ic is None else ic.size
+        op = hz.pitch8(Cp)
+        got = a.w_out[i].reshape(-1)[: Kp * s.R * s.S * op].reshape(Kp, s.R, s.S, op).cpu().numpy()[..., :Cp]
+        assert np.array_equal(got, oracle.compact_weights(weights[i], ik, ic).astype(np.float32))
+        if ik is not None:
+            for v, o in zip(a.bn[i], a.bn_out[i]):
+                assert np.array_equal(o.cpu().numpy()[:Kp], oracle.compact_vector(v.cpu().numpy(), ik))
