@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--detail", action="store_true", help="write per-layer tables under gpurun_out/")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch a plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB): the "
+                         "reference against which hardware byte counters of a profiler run are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -286,6 +289,13 @@ def main():
                                "frac_hbm_peak": round(sweep_bytes / (t_sweep * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
         },
     }
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.neg(src, out=dst)       # one launch: 2^30 bytes read, 2^30 bytes written
+        torch.cuda.synchronize()
+        out["copy_probe"] = {"kernel": "torch.neg (vectorized elementwise)", "read_bytes": 1 << 30, "write_bytes": 1 << 30}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
 

@@ -130,6 +130,7 @@ struct WgradPlan {
 };
 constexpr int kWgBM = 128, kWgBN = 128, kWgBK = 32;  // register-staged kernel
 constexpr int kWgDlBKP = 64;                          // direct kernel: pixels per reduction step
+constexpr int kWgTargetBlocks = 512;                  // workgroups per launch the split count aims at
 
 // 64-wide tiles when 128-wide ones would waste more than ~20 % of their rows
 inline int pick_tile(int n) {
@@ -161,10 +162,11 @@ inline WgradPlan plan_wgrad(const pt_conv_desc* d, bool dl) {
         p.tiles_n = (int)ceil_div(d->K, kWgBN);
         p.iters_total = (int)ceil_div(pixels, kWgBK);
     }
-    // about three workgroups per CU in total, at least 8 reduction steps each
+    // One resident set of workgroups (2 per CU x 256 CUs): more would run as a second, partly empty round.
+    // At least 4 reduction steps per workgroup.
     const int tiles = p.tiles_m * p.tiles_n;
-    int64_t splits = ceil_div(768, tiles);
-    const int64_t max_splits = p.iters_total / 8 > 0 ? p.iters_total / 8 : 1;
+    int64_t splits = kWgTargetBlocks / tiles;
+    const int64_t max_splits = p.iters_total / 4 > 0 ? p.iters_total / 4 : 1;
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
     p.iters_per_split = (int)ceil_div(p.iters_total, splits);

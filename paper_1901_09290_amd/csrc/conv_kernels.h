@@ -51,6 +51,19 @@ __device__ __forceinline__ uint4 mask8(uint4 v, bool ok, const Mask8& k) {
     return v;
 }
 
+#ifdef PT_KERNEL_TIMING
+// Working-build instrumentation (never defined for the library): per-workgroup phase time stamps.
+__device__ unsigned long long pt_dbg_times[4 * 16384];
+#define PT_STAMP(phase)                                                                                  \
+    do {                                                                                                 \
+        if (threadIdx.x == 0 && blockIdx.x < 16384) pt_dbg_times[blockIdx.x * 4 + (phase)] = wall_clock64(); \
+    } while (0)
+#else
+#define PT_STAMP(phase) \
+    do {                \
+    } while (0)
+#endif
+
 // XCD-aware block remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; give
 // each XCD a contiguous range of logical tiles so tiles that share operands share an L2.
 __device__ __forceinline__ int xcd_remap(int bid, int nb) {
@@ -367,6 +380,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
     static_assert(NW % 2 == 0 && GA % NW == 0 && GB % NW == 0 && LA >= 1 && LB >= 1 && TM >= 1 && TN >= 1, "tile config");
     static_assert(STAGES >= 2 && (STAGES - 2) * LPT < 64, "stages");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_b[];
+    PT_STAMP(0);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -543,8 +557,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < nk) issue(s);
+    PT_STAMP(1);
     if (all_live) main_loop(std::false_type{});
     else main_loop(std::true_type{});
+    PT_STAMP(2);
 
     // ---- epilogue: stage the bf16 tile in LDS, then 16-byte row-contiguous stores ------------------
     constexpr int LDC = BN + 8;  // elements
@@ -592,6 +608,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
             }
         }
     }
+    PT_STAMP(3);
 #endif
 }
 
@@ -663,10 +680,15 @@ __global__ __launch_bounds__(64 * WGM * WGN, MINB) void k_wgrad(const WgradArgs 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    // Workgroup ids are dealt round-robin to the 8 XCDs.  All tiles of one pixel split read the same x and dy
+    // slabs, so each XCD gets a contiguous range of the split-major (split, tile) order: a split's tiles run
+    // back to back on one XCD and the slabs are fetched into that L2 once.
+    const int ntile = a.tiles_m * a.tiles_n;
+    const int lin = xcd_remap(blockIdx.x, gridDim.x);
+    const int split = lin / ntile;
+    const int tile = lin - split * ntile;
     const int n0 = (tile % a.tiles_n) * BN;  // k origin
     const int m0 = (tile / a.tiles_n) * BM;  // (tap, c) origin
-    const int split = blockIdx.y;
     const int it0 = split * a.iters_per_split;
     const int it1 = min(a.iters_total, it0 + a.iters_per_split);
 
@@ -831,9 +853,9 @@ inline hipError_t launch_wgrad_cfg(WgradArgs& a, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int tiles_m = (int)ceil_div(a.Mtot, BM);
+    a.tiles_m = (int)ceil_div(a.Mtot, BM);
     a.tiles_n = (int)ceil_div(a.K, BN);
-    hipLaunchKernelGGL(kern, dim3(tiles_m * a.tiles_n, a.splits), dim3(NT), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(NT), lds, st, a);
     return hipSuccess;
 }
 
@@ -867,7 +889,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    PT_STAMP(0);
+    // Workgroup ids are dealt round-robin to the 8 XCDs.  All tiles of one pixel split read the same x and dy
+    // slabs, so each XCD gets a contiguous range of the split-major (split, tile) order: a split's tiles run
+    // back to back on one XCD and the slabs are fetched into that L2 once.
+    const int ntile = a.tiles_m * a.tiles_n;
+    const int lin = xcd_remap(blockIdx.x, gridDim.x);
+    const int split = lin / ntile;
+    const int tile = lin - split * ntile;
     const int n0 = (tile % a.tiles_n) * BN;        // k origin
     const int mt = tile / a.tiles_n;               // (tap, channel block)
     // tile row block: one filter tap (CP channels), or in folded mode one filter row (S*CP contiguous elements)
@@ -875,7 +904,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
     const int cb = (mt - tb * a.tiles_per_tap) * BM;
     const int run = a.fold ? a.S * a.CP : a.CP;
     const int fr = a.fold ? tb : tb / a.S;
-    const int split = blockIdx.y;
     const int it0 = split * a.iters_per_split;
     const int it1 = min(a.iters_total, it0 + a.iters_per_split);
 
@@ -968,6 +996,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < nk) issue(it0 + s, s);
+    PT_STAMP(1);
     for (int kt0 = 0; kt0 < nk; kt0 += STAGES) {
 #pragma unroll
         for (int s = 0; s < STAGES; ++s) {
@@ -982,6 +1011,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
         }
     }
 
+    PT_STAMP(2);
     // ---- epilogue: lane holds k (column) = lane%32 and rows 8g + 4*(lane/32) + {0..3} = 4 consecutive c
     float* out = a.OUT + (a.direct ? 0 : (int64_t)split * a.K * a.out_row_pitch);
 #pragma unroll
@@ -1017,6 +1047,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
             }
         }
     }
+    PT_STAMP(3);
 #endif
 }
 
@@ -1033,7 +1064,7 @@ inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n, a.splits), dim3(NT), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(NT), lds, st, a);
     return hipSuccess;
 }
 
