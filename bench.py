@@ -85,6 +85,8 @@ def main():
     ap.add_argument("--sparsity", type=float, default=0.3, help="fraction of each edge zeroed in the sweep")
     ap.add_argument("--detail", action="store_true", help="write per-layer tables under gpurun_out/")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="keep the weight gradients on the same stream as the input-gradient chain")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB): the "
@@ -110,6 +112,7 @@ def main():
     pruned_specs, pruned_edges = wl.with_widths(full_specs, edges, [k.size for k in keep])
     full = hz.Network(hz.build_network(full_specs, seed=2))
     pruned = hz.Network(hz.build_network(pruned_specs, seed=3))
+    full.overlap_wgrad = pruned.overlap_wgrad = not args.no_overlap
     rng = np.random.Generator(np.random.PCG64(10 + int(round(args.sparsity * 10))))
     zero_sets = wl.zeroed_channel_sets(pruned_edges, args.sparsity, rng)
     rweights = wl.network_weights(pruned_specs, pruned_edges, zero_sets, rng)
@@ -271,7 +274,8 @@ def main():
         "config": {"workload": f"ResNet-50 conv layers (53), batch {N}, 224x224, NHWC bf16: train step at full width "
                                f"(cfg3) + reconfiguration sweep at {int(args.sparsity * 100)}% zeroed groups (cfg5) + "
                                "train step at ragged pruned widths (cfg4)",
-                   "lambda": LAMBDA, "threshold": THRESHOLD, "hip_graphs": use_graph},
+                   "lambda": LAMBDA, "threshold": THRESHOLD, "hip_graphs": use_graph,
+                   "wgrad_on_second_stream": not args.no_overlap},
         "roofline": roofline,
         "breakdown": {
             "wall_ms_per_step": round(wall_ms, 4),

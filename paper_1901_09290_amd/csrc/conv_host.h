@@ -165,7 +165,9 @@ inline WgradPlan plan_wgrad(const pt_conv_desc* d, bool dl) {
     // One resident set of workgroups (2 per CU x 256 CUs): more would run as a second, partly empty round.
     // At least 4 reduction steps per workgroup.
     const int tiles = p.tiles_m * p.tiles_n;
-    int64_t splits = kWgTargetBlocks / tiles;
+    // 128x128 tiles run three stages deep (96 KiB of LDS: one workgroup per CU), the smaller tiles two per CU
+    const int target = (dl && p.BM == 128 && p.BN == 128) ? kWgTargetBlocks / 2 : kWgTargetBlocks;
+    int64_t splits = target / tiles;
     const int64_t max_splits = p.iters_total / 4 > 0 ? p.iters_total / 4 : 1;
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
@@ -205,7 +207,7 @@ inline hipError_t launch_wgrad(WgradArgs& a, const WgradPlan& p, bool vec, hipSt
         return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2>(a, st);
     }
     // wave grids and pipeline depths from measurements on ResNet-50 shapes
-    if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKP, 4, 2, 2>(a, st);
+    if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKP, 4, 2, 3>(a, st);
     if (p.BM == 64 && p.BN == 128) return launch_wgrad_dl_cfg<64, 128, kWgDlBKP, 2, 2, 3>(a, st);
     if (p.BM == 128 && p.BN == 64) return launch_wgrad_dl_cfg<128, 64, kWgDlBKP, 2, 2, 3>(a, st);
     return launch_wgrad_dl_cfg<64, 64, kWgDlBKP, 2, 2, 4>(a, st);

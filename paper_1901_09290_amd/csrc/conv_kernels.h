@@ -870,6 +870,36 @@ inline hipError_t launch_wgrad_cfg(WgradArgs& a, hipStream_t st) {
 // falls outside the image, and pixels past the end, fetch from the zero page (both operands, so no
 // garbage ever meets a zero).  Channel chunks past the channel count re-read the last valid chunk:
 // they only feed accumulator rows/columns that are never stored.
+// Transposing LDS read issued as inline assembly.  The compiler cannot see which LDS bytes the intrinsic
+// form touches and therefore waits for every outstanding global->LDS load before it, which serialises the
+// software pipeline; issued this way the read is ordered only by the explicit waits below.  The result
+// registers must not be touched before lds_wait() has been applied to them.
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_read_tr16_b64(uint32_t addr) {
+    static_assert(OFF >= 0 && OFF < 65536, "DS offset field");
+    s16x4 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+// Waits until at most N of this wave's LDS reads are outstanding (they return in order) and makes `first`
+// depend on the wait; lds_tie() extends the dependence to further registers.
+template <int N>
+__device__ __forceinline__ void lds_wait(s16x4& first) {
+    static_assert(N >= 0 && N < 16, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(first) : "n"(N));
+}
+__device__ __forceinline__ void lds_tie(s16x4& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ bf16x8 join_halves(s16x4 lo, s16x4 hi) {
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES>
 __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
@@ -963,36 +993,73 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
 
-    auto tr_read = [&](const uint8_t* base, int rb, int ks, int unit0) -> bf16x8 {
-        typedef __attribute__((address_space(3))) s16x4* lds_p;
-        const int r0 = ks * 16 + tr_row, r1 = r0 + 4;
-        const int u = unit0 + tr_u;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(base + r0 * rb + ((u ^ swz(r0, rb)) << 5) + tr_b));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(base + r1 * rb + ((u ^ swz(r1, rb)) << 5) + tr_b));
-        s16x8 r;
-        r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
-        r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
-        return __builtin_bit_cast(bf16x8, r);
-    };
+    // 32-bit LDS addresses of this lane's transposing reads: per 32-wide tile the 4-pixel halves at rows r, r+4.
+    // The swizzle term does not depend on the 16-pixel sub-step, which therefore is an immediate offset.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem_b;
+    uint32_t ax[TM][2], ay[TN][2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = tr_row + 4 * h;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int u = (wm * WTM + tm * 32) / 16 + tr_u;
+            ax[tm][h] = lds_base + (uint32_t)(r * RBX + ((u ^ swz(r, RBX)) << 5) + tr_b);
+        }
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int u = (wn * WTN + tn * 32) / 16 + tr_u;
+            ay[tn][h] = lds_base + (uint32_t)(r * RBY + ((u ^ swz(r, RBY)) << 5) + tr_b);
+        }
+    }
+    constexpr int NKS = BKP / 16, NRD = 2 * (TM + TN);  // sub-steps per stage, LDS reads per sub-step
+    static_assert(NRD < 16, "fragment reads per sub-step must fit the lgkmcnt field");
+    // One stage: the reads of sub-step ks+1 are in flight while the MFMAs of sub-step ks run.
     auto compute = [&](int stage) {
-        const uint8_t* sX = smem_b + stage * STAGE_BYTES;
-        const uint8_t* sY = sX + XBYTES;
+        const uint32_t sb = (uint32_t)(stage * STAGE_BYTES);
+        s16x4 fx[2][TM][2], fy[2][TN][2];
+        auto issue_reads = [&](auto ks_c) {
+            constexpr int KS = decltype(ks_c)::value;
 #pragma unroll
-        for (int ks = 0; ks < BKP / 16; ++ks) {
-            bf16x8 fx[TM], fy[TN];
+            for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) fx[tm] = tr_read(sX, RBX, ks, (wm * WTM + tm * 32) / 16);
+                for (int h = 0; h < 2; ++h) fx[KS & 1][tm][h] = lds_read_tr16_b64<KS * 16 * RBX>(ax[tm][h] + sb);
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) fy[tn] = tr_read(sY, RBY, ks, (wn * WTN + tn * 32) / 16);
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) fy[KS & 1][tn][h] = lds_read_tr16_b64<XBYTES + KS * 16 * RBY>(ay[tn][h] + sb);
+        };
+        issue_reads(std::integral_constant<int, 0>{});
+        static_for<0, NKS>([&](auto ks_c) {
+            constexpr int KS = decltype(ks_c)::value, B = KS & 1;
+            if constexpr (KS + 1 < NKS) {
+                issue_reads(std::integral_constant<int, KS + 1>{});
+                lds_wait<NRD>(fx[B][0][0]);
+            } else {
+                lds_wait<0>(fx[B][0][0]);
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) lds_tie(fx[B][tm][h]);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) lds_tie(fy[B][tn][h]);
+            bf16x8 vx[TM], vy[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) vx[tm] = join_halves(fx[B][tm][0], fx[B][tm][1]);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) vy[tn] = join_halves(fy[B][tn][0], fy[B][tn][1]);
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tm], fy[tn], acc[tm][tn], 0, 0, 0);
-        }
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vx[tm], vy[tn], acc[tm][tn], 0, 0, 0);
+        });
     };
 
     const int nk = it1 - it0;
+    const bool late = STAGES >= 3 && NW == 8 && (wave & 4) != 0;
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < nk) issue(it0 + s, s);
@@ -1005,8 +1072,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
                 if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * LPT>();
                 else wait_vmcnt<0>();
                 barrier_nofence();
-                if (kt + STAGES - 1 < nk) issue(it0 + kt + STAGES - 1, (s + STAGES - 1) % STAGES);
+                // Waves w and w+4 share a SIMD.  With three or more stages one of them issues the next stage's
+                // loads (address arithmetic on the vector ALU) before its MFMAs and the other after, so the two
+                // phases overlap on the SIMD instead of running in lockstep.  The target buffer is the one
+                // consumed in the previous step either way.
+                const bool more = kt + STAGES - 1 < nk;
+                if (more && !late) issue(it0 + kt + STAGES - 1, (s + STAGES - 1) % STAGES);
                 compute(s);
+                if (more && late) issue(it0 + kt + STAGES - 1, (s + STAGES - 1) % STAGES);
             }
         }
     }

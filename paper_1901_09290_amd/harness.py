@@ -151,19 +151,38 @@ class Network:
         crsk = [B.layer_crsk(l.w_bf16, l.w_crsk, l.spec.K, l.RS, l.spec.C, l.wp) for l in self.layers
                 if l.w_crsk is not None]
         self.crsk_jobs = (B.LayerCrsk * len(crsk))(*crsk) if crsk else None
+        # weight gradients run on a second stream, off the critical path of the input-gradient chain
+        self.side = torch.cuda.Stream()
+        self.overlap_wgrad = True
 
     def train_step(self, lam: float) -> None:
         """Alg. 1, one iteration restricted to the conv layers: GroupLassoReg (all layers' group norms, which
         also refreshes the bf16 weights the convolutions read), ForwardProp, BackProp (input and weight
-        gradients, last layer first), then the regulariser's gradient added onto every dW."""
+        gradients, last layer first), then the regulariser's gradient added onto every dW.
+
+        BackProp has two-way parallelism in any network: layer l's weight gradient needs only dy(l), which the
+        input gradient of layer l+1 produces, and nothing downstream waits for it.  So the input-gradient chain
+        stays on the caller's stream and each weight gradient is enqueued on a second stream behind the event
+        that marks its dy as ready; the two streams join before the regulariser's gradient."""
         B.group_norms_batched(self.norm_jobs, self.ws_norms)
         if self.crsk_jobs is not None:
             B.weights_to_crsk_batched(self.crsk_jobs)
         for l in self.layers:
             l.fwd(self.ws)
-        for l in reversed(self.layers):
-            l.bwd_data_crsk()
-            l.bwd_weight(self.ws)
+        if not self.overlap_wgrad:
+            for l in reversed(self.layers):
+                l.bwd_data_crsk()
+                l.bwd_weight(self.ws)
+        else:
+            main = torch.cuda.current_stream()
+            for l in reversed(self.layers):
+                ready = torch.cuda.Event()
+                ready.record(main)                 # dy(l) is final here (the layer above has produced it)
+                self.side.wait_event(ready)
+                with torch.cuda.stream(self.side):
+                    l.bwd_weight(self.ws)          # the workspace is used by this stream only
+                l.bwd_data_crsk()
+            main.wait_stream(self.side)
         B.group_lasso_grad_batched(self.lasso_jobs, lam)
 
     @property
