@@ -406,14 +406,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
         const uint32_t n = fdiv(row, a.gH), gi = row - n * a.gH.d;
         const int h0 = (int)gi * a.h_mul + a.h_add, w0 = (int)gj * a.w_mul + a.w_add;
         a_off[j] = (uint32_t)(((int)n * a.srcH + h0) * a.srcW + w0) * (uint32_t)a.apitch + (uint32_t)kvoff;
+        // validity is separable: one bit per filter column, replicated for every valid filter row
+        uint32_t colbits = 0;
+        for (int t = 0; t < a.TSm; ++t) colbits |= ((unsigned)(w0 + t * a.ts_step) < (unsigned)a.srcW ? 1u : 0u) << t;
         uint64_t mask = 0;
-        for (int r = 0; r < a.TR; ++r) {
-            const bool hok = (unsigned)(h0 + r * a.tr_step) < (unsigned)a.srcH;
-            for (int t = 0; t < a.TSm; ++t) {
-                const bool ok = hok && (unsigned)(w0 + t * a.ts_step) < (unsigned)a.srcW;
-                mask |= (uint64_t)(ok ? 1u : 0u) << (r * a.TSm + t);
-            }
-        }
+        for (int r = 0; r < a.TR; ++r)
+            if ((unsigned)(h0 + r * a.tr_step) < (unsigned)a.srcH) mask |= (uint64_t)colbits << (r * a.TSm);
         a_mask[j] = mask;
     }
     const uint32_t b_rowlen = (uint32_t)a.b_taps * a.bpitch;

@@ -118,55 +118,94 @@ __global__ void k_compact_nhwc(const uint16_t* __restrict__ x, int64_t pixels, i
     }
 }
 
-// Activation gather, streaming form (16-byte aligned rows on both sides).  A workgroup copies a run of
-// whole pixel rows into LDS with 16-byte loads - every source byte is read once, fully coalesced - then
-// every thread assembles 8 output channels from LDS with its eight channel indices held in registers
-// (a thread keeps the same output vector for all pixels it visits) and writes one 16-byte store.
-// Channels of the last vector past Cp are not written.
+// Activation gather, streaming form (16-byte aligned rows on both sides).  A workgroup streams runs of whole
+// pixel rows through two LDS buffers with direct global->LDS loads (every source byte is read once, fully
+// coalesced, and the next run is in flight while the current one is gathered); every thread keeps its eight
+// channel indices in registers, assembles 8 output channels of a pixel from LDS with eight 16-bit reads and
+// writes one 16-byte store.  Channels of the last vector past Cp are not written.
 constexpr int kGatherThreads = 256;
+constexpr int kGatherChunk = 32 * 1024;                           // bytes of pixel rows per LDS buffer
+constexpr int kGatherLoads = kGatherChunk / (kGatherThreads * 16);  // 16-byte loads per thread and run (8)
+typedef __attribute__((address_space(3))) void* lds_vptr;
+typedef const __attribute__((address_space(1))) void* glb_vptr;
+
 __global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const uint16_t* __restrict__ x, int64_t pixels,
                                                                       int x_cpitch, const int* __restrict__ idx, int Cp,
                                                                       uint16_t* __restrict__ out, int out_cpitch,
                                                                       int pix_per_chunk) {
-    extern __shared__ __attribute__((aligned(16))) uint16_t srow[];
-    const int tid = threadIdx.x;
+#if defined(__HIP_DEVICE_COMPILE__)
+    extern __shared__ __attribute__((aligned(16))) uint8_t sbuf[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nvec = (Cp + 7) >> 3;
     const int ppb = kGatherThreads / nvec;       // pixels gathered per pass (nvec <= 256)
     const int pp = tid / nvec, v = tid - pp * nvec;
     const bool active = pp < ppb;
-    int id[8];
+    uint32_t id2[8];                             // byte offset of each source channel inside a pixel row
 #pragma unroll
-    for (int e = 0; e < 8; ++e) id[e] = (active && v * 8 + e < Cp) ? idx[v * 8 + e] : 0;
+    for (int e = 0; e < 8; ++e) id2[e] = (active && v * 8 + e < Cp) ? 2u * (uint32_t)idx[v * 8 + e] : 0u;
     const int nlast = Cp - v * 8;                // valid channels of this thread's vector (>= 8: all)
-    const int row16 = x_cpitch >> 3;             // 16-byte units per source row
+    const int row_bytes = x_cpitch * 2;
     const int64_t nchunks = (pixels + pix_per_chunk - 1) / pix_per_chunk;
-    for (int64_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_vptr)sbuf;
+
+    // Every wave issues exactly kGatherLoads load instructions per run (lanes past the run's end re-read its last
+    // 16 bytes into a slot nobody reads), so "at most kGatherLoads outstanding" means the previous run has landed.
+    auto issue = [&](int64_t ch, int buf) {
         const int64_t p0 = ch * pix_per_chunk;
         const int np = (int)min((int64_t)pix_per_chunk, pixels - p0);
-        const uint4* src = reinterpret_cast<const uint4*>(x + p0 * x_cpitch);
-        uint4* dstl = reinterpret_cast<uint4*>(srow);
-        const int n16 = np * row16;
-        for (int i = tid; i < n16; i += kGatherThreads) dstl[i] = src[i];
-        __syncthreads();
+        const int n16 = np * (x_cpitch >> 3);
+        const uint8_t* src = reinterpret_cast<const uint8_t*>(x + p0 * x_cpitch);
+#pragma unroll
+        for (int k = 0; k < kGatherLoads; ++k) {
+            const int i0 = k * kGatherThreads + wave * 64;
+            const int i = min(i0 + lane, n16 - 1);
+            __builtin_amdgcn_global_load_lds((glb_vptr)(uintptr_t)(src + (size_t)i * 16),
+                                             (lds_vptr)(sbuf + buf * kGatherChunk + i0 * 16), 16, 0, 0);
+        }
+    };
+
+    int64_t ch = blockIdx.x;
+    if (ch < nchunks) issue(ch, 0);
+    for (int it = 0; ch < nchunks; ch += gridDim.x, ++it) {
+        const int buf = it & 1;
+        const bool more = ch + gridDim.x < nchunks;
+        if (more) {
+            issue(ch + gridDim.x, buf ^ 1);
+            __builtin_amdgcn_s_waitcnt((kGatherLoads & 15) | (7 << 4) | (15 << 8) | ((kGatherLoads >> 4) << 14));
+        } else {
+            __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();            // this run has landed for every wave
+        asm volatile("" ::: "memory");
+        const int64_t p0 = ch * pix_per_chunk;
+        const int np = (int)min((int64_t)pix_per_chunk, pixels - p0);
         if (active) {
             for (int p = pp; p < np; p += ppb) {
-                const uint16_t* r = srow + (size_t)p * x_cpitch;
-                uint4 o;
-                o.x = r[id[0]] | ((uint32_t)r[id[1]] << 16);
-                o.y = r[id[2]] | ((uint32_t)r[id[3]] << 16);
-                o.z = r[id[4]] | ((uint32_t)r[id[5]] << 16);
-                o.w = r[id[6]] | ((uint32_t)r[id[7]] << 16);
+                const uint32_t r = lds_base + (uint32_t)(buf * kGatherChunk + p * row_bytes);
+                uint32_t e[8];
+                // 16-bit LDS reads issued back to back; one wait, then pairs are packed into the output registers
+#pragma unroll
+                for (int k = 0; k < 8; ++k) asm volatile("ds_read_u16 %0, %1" : "=v"(e[k]) : "v"(r + id2[k]));
+                asm volatile("s_waitcnt lgkmcnt(0)"
+                             : "+v"(e[0]), "+v"(e[1]), "+v"(e[2]), "+v"(e[3]), "+v"(e[4]), "+v"(e[5]), "+v"(e[6]), "+v"(e[7]));
+                const uint32_t o0 = e[0] | (e[1] << 16), o1 = e[2] | (e[3] << 16);
+                const uint32_t o2 = e[4] | (e[5] << 16), o3 = e[6] | (e[7] << 16);
                 uint16_t* dst = out + (p0 + p) * (int64_t)out_cpitch + v * 8;
                 if (nlast >= 8) {
-                    *reinterpret_cast<uint4*>(dst) = o;
+                    *reinterpret_cast<uint4*>(dst) = make_uint4(o0, o1, o2, o3);
                 } else {
-                    const uint16_t* e = reinterpret_cast<const uint16_t*>(&o);
-                    for (int k = 0; k < nlast; ++k) dst[k] = e[k];
+                    const uint32_t w[4] = {o0, o1, o2, o3};
+                    for (int k = 0; k < nlast; ++k) dst[k] = (uint16_t)(w[k >> 1] >> ((k & 1) * 16));
                 }
             }
         }
-        __syncthreads();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();            // everyone is done with this buffer before it is refilled
+        asm volatile("" ::: "memory");
     }
+#endif
 }
 
 // ---- multi-job forms: a network has dozens of layers and edges and each of these steps is tiny, so the job
@@ -396,16 +435,25 @@ extern "C" int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C,
     hipStream_t st = (hipStream_t)stream;
     const bool rows_aligned = (x_cpitch % 8 == 0) && (out_cpitch % 8 == 0) && (((uintptr_t)x & 15) == 0) &&
                               (((uintptr_t)out & 15) == 0);
-    if (rows_aligned && (Cp + 7) / 8 <= kGatherThreads && (size_t)x_cpitch * 2 <= 32 * 1024) {
-        // ~32 KiB of pixel rows per LDS chunk, a multiple of the pixels gathered per pass
+    if (rows_aligned && (Cp + 7) / 8 <= kGatherThreads && (size_t)x_cpitch * 2 <= (size_t)kGatherChunk) {
+        // whole pixel rows per LDS buffer, a multiple of the pixels gathered per pass
         const int nvec = (Cp + 7) / 8, ppb = kGatherThreads / nvec;
-        int ppc = (int)((32 * 1024) / ((size_t)x_cpitch * 2));
+        int ppc = (int)(kGatherChunk / ((size_t)x_cpitch * 2));
         if (ppc > ppb) ppc = ppc / ppb * ppb;
-        if (ppc < 1) ppc = 1;
         const int64_t nchunks = ceil_div(pixels, ppc);
-        const unsigned grid = (unsigned)(nchunks < 256 * 8 ? nchunks : 256 * 8);
-        hipLaunchKernelGGL(k_compact_nhwc_lds, dim3(grid), dim3(kGatherThreads), (size_t)ppc * x_cpitch * 2, st, x, pixels,
-                           x_cpitch, idx, Cp, out, out_cpitch, ppc);
+        const unsigned grid = (unsigned)(nchunks < 512 ? nchunks : 512);  // two resident workgroups per CU
+        static bool attr_set = false;  // one-time opt-in to 64 KiB of dynamic LDS
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_compact_nhwc_lds),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kGatherChunk);
+            if (e != hipSuccess) {
+                set_hip_error(e);
+                return PT_ERR_LAUNCH;
+            }
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(k_compact_nhwc_lds, dim3(grid), dim3(kGatherThreads), 2 * kGatherChunk, st, x, pixels, x_cpitch,
+                           idx, Cp, out, out_cpitch, ppc);
         return launch_status();
     }
     const int64_t work = pixels * ((Cp + 7) / 8);
