@@ -560,49 +560,47 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
     else main_loop(std::true_type{});
     PT_STAMP(2);
 
-    // ---- epilogue: stage the bf16 tile in LDS, then 16-byte row-contiguous stores ------------------
-    constexpr int LDC = BN + 8;  // elements
-    static_assert(BM * LDC * 2 <= 160 * 1024, "epilogue tile must fit in LDS");  // launch sizes LDS for both uses
-    uint16_t* sC = reinterpret_cast<uint16_t*>(smem_b);
-    __syncthreads();
+    // ---- epilogue: registers -> global.  A lane holds, per 32x32 block, channels 8g + 4*(lane/32) + {0..3}
+    // (g = 0..3) of pixel lane%32.  Swapping the upper half-wave of the g-even registers with the lower
+    // half-wave of the g-odd ones leaves every lane with two runs of 8 consecutive channels (16 bytes of bf16).
+    {
+        const int hi = lane >> 5;
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                uint2 o;
-                o.x = cvt_pk_bf16(acc[tn][tm][4 * g + 0], acc[tn][tm][4 * g + 1]);
-                o.y = cvt_pk_bf16(acc[tn][tm][4 * g + 2], acc[tn][tm][4 * g + 3]);
-                *reinterpret_cast<uint2*>(&sC[(wm * WTM + tm * 32 + l32) * LDC + wn * WTN + tn * 32 + 8 * g + (lane >> 5) * 4]) = o;
-            }
-    __syncthreads();
-    constexpr int CV = BN / 8;    // 16-byte vectors per tile row
-    constexpr int RPP = NT / CV;  // rows per pass
-    const int cv = tid % CV, r0 = tid / CV;
-    const int ch = n0 + cv * 8;
-    if (ch < a.Nout) {
-#pragma unroll 4
-        for (int r = r0; r < BM; r += RPP) {
-            const int m = m0 + r;
-            if (m >= a.M) break;
+        for (int tm = 0; tm < TM; ++tm) {
+            const int m = m0 + wm * WTM + tm * 32 + l32;
             int64_t dpix;
             if (a.d_linear) {
                 dpix = (int64_t)m * a.dpitch;
             } else {
-                const uint32_t row = fdiv((uint32_t)m, a.gW), gj = m - row * a.gW.d;
+                const uint32_t mm = (uint32_t)min(m, a.M - 1);
+                const uint32_t row = fdiv(mm, a.gW), gj = mm - row * a.gW.d;
                 const uint32_t n = fdiv(row, a.gH), gi = row - n * a.gH.d;
                 dpix = (((int64_t)n * a.DH + (int)gi * a.d_hmul + a.d_hadd) * a.DW + (int)gj * a.d_wmul + a.d_wadd) * a.dpitch;
             }
-            const uint4 v = *reinterpret_cast<const uint4*>(&sC[r * LDC + cv * 8]);
-            uint16_t* dst = a.D + dpix + ch;
-            if (a.d_vec16 && ch + 7 < a.Nout) {
-                *reinterpret_cast<uint4*>(dst) = v;
-            } else {
-                const uint16_t* e = reinterpret_cast<const uint16_t*>(&v);
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (ch + i < a.Nout) dst[i] = e[i];
+            for (int tn = 0; tn < TN; ++tn) {
+                const int chb = n0 + wn * WTN + tn * 32;
+                if (chb >= a.Nout) continue;  // wave-uniform
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp) {  // register pairs (g = 2gp, 2gp + 1)
+                    const f32x16& c = acc[tn][tm];
+                    const uint32_t p0 = cvt_pk_bf16(c[8 * gp + 0], c[8 * gp + 1]), q0 = cvt_pk_bf16(c[8 * gp + 2], c[8 * gp + 3]);
+                    const uint32_t p1 = cvt_pk_bf16(c[8 * gp + 4], c[8 * gp + 5]), q1 = cvt_pk_bf16(c[8 * gp + 6], c[8 * gp + 7]);
+                    const auto ps = __builtin_amdgcn_permlane32_swap(p0, p1, false, false);
+                    const auto qs = __builtin_amdgcn_permlane32_swap(q0, q1, false, false);
+                    const int ch = chb + 16 * gp + 8 * hi;
+                    if (m < a.M && ch < a.Nout) {
+                        uint16_t* dst = a.D + dpix + ch;
+                        if (a.d_vec16 && ch + 7 < a.Nout) {
+                            *reinterpret_cast<uint4*>(dst) = make_uint4(ps[0], qs[0], ps[1], qs[1]);
+                        } else {
+                            const uint32_t w[4] = {ps[0], qs[0], ps[1], qs[1]};
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (ch + e < a.Nout) dst[e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                        }
+                    }
+                }
             }
         }
     }
@@ -613,8 +611,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 template <int BM, int BN, int WGM, int WGN, int STAGES>
 inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
     constexpr int NT = 64 * WGM * WGN;
-    constexpr size_t lds_pipe = (size_t)STAGES * (BM + BN) * 128, lds_epi = (size_t)BM * (BN + 8) * 2;
-    constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
+    constexpr size_t lds = (size_t)STAGES * (BM + BN) * 128;
     static_assert(lds <= 160 * 1024, "LDS capacity");
     // last channel block of a tap is short and/or some chunk has a masked tail
     const bool ragged = (a.Cred % 64) != 0 || (a.fold && a.Creal % 8 != 0);
