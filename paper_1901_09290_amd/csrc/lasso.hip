@@ -30,6 +30,7 @@ struct NormJob {
     float* in_norm;
     int K, RS, C, cpitch;
     int first_block, n_chunks, rows_per_chunk, txlog2;
+    int fin_first, pad;  // first workgroup of this job in the finish kernel
 };
 struct NormJobs {
     NormJob j[kMaxJobs];
@@ -150,20 +151,29 @@ __global__ __launch_bounds__(kThreads) void k_group_norms_partial(const NormJobs
     }
 }
 
-// One thread per group: K filters then C input channels of each job.
+// Sixteen lanes per group (K filters, then C input channels of each job): the lanes stride over the R*S row
+// sums of a filter / the per-chunk partials of a channel, then a fixed shuffle tree adds the 16 lane sums.
+// The order of additions depends only on the shapes, so results are run-to-run identical.
+constexpr int kFinLanes = 16, kFinGroups = kThreads / kFinLanes;
 __global__ __launch_bounds__(kThreads) void k_group_norms_finish(const NormJobs jobs) {
-    const int ji = blockIdx.y;
+    int ji = 0;
+    for (int i = 1; i < jobs.n; ++i)
+        if ((int)blockIdx.x >= jobs.j[i].fin_first) ji = i;
     const NormJob& J = jobs.j[ji];
-    const int g = blockIdx.x * kThreads + threadIdx.x;
-    if (g < J.K) {
-        float s = 0.f;
-        for (int t = 0; t < J.RS; ++t) s += J.rowsq[(size_t)g * J.RS + t];
-        J.out_norm[g] = sqrtf(s);
-    } else if (g < J.K + J.C) {
+    const int l = threadIdx.x & (kFinLanes - 1);
+    const int g = (blockIdx.x - J.fin_first) * kFinGroups + (threadIdx.x / kFinLanes);
+    const bool live = g < J.K + J.C;
+    float s = 0.f;
+    if (live && g < J.K) {
+        for (int t = l; t < J.RS; t += kFinLanes) s += J.rowsq[(size_t)g * J.RS + t];
+    } else if (live) {
         const int c = g - J.K;
-        float s = 0.f;
-        for (int b = 0; b < J.n_chunks; ++b) s += J.colpart[(size_t)b * J.C + c];
-        J.in_norm[c] = sqrtf(s);
+        for (int b = l; b < J.n_chunks; b += kFinLanes) s += J.colpart[(size_t)b * J.C + c];
+    }
+    for (int off = kFinLanes / 2; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if (live && l == 0) {
+        if (g < J.K) J.out_norm[g] = sqrtf(s);
+        else J.in_norm[g - J.K] = sqrtf(s);
     }
 }
 
@@ -294,7 +304,7 @@ extern "C" int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_
         const bool want_vec = pass == 0;
         NormJobs jobs;
         jobs.n = 0;
-        int blocks = 0, maxg = 0;
+        int blocks = 0, fin_blocks = 0;
         auto flush = [&]() -> int32_t {
             if (jobs.n == 0) return PT_OK;
             if (want_vec)
@@ -303,11 +313,10 @@ extern "C" int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_
                 hipLaunchKernelGGL(k_group_norms_partial<1>, dim3(blocks), dim3(kThreads), 0, st, jobs);
             int32_t rc = launch_status();
             if (rc != PT_OK) return rc;
-            hipLaunchKernelGGL(k_group_norms_finish, dim3((unsigned)ceil_div(maxg, kThreads), jobs.n), dim3(kThreads), 0, st,
-                               jobs);
+            hipLaunchKernelGGL(k_group_norms_finish, dim3((unsigned)fin_blocks), dim3(kThreads), 0, st, jobs);
             jobs.n = 0;
             blocks = 0;
-            maxg = 0;
+            fin_blocks = 0;
             return launch_status();
         };
         char* p = wsp;
@@ -323,8 +332,9 @@ extern "C" int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_
                 J.rowsq = (float*)p; J.colpart = (float*)p + rows;
                 J.K = L.K; J.RS = L.RS; J.C = L.C; J.cpitch = L.w_cpitch;
                 J.first_block = blocks; J.n_chunks = cp.n_chunks; J.rows_per_chunk = cp.rows_per_chunk; J.txlog2 = cp.txlog2;
+                J.fin_first = fin_blocks; J.pad = 0;
                 blocks += cp.n_chunks;
-                if (L.K + L.C > maxg) maxg = L.K + L.C;
+                fin_blocks += (int)ceil_div(L.K + L.C, kFinGroups);
                 if (jobs.n == kMaxJobs) {
                     int32_t rc = flush();
                     if (rc != PT_OK) return rc;
