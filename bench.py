@@ -250,6 +250,16 @@ def main():
                 "tflops": round(dom_flops / dom_s / 1e12, 2), "frac_mfma_peak": round(dom_flops / dom_s / 1e12 / PEAK_BF16_TFLOPS, 4),
                 "frac_of_per_layer_roof": round(t_roof / dom_s, 4)}
 
+    # HBM traffic of the dominant family, measured separately with hardware counters (this file is written from
+    # two `rocprofv3 --pmc` runs of this script; see its header for the commands and the scale factors)
+    tpath = os.path.join(ROOT, "profiles", "bench_resnet50_b64_hbm_traffic.txt")
+    if dom == "bwd_weight" and os.path.exists(tpath):
+        import re
+        m = re.search(r"per pt_conv_bwd_weight call .*?= ([0-9.]+) MB of HBM traffic", open(tpath).read())
+        if m:
+            roofline["traffic"] = float(m.group(1)) * 1e6
+            roofline["traffic_unit"] = "bytes per launch (FETCH_SIZE x 2.0 + WRITE_SIZE, from profiles/)"
+
     ab = rmodel.algorithmic_bytes()
     sweep_bytes = sum(ab.values())
     t_sweep = t_detect + t_compact
