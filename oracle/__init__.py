@@ -154,6 +154,22 @@ def group_lasso_grad(w, out_norm, in_norm, lam: float, flags: int, dw) -> np.nda
     return g.reshape(w.shape)
 
 
+def group_lasso_penalty(layers) -> float:
+    """layers: iterable of (out_norm, in_norm, flags); the regulariser's value summed over them."""
+    p = C.c_double(0.0)
+    for on, inn, flags in layers:
+        on, inn = _d(on), _d(inn)
+        _check(_load().oracle_group_lasso_penalty(_p(on), on.size, _p(inn), inn.size, C.c_uint32(flags), C.byref(p)),
+               "group_lasso_penalty")
+    return p.value
+
+
+def set_coeff(loss1: float, loss2: float, ratio: float) -> float:
+    lam = C.c_double(0.0)
+    _check(_load().oracle_set_coeff(C.c_double(loss1), C.c_double(loss2), C.c_double(ratio), C.byref(lam)), "set_coeff")
+    return lam.value
+
+
 def zero_groups(norms, thr: float) -> np.ndarray:
     norms = _d(norms)
     z = np.empty(norms.size, dtype=np.uint8)

@@ -238,6 +238,26 @@ int oracle_group_lasso_grad(const double* w, const double* out_norm, const doubl
     return 0;
 }
 
+int oracle_group_lasso_penalty(const double* out_norm, int32_t K, const double* in_norm, int32_t C, uint32_t flags,
+                               double* penalty) {
+    if (!penalty || (K > 0 && !out_norm) || (C > 0 && !in_norm)) return -1;
+    if (K < 0 || C < 0) return -2;
+    double p = 0.0;
+    if (flags & 1u)
+        for (int k = 0; k < K; ++k) p += out_norm[k];
+    if (flags & 2u)
+        for (int c = 0; c < C; ++c) p += in_norm[c];
+    *penalty += p;
+    return 0;
+}
+
+int oracle_set_coeff(double loss1, double loss2, double ratio, double* lambda) {
+    if (!lambda) return -1;
+    if (!(ratio > 0.0 && ratio < 1.0) || !(loss2 > 0.0) || !(loss1 >= 0.0)) return -2;
+    *lambda = ratio * loss1 / ((1.0 - ratio) * loss2);
+    return 0;
+}
+
 int oracle_zero_groups(const double* norms, int32_t n, double thr, uint8_t* zero) {
     if (!norms || !zero) return -1;
     if (n < 0) return -2;

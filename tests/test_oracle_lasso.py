@@ -130,3 +130,58 @@ def test_zero_groups_threshold_is_strict():
     w = _rand((4, 3, 3, 4), 9) * 1e-4
     on, _ = oracle.group_norms(w)
     assert np.all(on >= np.abs(w).reshape(4, -1).max(axis=1))
+
+
+def test_penalty_value_and_first_layer_exemption():
+    """GroupLassoReg of Alg. 1: the plain sum of group norms, one global coefficient (no size weighting);
+    flags drop a layer's input or output groups.  Pinned to the hand example and to numpy sums."""
+    g = _golden()
+    w = np.array([[3.0, 0.0], [4.0, 0.0]]).reshape(2, 1, 1, 2)
+    on, inn = oracle.group_norms(w)
+    assert oracle.group_lasso_penalty([(on, inn, 3)]) == g["penalty"][0]
+    assert oracle.group_lasso_penalty([(on, inn, 1)]) == g["penalty_out_only"][0]
+    assert oracle.group_lasso_penalty([(on, inn, 0)]) == 0.0
+    layers, want = [], 0.0
+    for i, shape in enumerate([(8, 3, 3, 3), (16, 1, 1, 8), (5, 3, 3, 16)]):
+        v = _rand(shape, 40 + i)
+        a, b = oracle.group_norms(v)
+        flags = 1 if i == 0 else 3          # the first convolution's input groups are exempt
+        layers.append((a, b, flags))
+        want += np.sqrt((v ** 2).sum(axis=(1, 2, 3))).sum()
+        if flags & 2:
+            want += np.sqrt((v ** 2).sum(axis=(0, 1, 2))).sum()
+    assert abs(oracle.group_lasso_penalty(layers) - want) < 1e-12 * want
+
+
+def test_penalty_is_what_the_gradient_differentiates():
+    """Finite differences of the oracle's own penalty value (not a retyped formula) reproduce the oracle's gradient,
+    including the exemption flags."""
+    w = _rand((4, 3, 3, 3), 55)
+    for flags in (1, 2, 3):
+        on, inn = oracle.group_norms(w)
+        g = oracle.group_lasso_grad(w, on, inn, 1.0, flags, np.zeros_like(w))
+        rng = np.random.Generator(np.random.PCG64(56))
+        for _ in range(10):
+            i = tuple(rng.integers(0, d) for d in w.shape)
+            wp, wm = w.copy(), w.copy()
+            wp[i] += 1e-6
+            wm[i] -= 1e-6
+            pp = oracle.group_lasso_penalty([(*oracle.group_norms(wp), flags)])
+            pm = oracle.group_lasso_penalty([(*oracle.group_norms(wm), flags)])
+            assert abs((pp - pm) / 2e-6 - g[i]) < 1e-8
+
+
+def test_set_coeff_solves_the_penalty_ratio_equation():
+    g = _golden()
+    lam = oracle.set_coeff(g["set_coeff_loss1"][0], g["penalty"][0], g["set_coeff_ratio"][0])
+    assert lam == g["set_coeff_lambda"][0]
+    rng = np.random.Generator(np.random.PCG64(57))
+    for _ in range(20):
+        l1, l2, r = rng.uniform(0.1, 10), rng.uniform(1, 5000), rng.uniform(0.05, 0.6)
+        lam = oracle.set_coeff(l1, l2, r)
+        assert abs(lam * l2 / (l1 + lam * l2) - r) < 1e-14      # plugging back gives the wanted ratio
+    # larger wanted ratio -> larger coefficient; invalid inputs are refused
+    assert oracle.set_coeff(2.0, 100.0, 0.25) > oracle.set_coeff(2.0, 100.0, 0.20)
+    for bad in ((1.0, 10.0, 0.0), (1.0, 10.0, 1.0), (1.0, 0.0, 0.2), (-1.0, 10.0, 0.2)):
+        with pytest.raises(Exception):
+            oracle.set_coeff(*bad)
