@@ -152,6 +152,26 @@ int32_t pt_group_norms_batched_workspace_bytes(const pt_layer_weights* layers, i
 int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_t n, void* ws, size_t ws_bytes, void* stream);
 int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int32_t n, float lambda, void* stream);
 
+/* Value of the regulariser over a whole network (GroupLassoReg of Alg. 1, Eq. 1-2):
+ *   *penalty_dev = sum over layers of ( a * sum_k out_norm[k] + b * sum_c in_norm[c] ),  a, b = flags bits.
+ * No weighting by group size (one global coefficient, Sec. 3.1).  The norms are those pt_group_norms wrote;
+ * `layers` is a HOST array whose pointers are device pointers; penalty_dev is a device double, overwritten
+ * (0 for n == 0).  fp64 accumulation in a fixed order: run-to-run identical.  One small launch per 96 layers. */
+typedef struct pt_layer_penalty {
+    const float* out_norm; /* [K] */
+    const float* in_norm;  /* [C] */
+    int32_t K, C;
+    uint32_t flags;        /* PT_LASSO_OUT | PT_LASSO_IN */
+    uint32_t reserved;
+} pt_layer_penalty;
+int32_t pt_group_lasso_penalty_batched(const pt_layer_penalty* layers, int32_t n, double* penalty_dev, void* stream);
+
+/* Host-only: SetCoeff of Alg. 1.  The coefficient for which the regulariser makes up `ratio` of the total loss at
+ * the first iteration (penalty-ratio equation of Sec. 3.1; the paper uses 0.20-0.25):
+ *   ratio = lambda*loss2 / (loss1 + lambda*loss2)   =>   lambda = ratio*loss1 / ((1 - ratio)*loss2),
+ * loss1 = classification loss, loss2 = the value above.  PT_ERR_SHAPE unless 0 < ratio < 1, loss2 > 0, loss1 >= 0. */
+int32_t pt_lasso_set_coeff(double loss1, double loss2, double ratio, double* lambda);
+
 /* ---- reconfiguration: Sec. 4.1-4.2 ---------------------------------------------------------- */
 
 /* zero[g] = (norms[g] < thr) ? 1 : 0, compared in fp32; thr <= 0 marks nothing. n may be 0. */

@@ -28,6 +28,7 @@ EXPORTS = [
     "pt_zero_groups", "pt_reconcile_edge", "pt_compact_plan",
     "pt_compact_weights", "pt_compact_vector", "pt_compact_nhwc",
     "pt_weights_to_crsk_batched", "pt_conv_bwd_data_crsk",
+    "pt_group_lasso_penalty_batched", "pt_lasso_set_coeff",
     "pt_zero_groups_batched", "pt_reconcile_plan_batched", "pt_compact_vector_batched", "pt_compact_weights_batched",
 ]
 
@@ -59,6 +60,11 @@ class LayerLasso(C.Structure):
 class LayerCrsk(C.Structure):
     _fields_ = [("w", C.c_void_p), ("wt", C.c_void_p), ("K", C.c_int32), ("RS", C.c_int32), ("C", C.c_int32),
                 ("w_cpitch", C.c_int32)]
+
+
+class LayerPenalty(C.Structure):
+    _fields_ = [("out_norm", C.c_void_p), ("in_norm", C.c_void_p), ("K", C.c_int32), ("C", C.c_int32),
+                ("flags", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class NormMask(C.Structure):
@@ -113,6 +119,8 @@ def lib() -> C.CDLL:
             "pt_compact_nhwc": [vp, i64, i32, i32, vp, i32, vp, i32, vp],
             "pt_weights_to_crsk_batched": [C.POINTER(LayerCrsk), i32, vp],
             "pt_conv_bwd_data_crsk": [dp, vp, vp, vp, vp],
+            "pt_group_lasso_penalty_batched": [C.POINTER(LayerPenalty), i32, vp, vp],
+            "pt_lasso_set_coeff": [C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)],
             "pt_zero_groups_batched": [C.POINTER(NormMask), i32, f32, vp],
             "pt_reconcile_plan_batched": [C.POINTER(EdgePlan), i32, vp],
             "pt_compact_vector_batched": [C.POINTER(GatherVector), i32, vp],
@@ -329,3 +337,20 @@ def weights_to_crsk_batched(layers, stream=None) -> None:
 
 def conv_bwd_data_crsk(d: ConvDesc, dy, wt, dx, stream=None) -> None:
     _ck("pt_conv_bwd_data_crsk", lib().pt_conv_bwd_data_crsk(C.byref(d), _ptr(dy), _ptr(wt), _ptr(dx), _stream(stream)))
+
+
+def layer_penalty(out_norm, in_norm, K: int, Cc: int, flags: int) -> LayerPenalty:
+    return LayerPenalty(_ptr(out_norm), _ptr(in_norm), K, Cc, flags, 0)
+
+
+def group_lasso_penalty_batched(layers, penalty_dev, stream=None) -> None:
+    """penalty_dev: a float64 device tensor with one element."""
+    arr = _array(layers, LayerPenalty)
+    _ck("pt_group_lasso_penalty_batched",
+        lib().pt_group_lasso_penalty_batched(arr, len(layers), _ptr(penalty_dev), _stream(stream)))
+
+
+def lasso_set_coeff(loss1: float, loss2: float, ratio: float) -> float:
+    lam = C.c_double(0.0)
+    _ck("pt_lasso_set_coeff", lib().pt_lasso_set_coeff(loss1, loss2, ratio, C.byref(lam)))
+    return lam.value

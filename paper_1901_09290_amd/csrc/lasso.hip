@@ -267,6 +267,44 @@ static size_t layer_ws_bytes(const pt_layer_weights& L) {
     return (size_t)round_up((rows + (int64_t)n_chunks * L.C) * 4, 256);
 }
 
+// Value of the regulariser (GroupLassoReg of Alg. 1): the sum of the enabled group norms of up to
+// kMaxPenaltyJobs layers, ONE workgroup, fp64 accumulation in a fixed order (thread t adds elements
+// t, t+1024, ... of the concatenated norm vectors; a fixed tree adds the 1024 thread sums), so the value is
+// run-to-run identical.  A few 10^4 floats: the launch's fixed cost is all of it.
+constexpr int kMaxPenaltyJobs = 96;
+struct PenaltyJob {
+    const float* out_norm;
+    const float* in_norm;
+    int K, C;  // 0 when that group kind is not regularised
+};
+struct PenaltyJobs {
+    PenaltyJob j[kMaxPenaltyJobs];
+    int n, accumulate;
+};
+__global__ __launch_bounds__(1024) void k_group_lasso_penalty(const PenaltyJobs jobs, double* __restrict__ penalty) {
+    __shared__ double red[1024];
+    const int tid = threadIdx.x;
+    double s = 0.0;
+    int base = 0;  // position of the current vector in the concatenation, modulo 1024
+    for (int i = 0; i < jobs.n; ++i) {
+        const PenaltyJob& J = jobs.j[i];
+        for (int v = 0; v < 2; ++v) {
+            const float* p = v == 0 ? J.out_norm : J.in_norm;
+            const int n = v == 0 ? J.K : J.C;
+            // element e of this vector belongs to thread (base + e) % 1024
+            for (int e = (tid - base + 1024) & 1023; e < n; e += 1024) s += (double)p[e];
+            base = (base + n) & 1023;
+        }
+    }
+    red[tid] = s;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if (tid < w) red[tid] += red[tid + w];
+        __syncthreads();
+    }
+    if (tid == 0) *penalty = (jobs.accumulate ? *penalty : 0.0) + red[0];
+}
+
 }  // namespace pt
 
 using namespace pt;
@@ -422,4 +460,41 @@ extern "C" int32_t pt_group_lasso_grad(const float* w, const float* out_norm, co
     L.w = w; L.out_norm = out_norm; L.in_norm = in_norm; L.dw = dw;
     L.K = K; L.RS = RS; L.C = C; L.w_cpitch = w_cpitch; L.flags = flags;
     return pt_group_lasso_grad_batched(&L, 1, lambda, stream);
+}
+
+extern "C" int32_t pt_group_lasso_penalty_batched(const pt_layer_penalty* layers, int32_t n, double* penalty_dev,
+                                                  void* stream) {
+    if (n < 0) return PT_ERR_SHAPE;
+    if (!penalty_dev || (n > 0 && !layers)) return PT_ERR_NULL;
+    for (int i = 0; i < n; ++i) {
+        if (layers[i].K < 0 || layers[i].C < 0) return PT_ERR_SHAPE;
+        if (layers[i].flags & ~(PT_LASSO_OUT | PT_LASSO_IN)) return PT_ERR_UNSUPPORTED;
+        if (((layers[i].flags & PT_LASSO_OUT) && layers[i].K > 0 && !layers[i].out_norm) ||
+            ((layers[i].flags & PT_LASSO_IN) && layers[i].C > 0 && !layers[i].in_norm))
+            return PT_ERR_NULL;
+    }
+    PenaltyJobs jobs;
+    jobs.n = 0;
+    jobs.accumulate = 0;
+    int i = 0;
+    do {  // at least one launch, so that n == 0 writes 0
+        for (; i < n && jobs.n < kMaxPenaltyJobs; ++i) {
+            const pt_layer_penalty& L = layers[i];
+            jobs.j[jobs.n++] = PenaltyJob{L.out_norm, L.in_norm, (L.flags & PT_LASSO_OUT) ? L.K : 0,
+                                          (L.flags & PT_LASSO_IN) ? L.C : 0};
+        }
+        hipLaunchKernelGGL(k_group_lasso_penalty, dim3(1), dim3(1024), 0, (hipStream_t)stream, jobs, penalty_dev);
+        const int32_t rc = launch_status();
+        if (rc != PT_OK) return rc;
+        jobs.n = 0;
+        jobs.accumulate = 1;
+    } while (i < n);
+    return PT_OK;
+}
+
+extern "C" int32_t pt_lasso_set_coeff(double loss1, double loss2, double ratio, double* lambda) {
+    if (!lambda) return PT_ERR_NULL;
+    if (!(ratio > 0.0 && ratio < 1.0) || !(loss2 > 0.0) || !(loss1 >= 0.0)) return PT_ERR_SHAPE;
+    *lambda = ratio * loss1 / ((1.0 - ratio) * loss2);
+    return PT_OK;
 }

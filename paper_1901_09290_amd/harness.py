@@ -151,6 +151,9 @@ class Network:
         crsk = [B.layer_crsk(l.w_bf16, l.w_crsk, l.spec.K, l.RS, l.spec.C, l.wp) for l in self.layers
                 if l.w_crsk is not None]
         self.crsk_jobs = (B.LayerCrsk * len(crsk))(*crsk) if crsk else None
+        pen = [B.layer_penalty(l.out_norm, l.in_norm, l.spec.K, l.spec.C, l.lasso_flags) for l in self.layers]
+        self.penalty_jobs = (B.LayerPenalty * len(pen))(*pen)
+        self.penalty = torch.zeros(1, dtype=torch.float64, device=DEV)
         # weight gradients run on a second stream, off the critical path of the input-gradient chain
         self.side = torch.cuda.Stream()
         self.overlap_wgrad = True
@@ -184,6 +187,12 @@ class Network:
                 l.bwd_data_crsk()
             main.wait_stream(self.side)
         B.group_lasso_grad_batched(self.lasso_jobs, lam)
+
+    def regulariser_value(self) -> None:
+        """GroupLassoReg of Alg. 1 from the norms of the last train_step / norms call: one launch, result in
+        self.penalty (device fp64 scalar).  With the first iteration's classification loss it gives the
+        coefficient through binding.lasso_set_coeff (SetCoeff)."""
+        B.group_lasso_penalty_batched(self.penalty_jobs, self.penalty)
 
     @property
     def step_flops(self) -> int:

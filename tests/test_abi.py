@@ -117,3 +117,24 @@ def test_crsk_calls_validate_on_the_host(lib):
     d = B.conv_desc(1, 4, 4, 8, 8, 1, 1, 1, 0)
     assert lib.pt_conv_bwd_data_crsk(C.byref(d), None, None, None, None) == -1
     assert lib.pt_conv_bwd_data_crsk(C.byref(d), fake, 8, fake, None) == -2   # wt not 16-byte aligned
+
+
+def test_penalty_and_set_coeff_validate_on_the_host(lib):
+    import oracle
+    fake = 256
+    assert lib.pt_group_lasso_penalty_batched(None, 0, None, None) == -1       # no result pointer
+    assert lib.pt_group_lasso_penalty_batched(None, 2, fake, None) == -1
+    j = (B.LayerPenalty * 1)(B.LayerPenalty(fake, fake, -1, 4, 3, 0))
+    assert lib.pt_group_lasso_penalty_batched(j, 1, fake, None) == -2
+    j = (B.LayerPenalty * 1)(B.LayerPenalty(fake, fake, 4, 4, 8, 0))
+    assert lib.pt_group_lasso_penalty_batched(j, 1, fake, None) == -4          # unknown flag bit
+    j = (B.LayerPenalty * 1)(B.LayerPenalty(None, fake, 4, 4, 3, 0))
+    assert lib.pt_group_lasso_penalty_batched(j, 1, fake, None) == -1
+    # SetCoeff is pure host arithmetic: identical to the oracle's, refuses what the oracle refuses
+    for l1, l2, r in ((36.0, 12.0, 0.25), (2.3, 5311.7, 0.2), (0.0, 3.0, 0.5)):
+        assert B.lasso_set_coeff(l1, l2, r) == oracle.set_coeff(l1, l2, r)
+    for bad in ((1.0, 10.0, 0.0), (1.0, 10.0, 1.0), (1.0, 0.0, 0.2), (-1.0, 10.0, 0.2), (1.0, 10.0, float("nan"))):
+        with pytest.raises(B.PruneTrainError) as e:
+            B.lasso_set_coeff(*bad)
+        assert e.value.status == -2
+    assert lib.pt_lasso_set_coeff(1.0, 1.0, 0.5, None) == -1

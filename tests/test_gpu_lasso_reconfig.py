@@ -369,3 +369,40 @@ def test_multi_job_reconfiguration_equals_single_calls_and_oracle():
         if ik is not None:
             for v, o in zip(a.bn[i], a.bn_out[i]):
                 assert np.array_equal(o.cpu().numpy()[:Kp], oracle.compact_vector(v.cpu().numpy(), ik))
+
+
+def test_regulariser_value_matches_oracle_and_is_deterministic():
+    """GroupLassoReg over a whole network (ResNet-32 shapes + a 100-layer stack that needs two launches):
+    device fp64 sum of the device's fp32 norms vs the oracle's fp64 sum of fp64 norms, 1e-5 relative; exact
+    against the fp64 sum of the device's own norms; identical on a second run; first-layer exemption honoured."""
+    from gpu_util import DEV, F32_TOL
+    specs, _ = wl.resnet32_layers(N=2)
+    specs = list(specs) + [wl.ConvSpec(f"x{i}", 1, 4, 4, 5 + i % 7, 3 + i % 11, 1, 1, 1, 0, None, None) for i in range(100)]
+    rng = np.random.Generator(np.random.PCG64(91))
+    jobs, ref_layers, dev_sum, keep = [], [], 0.0, []
+    for i, s in enumerate(specs):
+        w = wl.master_weights(s, rng)
+        flags = 1 if s.first else 3
+        wd, on, inn, _ = _norms_gpu(w, shadow=False)
+        keep += [wd, on, inn]
+        jobs.append(B.layer_penalty(on, inn, s.K, s.C, flags))
+        a, b = oracle.group_norms(w)
+        ref_layers.append((a, b, flags))
+        dev_sum += float(on.double().sum()) + (float(inn.double().sum()) if flags & 2 else 0.0)
+    out = torch.full((1,), float("nan"), dtype=torch.float64, device=DEV)
+    B.group_lasso_penalty_batched(jobs, out)
+    torch.cuda.synchronize()
+    got = out.item()
+    ref = oracle.group_lasso_penalty(ref_layers)
+    assert abs(got - ref) <= F32_TOL * ref
+    assert abs(got - dev_sum) <= 1e-12 * ref          # the reduction itself is fp64
+    out2 = torch.zeros(1, dtype=torch.float64, device=DEV)
+    B.group_lasso_penalty_batched(jobs, out2)
+    torch.cuda.synchronize()
+    assert out2.item() == got
+    B.group_lasso_penalty_batched([], out2)            # no layers: the value is 0
+    torch.cuda.synchronize()
+    assert out2.item() == 0.0
+    # the coefficient that makes the regulariser 25 % of the total loss at a classification loss of 6.9
+    lam = B.lasso_set_coeff(6.9, got, 0.25)
+    assert abs(lam * got / (6.9 + lam * got) - 0.25) < 1e-12
