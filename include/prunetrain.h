@@ -250,6 +250,17 @@ int32_t pt_compact_weights_batched(const pt_gather_weights* jobs, int32_t n_jobs
 int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const int32_t* idx,
                         int32_t Cp, uint16_t* out, int32_t out_cpitch, void* stream);
 
+/* Several activation tensors in one call (jobs: HOST array, device pointers inside; per job the semantics of
+ * pt_compact_nhwc).  Tensors with 16-byte aligned rows share launches of the streaming kernel. */
+typedef struct pt_gather_nhwc {
+    const uint16_t* x;
+    const int32_t* idx;
+    uint16_t* out;
+    int64_t pixels;
+    int32_t C, x_cpitch, Cp, out_cpitch;
+} pt_gather_nhwc;
+int32_t pt_compact_nhwc_batched(const pt_gather_nhwc* jobs, int32_t n_jobs, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

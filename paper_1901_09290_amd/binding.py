@@ -28,7 +28,7 @@ EXPORTS = [
     "pt_zero_groups", "pt_reconcile_edge", "pt_compact_plan",
     "pt_compact_weights", "pt_compact_vector", "pt_compact_nhwc",
     "pt_weights_to_crsk_batched", "pt_conv_bwd_data_crsk",
-    "pt_group_lasso_penalty_batched", "pt_lasso_set_coeff",
+    "pt_group_lasso_penalty_batched", "pt_lasso_set_coeff", "pt_compact_nhwc_batched",
     "pt_zero_groups_batched", "pt_reconcile_plan_batched", "pt_compact_vector_batched", "pt_compact_weights_batched",
 ]
 
@@ -65,6 +65,11 @@ class LayerCrsk(C.Structure):
 class LayerPenalty(C.Structure):
     _fields_ = [("out_norm", C.c_void_p), ("in_norm", C.c_void_p), ("K", C.c_int32), ("C", C.c_int32),
                 ("flags", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class GatherNhwc(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("idx", C.c_void_p), ("out", C.c_void_p), ("pixels", C.c_int64),
+                ("C", C.c_int32), ("x_cpitch", C.c_int32), ("Cp", C.c_int32), ("out_cpitch", C.c_int32)]
 
 
 class NormMask(C.Structure):
@@ -121,6 +126,7 @@ def lib() -> C.CDLL:
             "pt_conv_bwd_data_crsk": [dp, vp, vp, vp, vp],
             "pt_group_lasso_penalty_batched": [C.POINTER(LayerPenalty), i32, vp, vp],
             "pt_lasso_set_coeff": [C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)],
+            "pt_compact_nhwc_batched": [C.POINTER(GatherNhwc), i32, vp],
             "pt_zero_groups_batched": [C.POINTER(NormMask), i32, f32, vp],
             "pt_reconcile_plan_batched": [C.POINTER(EdgePlan), i32, vp],
             "pt_compact_vector_batched": [C.POINTER(GatherVector), i32, vp],
@@ -354,3 +360,12 @@ def lasso_set_coeff(loss1: float, loss2: float, ratio: float) -> float:
     lam = C.c_double(0.0)
     _ck("pt_lasso_set_coeff", lib().pt_lasso_set_coeff(loss1, loss2, ratio, C.byref(lam)))
     return lam.value
+
+
+def gather_nhwc(x, pixels: int, Cc: int, x_cpitch: int, idx, Cp: int, out, out_cpitch: int) -> GatherNhwc:
+    return GatherNhwc(_ptr(x), _ptr(idx), _ptr(out), pixels, Cc, x_cpitch, Cp, out_cpitch)
+
+
+def compact_nhwc_batched(jobs, stream=None) -> None:
+    arr = _array(jobs, GatherNhwc)
+    _ck("pt_compact_nhwc_batched", lib().pt_compact_nhwc_batched(arr, len(jobs), _stream(stream)))

@@ -129,33 +129,48 @@ constexpr int kGatherLoads = kGatherChunk / (kGatherThreads * 16);  // 16-byte l
 typedef __attribute__((address_space(3))) void* lds_vptr;
 typedef const __attribute__((address_space(1))) void* glb_vptr;
 
-__global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const uint16_t* __restrict__ x, int64_t pixels,
-                                                                      int x_cpitch, const int* __restrict__ idx, int Cp,
-                                                                      uint16_t* __restrict__ out, int out_cpitch,
-                                                                      int pix_per_chunk) {
+// Up to kMaxGatherJobs activation tensors per launch: runs ("chunks") of all tensors form one global sequence
+// that the workgroups walk with a fixed stride; a workgroup re-reads its eight channel indices only when the
+// tensor changes between two of its runs.
+constexpr int kMaxGatherJobs = 64;
+struct GatherJob {
+    const uint16_t* x;
+    const int* idx;
+    uint16_t* out;
+    int64_t pixels;
+    int x_cpitch, Cp, out_cpitch, ppc;  // ppc: pixels per run
+    int chunk0, pad;                    // first run of this tensor in the global sequence
+};
+struct GatherJobs {
+    GatherJob j[kMaxGatherJobs];
+    int n, total_chunks;
+};
+
+__global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const GatherJobs jobs) {
 #if defined(__HIP_DEVICE_COMPILE__)
     extern __shared__ __attribute__((aligned(16))) uint8_t sbuf[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nvec = (Cp + 7) >> 3;
-    const int ppb = kGatherThreads / nvec;       // pixels gathered per pass (nvec <= 256)
-    const int pp = tid / nvec, v = tid - pp * nvec;
-    const bool active = pp < ppb;
-    uint32_t id2[8];                             // byte offset of each source channel inside a pixel row
-#pragma unroll
-    for (int e = 0; e < 8; ++e) id2[e] = (active && v * 8 + e < Cp) ? 2u * (uint32_t)idx[v * 8 + e] : 0u;
-    const int nlast = Cp - v * 8;                // valid channels of this thread's vector (>= 8: all)
-    const int row_bytes = x_cpitch * 2;
-    const int64_t nchunks = (pixels + pix_per_chunk - 1) / pix_per_chunk;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_vptr)sbuf;
+    const int total = jobs.total_chunks;
 
+    auto job_of = [&](int g) {  // last job whose chunk0 <= g (uniform)
+        int lo = 0, hi = jobs.n - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (jobs.j[mid].chunk0 <= g) lo = mid;
+            else hi = mid - 1;
+        }
+        return lo;
+    };
     // Every wave issues exactly kGatherLoads load instructions per run (lanes past the run's end re-read its last
     // 16 bytes into a slot nobody reads), so "at most kGatherLoads outstanding" means the previous run has landed.
-    auto issue = [&](int64_t ch, int buf) {
-        const int64_t p0 = ch * pix_per_chunk;
-        const int np = (int)min((int64_t)pix_per_chunk, pixels - p0);
-        const int n16 = np * (x_cpitch >> 3);
-        const uint8_t* src = reinterpret_cast<const uint8_t*>(x + p0 * x_cpitch);
+    auto issue = [&](int g, int buf) {
+        const GatherJob& J = jobs.j[job_of(g)];
+        const int64_t p0 = (int64_t)(g - J.chunk0) * J.ppc;
+        const int np = (int)min((int64_t)J.ppc, J.pixels - p0);
+        const int n16 = np * (J.x_cpitch >> 3);
+        const uint8_t* src = reinterpret_cast<const uint8_t*>(J.x + p0 * J.x_cpitch);
 #pragma unroll
         for (int k = 0; k < kGatherLoads; ++k) {
             const int i0 = k * kGatherThreads + wave * 64;
@@ -165,13 +180,18 @@ __global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const uint1
         }
     };
 
-    int64_t ch = blockIdx.x;
-    if (ch < nchunks) issue(ch, 0);
-    for (int it = 0; ch < nchunks; ch += gridDim.x, ++it) {
+    // gather-side state of the current tensor
+    int cur = -1, ppb = 1, pp = 0, v = 0, nlast = 0, row_bytes = 0;
+    bool active = false;
+    uint32_t id2[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // byte offset of each source channel inside a pixel row
+
+    int g = blockIdx.x;
+    if (g < total) issue(g, 0);
+    for (int it = 0; g < total; g += gridDim.x, ++it) {
         const int buf = it & 1;
-        const bool more = ch + gridDim.x < nchunks;
+        const bool more = g + (int)gridDim.x < total;
         if (more) {
-            issue(ch + gridDim.x, buf ^ 1);
+            issue(g + gridDim.x, buf ^ 1);
             __builtin_amdgcn_s_waitcnt((kGatherLoads & 15) | (7 << 4) | (15 << 8) | ((kGatherLoads >> 4) << 14));
         } else {
             __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
@@ -179,8 +199,22 @@ __global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const uint1
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();            // this run has landed for every wave
         asm volatile("" ::: "memory");
-        const int64_t p0 = ch * pix_per_chunk;
-        const int np = (int)min((int64_t)pix_per_chunk, pixels - p0);
+        const int ji = job_of(g);
+        const GatherJob& J = jobs.j[ji];
+        if (ji != cur) {                         // uniform: a new tensor, new thread roles and channel indices
+            cur = ji;
+            const int nvec = (J.Cp + 7) >> 3;
+            ppb = kGatherThreads / nvec;         // pixels gathered per pass (nvec <= 256)
+            pp = tid / nvec;
+            v = tid - pp * nvec;
+            active = pp < ppb;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) id2[e] = (active && v * 8 + e < J.Cp) ? 2u * (uint32_t)J.idx[v * 8 + e] : 0u;
+            nlast = J.Cp - v * 8;                // valid channels of this thread's vector (>= 8: all)
+            row_bytes = J.x_cpitch * 2;
+        }
+        const int64_t p0 = (int64_t)(g - J.chunk0) * J.ppc;
+        const int np = (int)min((int64_t)J.ppc, J.pixels - p0);
         if (active) {
             for (int p = pp; p < np; p += ppb) {
                 const uint32_t r = lds_base + (uint32_t)(buf * kGatherChunk + p * row_bytes);
@@ -192,7 +226,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const uint1
                              : "+v"(e[0]), "+v"(e[1]), "+v"(e[2]), "+v"(e[3]), "+v"(e[4]), "+v"(e[5]), "+v"(e[6]), "+v"(e[7]));
                 const uint32_t o0 = e[0] | (e[1] << 16), o1 = e[2] | (e[3] << 16);
                 const uint32_t o2 = e[4] | (e[5] << 16), o3 = e[6] | (e[7] << 16);
-                uint16_t* dst = out + (p0 + p) * (int64_t)out_cpitch + v * 8;
+                uint16_t* dst = J.out + (p0 + p) * (int64_t)J.out_cpitch + v * 8;
                 if (nlast >= 8) {
                     *reinterpret_cast<uint4*>(dst) = make_uint4(o0, o1, o2, o3);
                 } else {
@@ -427,35 +461,54 @@ extern "C" int32_t pt_compact_vector(const void* v, int32_t elem_bytes, const in
     return launch_status();
 }
 
-extern "C" int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const int32_t* idx,
-                                   int32_t Cp, uint16_t* out, int32_t out_cpitch, void* stream) {
+// Host side of the activation gathers: tensors that qualify for the streaming kernel are collected into job
+// tables (one launch per kMaxGatherJobs tensors); the others take the element-wise kernel one by one.
+static int32_t check_gather(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const int32_t* idx, int32_t Cp,
+                            uint16_t* out, int32_t out_cpitch) {
     if (pixels < 0 || C <= 0 || Cp <= 0 || Cp > C || x_cpitch < C || out_cpitch < Cp) return PT_ERR_SHAPE;
-    if (pixels == 0) return PT_OK;
-    if (!x || !idx || !out) return PT_ERR_NULL;
-    hipStream_t st = (hipStream_t)stream;
-    const bool rows_aligned = (x_cpitch % 8 == 0) && (out_cpitch % 8 == 0) && (((uintptr_t)x & 15) == 0) &&
-                              (((uintptr_t)out & 15) == 0);
-    if (rows_aligned && (Cp + 7) / 8 <= kGatherThreads && (size_t)x_cpitch * 2 <= (size_t)kGatherChunk) {
-        // whole pixel rows per LDS buffer, a multiple of the pixels gathered per pass
-        const int nvec = (Cp + 7) / 8, ppb = kGatherThreads / nvec;
-        int ppc = (int)(kGatherChunk / ((size_t)x_cpitch * 2));
-        if (ppc > ppb) ppc = ppc / ppb * ppb;
-        const int64_t nchunks = ceil_div(pixels, ppc);
-        const unsigned grid = (unsigned)(nchunks < 512 ? nchunks : 512);  // two resident workgroups per CU
-        static bool attr_set = false;  // one-time opt-in to 64 KiB of dynamic LDS
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_compact_nhwc_lds),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kGatherChunk);
-            if (e != hipSuccess) {
-                set_hip_error(e);
-                return PT_ERR_LAUNCH;
-            }
-            attr_set = true;
+    if (pixels > 0 && (!x || !idx || !out)) return PT_ERR_NULL;
+    return PT_OK;
+}
+static bool gather_streams(const uint16_t* x, int32_t x_cpitch, int32_t Cp, const uint16_t* out, int32_t out_cpitch) {
+    return (x_cpitch % 8 == 0) && (out_cpitch % 8 == 0) && (((uintptr_t)x & 15) == 0) && (((uintptr_t)out & 15) == 0) &&
+           (Cp + 7) / 8 <= kGatherThreads && (size_t)x_cpitch * 2 <= (size_t)kGatherChunk;
+}
+static int32_t launch_gather_jobs(GatherJobs& t, hipStream_t st) {
+    if (t.n == 0) return PT_OK;
+    static bool attr_set = false;  // one-time opt-in to 64 KiB of dynamic LDS
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_compact_nhwc_lds),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kGatherChunk);
+        if (e != hipSuccess) {
+            set_hip_error(e);
+            return PT_ERR_LAUNCH;
         }
-        hipLaunchKernelGGL(k_compact_nhwc_lds, dim3(grid), dim3(kGatherThreads), 2 * kGatherChunk, st, x, pixels, x_cpitch,
-                           idx, Cp, out, out_cpitch, ppc);
-        return launch_status();
+        attr_set = true;
     }
+    const unsigned grid = (unsigned)(t.total_chunks < 512 ? t.total_chunks : 512);  // two resident workgroups per CU
+    hipLaunchKernelGGL(k_compact_nhwc_lds, dim3(grid), dim3(kGatherThreads), 2 * kGatherChunk, st, t);
+    t.n = 0;
+    t.total_chunks = 0;
+    return launch_status();
+}
+static int32_t add_gather_job(GatherJobs& t, const uint16_t* x, int64_t pixels, int32_t x_cpitch, const int32_t* idx,
+                              int32_t Cp, uint16_t* out, int32_t out_cpitch, hipStream_t st) {
+    // whole pixel rows per LDS buffer, a multiple of the pixels gathered per pass
+    const int nvec = (Cp + 7) / 8, ppb = kGatherThreads / nvec;
+    int ppc = (int)(kGatherChunk / ((size_t)x_cpitch * 2));
+    if (ppc > ppb) ppc = ppc / ppb * ppb;
+    const int64_t nchunks = ceil_div(pixels, ppc);
+    if (nchunks > 0x3fffffff) return PT_ERR_UNSUPPORTED;
+    if (t.n == kMaxGatherJobs || (int64_t)t.total_chunks + nchunks > 0x3fffffff) {
+        const int32_t rc = launch_gather_jobs(t, st);
+        if (rc != PT_OK) return rc;
+    }
+    t.j[t.n++] = GatherJob{x, idx, out, pixels, x_cpitch, Cp, out_cpitch, ppc, t.total_chunks, 0};
+    t.total_chunks += (int)nchunks;
+    return PT_OK;
+}
+static int32_t gather_elementwise(const uint16_t* x, int64_t pixels, int32_t x_cpitch, const int32_t* idx, int32_t Cp,
+                                  uint16_t* out, int32_t out_cpitch, hipStream_t st) {
     const int64_t work = pixels * ((Cp + 7) / 8);
     const int64_t nblk = ceil_div(work, 256);
     if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
@@ -463,6 +516,47 @@ extern "C" int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C,
     hipLaunchKernelGGL(k_compact_nhwc, dim3((unsigned)nblk), dim3(256), 0, st, x, pixels, x_cpitch, idx, Cp, out,
                        out_cpitch, vec_ok);
     return launch_status();
+}
+
+extern "C" int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const int32_t* idx,
+                                   int32_t Cp, uint16_t* out, int32_t out_cpitch, void* stream) {
+    const int32_t rc = check_gather(x, pixels, C, x_cpitch, idx, Cp, out, out_cpitch);
+    if (rc != PT_OK) return rc;
+    if (pixels == 0) return PT_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (!gather_streams(x, x_cpitch, Cp, out, out_cpitch)) return gather_elementwise(x, pixels, x_cpitch, idx, Cp, out, out_cpitch, st);
+    GatherJobs t;
+    t.n = 0;
+    t.total_chunks = 0;
+    const int32_t r2 = add_gather_job(t, x, pixels, x_cpitch, idx, Cp, out, out_cpitch, st);
+    if (r2 != PT_OK) return r2;
+    return launch_gather_jobs(t, st);
+}
+
+extern "C" int32_t pt_compact_nhwc_batched(const pt_gather_nhwc* jobs, int32_t n_jobs, void* stream) {
+    if (n_jobs < 0) return PT_ERR_SHAPE;
+    if (n_jobs == 0) return PT_OK;
+    if (!jobs) return PT_ERR_NULL;
+    for (int i = 0; i < n_jobs; ++i) {
+        const pt_gather_nhwc& j = jobs[i];
+        const int32_t rc = check_gather(j.x, j.pixels, j.C, j.x_cpitch, j.idx, j.Cp, j.out, j.out_cpitch);
+        if (rc != PT_OK) return rc;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    GatherJobs t;
+    t.n = 0;
+    t.total_chunks = 0;
+    for (int i = 0; i < n_jobs; ++i) {
+        const pt_gather_nhwc& j = jobs[i];
+        if (j.pixels == 0) continue;
+        int32_t rc;
+        if (gather_streams(j.x, j.x_cpitch, j.Cp, j.out, j.out_cpitch))
+            rc = add_gather_job(t, j.x, j.pixels, j.x_cpitch, j.idx, j.Cp, j.out, j.out_cpitch, st);
+        else
+            rc = gather_elementwise(j.x, j.pixels, j.x_cpitch, j.idx, j.Cp, j.out, j.out_cpitch, st);
+        if (rc != PT_OK) return rc;
+    }
+    return launch_gather_jobs(t, st);
 }
 
 // ---- multi-job entry points ------------------------------------------------------------------------

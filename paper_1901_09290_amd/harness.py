@@ -279,12 +279,11 @@ class ReconfigModel:
     def compact(self, cnt: Optional[np.ndarray] = None, per_call: bool = False) -> None:
         """Gathers every tensor with the planned index lists.  The survivor counts size the outputs: they
         are read back here (one synchronising copy) unless the caller already holds them.  Weights, momentum
-        and the per-channel vectors of all layers go through the multi-job calls; each saved activation is
-        one launch of its own."""
+        the per-channel vectors and the saved activations of all layers go through the multi-job calls."""
         if cnt is None:
             cnt = self.counts.cpu().numpy()
         self.new_counts = cnt
-        wjobs, vjobs = [], []
+        wjobs, vjobs, ajobs = [], [], []
         for i, s in enumerate(self.specs):
             ik = self.idx[s.out_edge] if s.out_edge is not None else None
             ic = self.idx[s.in_edge] if s.in_edge is not None else None
@@ -304,10 +303,15 @@ class ReconfigModel:
                     else:
                         vjobs.append(B.gather_vector(v, 4, ik, Kp, o))
             if self.act and ic is not None:
-                B.compact_nhwc(self.act[i], s.N * s.H * s.W, s.C, wp, ic, Cp, self.act_out[i], op)
+                if per_call:
+                    B.compact_nhwc(self.act[i], s.N * s.H * s.W, s.C, wp, ic, Cp, self.act_out[i], op)
+                else:
+                    ajobs.append(B.gather_nhwc(self.act[i], s.N * s.H * s.W, s.C, wp, ic, Cp, self.act_out[i], op))
         if not per_call:
             B.compact_weights_batched(wjobs)
             B.compact_vector_batched(vjobs)
+            if ajobs:
+                B.compact_nhwc_batched(ajobs)
 
     def sweep(self, thr: float) -> None:
         self.detect(thr)

@@ -138,3 +138,16 @@ def test_penalty_and_set_coeff_validate_on_the_host(lib):
             B.lasso_set_coeff(*bad)
         assert e.value.status == -2
     assert lib.pt_lasso_set_coeff(1.0, 1.0, 0.5, None) == -1
+
+
+def test_activation_gather_batched_validates_on_the_host(lib):
+    fake = 256
+    assert lib.pt_compact_nhwc_batched(None, 0, None) == 0
+    assert lib.pt_compact_nhwc_batched(None, 2, None) == -1
+    assert lib.pt_compact_nhwc_batched(None, -1, None) == -2
+    j = (B.GatherNhwc * 2)(B.GatherNhwc(fake, fake, fake, 0, 8, 8, 4, 4), B.GatherNhwc(fake, fake, fake, 10, 8, 8, 9, 16))
+    assert lib.pt_compact_nhwc_batched(j, 2, None) == -2             # Cp > C in the second job: nothing is launched
+    j = (B.GatherNhwc * 1)(B.GatherNhwc(None, fake, fake, 10, 8, 8, 4, 4))
+    assert lib.pt_compact_nhwc_batched(j, 1, None) == -1
+    j = (B.GatherNhwc * 1)(B.GatherNhwc(None, None, None, 0, 8, 8, 4, 4))
+    assert lib.pt_compact_nhwc_batched(j, 1, None) == 0              # an empty tensor needs no pointers
