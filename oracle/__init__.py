@@ -231,3 +231,40 @@ def compact_nhwc(x, idx) -> np.ndarray:
     _check(_load().oracle_compact_nhwc(_p(x), C.c_int64(pixels), Cc, x.dtype.itemsize, _p(idx), idx.size, _p(out)),
            "compact_nhwc")
     return out
+
+
+def scatter_nhwc(x, idx, Cc: int) -> np.ndarray:
+    """x [..., Cp] -> out [..., Cc] with out[..., idx] = x and zeros elsewhere (byte-exact copy)."""
+    x = np.ascontiguousarray(x)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    Cp = x.shape[-1]
+    assert idx.size == Cp
+    pixels = x.size // Cp
+    out = np.empty(x.shape[:-1] + (Cc,), dtype=x.dtype)
+    _check(_load().oracle_scatter_nhwc(_p(x), C.c_int64(pixels), Cp, x.dtype.itemsize, _p(idx), Cc, _p(out)),
+           "scatter_nhwc")
+    return out
+
+
+def group_maxabs(w):
+    """w [K,R,S,C] -> (out_max[K], in_max[C])."""
+    w = _d(w)
+    K, Cc = w.shape[0], w.shape[-1]
+    RS = w.size // (K * Cc)
+    om = np.empty(K, dtype=np.float64)
+    im = np.empty(Cc, dtype=np.float64)
+    _check(_load().oracle_group_maxabs(_p(w), K, RS, Cc, _p(om), _p(im)), "group_maxabs")
+    return om, im
+
+
+def apply_zero(w, zero_out=None, zero_in=None) -> np.ndarray:
+    """Returns a copy of w with the flagged groups written to exact zero."""
+    out = _d(w).copy()
+    K, Cc = out.shape[0], out.shape[-1]
+    RS = out.size // (K * Cc)
+    zo = None if zero_out is None else np.ascontiguousarray(zero_out, dtype=np.uint8)
+    zi = None if zero_in is None else np.ascontiguousarray(zero_in, dtype=np.uint8)
+    assert (zo is None or zo.size == K) and (zi is None or zi.size == Cc)
+    _check(_load().oracle_apply_zero(_p(out), K, RS, Cc, None if zo is None else _p(zo), None if zi is None else _p(zi)),
+           "apply_zero")
+    return out

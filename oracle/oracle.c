@@ -329,3 +329,53 @@ int oracle_compact_nhwc(const void* x, int64_t pixels, int32_t C, int32_t elem_b
                    (const char*)x + ((size_t)p * C + idx[b]) * elem_bytes, (size_t)elem_bytes);
     return 0;
 }
+
+int oracle_scatter_nhwc(const void* x, int64_t pixels, int32_t Cp, int32_t elem_bytes, const int32_t* idx, int32_t C,
+                        void* out) {
+    if (!x || !idx || !out) return -1;
+    if (pixels < 0 || C <= 0 || Cp <= 0 || Cp > C || elem_bytes <= 0) return -2;
+    for (int b = 0; b < Cp; ++b) {
+        if (idx[b] < 0 || idx[b] >= C) return -2;
+        if (b > 0 && idx[b] <= idx[b - 1]) return -2; /* survivor lists are strictly ascending */
+    }
+    memset(out, 0, (size_t)pixels * C * elem_bytes);
+    for (int64_t p = 0; p < pixels; ++p)
+        for (int b = 0; b < Cp; ++b)
+            memcpy((char*)out + ((size_t)p * C + idx[b]) * elem_bytes,
+                   (const char*)x + ((size_t)p * Cp + b) * elem_bytes, (size_t)elem_bytes);
+    return 0;
+}
+
+int oracle_group_maxabs(const double* w, int32_t K, int32_t RS, int32_t C, double* out_max, double* in_max) {
+    if (!w || !out_max || !in_max) return -1;
+    if (K <= 0 || RS <= 0 || C <= 0) return -2;
+    for (int k = 0; k < K; ++k) {
+        double m = 0.0;
+        for (int j = 0; j < RS; ++j)
+            for (int c = 0; c < C; ++c) {
+                double v = fabs(w[((size_t)k * RS + j) * C + c]);
+                if (v > m) m = v;
+            }
+        out_max[k] = m;
+    }
+    for (int c = 0; c < C; ++c) {
+        double m = 0.0;
+        for (int k = 0; k < K; ++k)
+            for (int j = 0; j < RS; ++j) {
+                double v = fabs(w[((size_t)k * RS + j) * C + c]);
+                if (v > m) m = v;
+            }
+        in_max[c] = m;
+    }
+    return 0;
+}
+
+int oracle_apply_zero(double* w, int32_t K, int32_t RS, int32_t C, const uint8_t* zero_out, const uint8_t* zero_in) {
+    if (!w) return -1;
+    if (K <= 0 || RS <= 0 || C <= 0) return -2;
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < RS; ++j)
+            for (int c = 0; c < C; ++c)
+                if ((zero_out && zero_out[k]) || (zero_in && zero_in[c])) w[((size_t)k * RS + j) * C + c] = 0.0;
+    return 0;
+}

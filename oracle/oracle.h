@@ -101,6 +101,19 @@ int oracle_compact_nhwc(const void* x, int64_t pixels, int32_t C, int32_t elem_b
 int oracle_num_threads(void);
 void oracle_set_num_threads(int n);
 
+/* Channel scatter (the inverse of the activation gather; the scatter layer of channel gating, Sec. 4.2):
+ * out[pix, idx[c']] = x[pix, c'] for c' < Cp, every other channel of out is zero.  idx strictly ascending. */
+int oracle_scatter_nhwc(const void* x, int64_t pixels, int32_t Cp, int32_t elem_bytes, const int32_t* idx, int32_t C,
+                        void* out);
+
+/* Largest absolute weight of every channel group (the criterion Sec. 4.1 describes next to the L2 one):
+ * out_max[k] = max |w[k,:,:,:]|, in_max[c] = max |w[:,:,:,c]|. */
+int oracle_group_maxabs(const double* w, int32_t K, int32_t RS, int32_t C, double* out_max, double* in_max);
+
+/* Writes exact zeros into every weight of the flagged groups (Sec. 4.1: weights of a channel below the threshold
+ * are zeroed out): w[k,:,:,c] = 0 where zero_out[k] or zero_in[c]; either mask may be NULL. */
+int oracle_apply_zero(double* w, int32_t K, int32_t RS, int32_t C, const uint8_t* zero_out, const uint8_t* zero_in);
+
 #ifdef __cplusplus
 }
 #endif

@@ -180,3 +180,60 @@ def test_workload_tables():
     assert all(k.size % 16 != 0 and 1 <= k.size <= e.n for k, e in zip(keep, e50))
     lp, ep = wl.with_widths(l50, e50, [k.size for k in keep])
     assert lp[0].C == 3 and all(l.C == ep[l.in_edge].n for l in lp if l.in_edge is not None)
+
+
+# ---- channel scatter, max-abs criterion, writing flagged groups to zero --------------------------------- #
+def test_scatter_is_the_inverse_of_gather_on_kept_channels():
+    rng = np.random.Generator(np.random.PCG64(301))
+    for C, pixels in ((5, 7), (16, 33), (37, 10)):
+        x = rng.integers(1, 60000, size=(pixels, C)).astype(np.uint16)        # no zeros in the data
+        idx = np.sort(rng.choice(C, max(1, C * 2 // 3), replace=False)).astype(np.int32)
+        g = oracle.compact_nhwc(x, idx)
+        s = oracle.scatter_nhwc(g, idx, C)
+        want = np.zeros_like(x)
+        want[:, idx] = x[:, idx]                                             # numpy fancy indexing as the second evaluator
+        assert np.array_equal(s, want)
+        assert np.array_equal(oracle.compact_nhwc(s, idx), g)                # gather is a left inverse of scatter
+        dropped = np.setdiff1d(np.arange(C), idx)
+        assert not s[:, dropped].any()
+    # hand-worked: 1 pixel, Cp = 2 survivors at positions 1 and 3 of C = 4
+    assert oracle.scatter_nhwc(np.array([[7, 9]], dtype=np.uint16), [1, 3], 4).tolist() == [[0, 7, 0, 9]]
+    with pytest.raises(Exception):
+        oracle.scatter_nhwc(np.array([[7, 9]], dtype=np.uint16), [3, 1], 4)   # not ascending
+
+
+def test_group_maxabs_matches_numpy_and_bounds_the_l2_norm():
+    rng = np.random.Generator(np.random.PCG64(302))
+    w = rng.standard_normal((6, 3, 3, 5))
+    w[2] = 0.0
+    w[..., 4] = 0.0
+    om, im = oracle.group_maxabs(w)
+    assert np.array_equal(om, np.abs(w).max(axis=(1, 2, 3))) and np.array_equal(im, np.abs(w).max(axis=(0, 1, 2)))
+    on, inn = oracle.group_norms(w)
+    # max|g| <= ||g||_2 <= sqrt(size) * max|g|: the L2 criterion never flags a group the max-abs one would keep
+    assert np.all(om <= on + 1e-15) and np.all(on <= np.sqrt(45) * om + 1e-12)
+    assert np.all(im <= inn + 1e-15) and np.all(inn <= np.sqrt(54) * im + 1e-12)
+    assert om[2] == 0.0 and im[4] == 0.0
+    # both criteria agree on exactly-zero groups, whatever the threshold
+    for thr in (1e-6, 1e-4):
+        assert np.array_equal(oracle.zero_groups(om, thr) & (on == 0), oracle.zero_groups(on, thr) & (on == 0))
+    # hand-worked 2x1x1x2 example of the golden file: w = [[3, 0], [4, 0]]
+    om, im = oracle.group_maxabs(np.array([[3.0, 0.0], [-4.0, 0.0]]).reshape(2, 1, 1, 2))
+    assert om.tolist() == [3.0, 4.0] and im.tolist() == [4.0, 0.0]
+
+
+def test_apply_zero_writes_exact_zeros_and_makes_the_groups_detectable():
+    rng = np.random.Generator(np.random.PCG64(303))
+    w = rng.standard_normal((5, 2, 2, 4)) * 1e-5 + 1.0
+    zo = np.array([0, 1, 0, 0, 1], dtype=np.uint8)
+    zi = np.array([1, 0, 0, 0], dtype=np.uint8)
+    z = oracle.apply_zero(w, zo, zi)
+    want = w.copy()
+    want[zo.astype(bool)] = 0.0
+    want[..., zi.astype(bool)] = 0.0
+    assert np.array_equal(z, want)
+    assert np.array_equal(oracle.apply_zero(w, None, zi), np.where(zi.astype(bool), 0.0, w))
+    assert np.array_equal(oracle.apply_zero(w, None, None), w)
+    on, inn = oracle.group_norms(z)
+    assert np.array_equal(oracle.zero_groups(on, 1e-6), zo) and np.array_equal(oracle.zero_groups(inn, 1e-6), zi)
+    assert np.array_equal(oracle.apply_zero(z, zo, zi), z)                      # idempotent
