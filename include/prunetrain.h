@@ -261,6 +261,26 @@ typedef struct pt_gather_nhwc {
 } pt_gather_nhwc;
 int32_t pt_compact_nhwc_batched(const pt_gather_nhwc* jobs, int32_t n_jobs, void* stream);
 
+/* ---- channel gating pieces and the paper's other zeroing rule: Sec. 4.1, 4.2 ----------------------------- */
+
+/* Channel scatter, the inverse of pt_compact_nhwc (the scatter layer of channel gating, Sec. 4.2):
+ *   out[pix][idx[c']] = x[pix][c'] for c' < Cp; every other logical channel of out is written as zero.
+ * x has Cp channels at pitch x_cpitch, out has C channels at pitch out_cpitch; idx as written by pt_compact_plan
+ * (strictly ascending, values < C).  Limit: C <= 8192. */
+int32_t pt_scatter_nhwc(const uint16_t* x, int64_t pixels, int32_t Cp, int32_t x_cpitch, const int32_t* idx, int32_t C,
+                        uint16_t* out, int32_t out_cpitch, void* stream);
+
+/* Largest absolute weight per channel group (Sec. 4.1 also states the zeroing rule this way):
+ *   out_max[k] = max |w[k,:,:]|,  in_max[c] = max |w[:,:,c]|.   Exact (a maximum has no rounding); feed the
+ * results to pt_zero_groups like norms.  Limit: C <= 2048.  Three small launches. */
+int32_t pt_group_maxabs(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, float* out_max,
+                        float* in_max, void* stream);
+
+/* Writes exact zeros into the flagged groups of an fp32 [K][RS][w_cpitch] tensor (weights, momentum):
+ *   w[k][rs][c] = 0 where zero_out[k] != 0 or zero_in[c] != 0.   Either mask may be NULL (none of that kind). */
+int32_t pt_apply_zero(float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, const uint8_t* zero_out,
+                      const uint8_t* zero_in, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,6 +29,7 @@ EXPORTS = [
     "pt_compact_weights", "pt_compact_vector", "pt_compact_nhwc",
     "pt_weights_to_crsk_batched", "pt_conv_bwd_data_crsk",
     "pt_group_lasso_penalty_batched", "pt_lasso_set_coeff", "pt_compact_nhwc_batched",
+    "pt_scatter_nhwc", "pt_group_maxabs", "pt_apply_zero",
     "pt_zero_groups_batched", "pt_reconcile_plan_batched", "pt_compact_vector_batched", "pt_compact_weights_batched",
 ]
 
@@ -127,6 +128,9 @@ def lib() -> C.CDLL:
             "pt_group_lasso_penalty_batched": [C.POINTER(LayerPenalty), i32, vp, vp],
             "pt_lasso_set_coeff": [C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)],
             "pt_compact_nhwc_batched": [C.POINTER(GatherNhwc), i32, vp],
+            "pt_scatter_nhwc": [vp, i64, i32, i32, vp, i32, vp, i32, vp],
+            "pt_group_maxabs": [vp, i32, i32, i32, i32, vp, vp, vp],
+            "pt_apply_zero": [vp, i32, i32, i32, i32, vp, vp, vp],
             "pt_zero_groups_batched": [C.POINTER(NormMask), i32, f32, vp],
             "pt_reconcile_plan_batched": [C.POINTER(EdgePlan), i32, vp],
             "pt_compact_vector_batched": [C.POINTER(GatherVector), i32, vp],
@@ -369,3 +373,18 @@ def gather_nhwc(x, pixels: int, Cc: int, x_cpitch: int, idx, Cp: int, out, out_c
 def compact_nhwc_batched(jobs, stream=None) -> None:
     arr = _array(jobs, GatherNhwc)
     _ck("pt_compact_nhwc_batched", lib().pt_compact_nhwc_batched(arr, len(jobs), _stream(stream)))
+
+
+def scatter_nhwc(x, pixels: int, Cp: int, x_cpitch: int, idx, Cc: int, out, out_cpitch: int, stream=None) -> None:
+    _ck("pt_scatter_nhwc", lib().pt_scatter_nhwc(_ptr(x), pixels, Cp, x_cpitch, _ptr(idx), Cc, _ptr(out), out_cpitch,
+                                                 _stream(stream)))
+
+
+def group_maxabs(w, K, RS, Cc, w_cpitch, out_max, in_max, stream=None) -> None:
+    _ck("pt_group_maxabs", lib().pt_group_maxabs(_ptr(w), K, RS, Cc, w_cpitch, _ptr(out_max), _ptr(in_max),
+                                                 _stream(stream)))
+
+
+def apply_zero(w, K, RS, Cc, w_cpitch, zero_out=None, zero_in=None, stream=None) -> None:
+    _ck("pt_apply_zero", lib().pt_apply_zero(_ptr(w), K, RS, Cc, w_cpitch, _ptr(zero_out), _ptr(zero_in),
+                                             _stream(stream)))

@@ -387,6 +387,98 @@ __global__ __launch_bounds__(256) void k_compact_weights_multi(const WJobs jobs)
     }
 }
 
+// ---- channel scatter (inverse of the activation gather), max-abs criterion, zeroing of flagged groups -----
+
+// out[pix][idx[c']] = x[pix][c'], all other channels of out zero.  A workgroup first builds the inverse map
+// (source channel or -1 for every output channel) in LDS; a thread then produces 8 consecutive output
+// channels of one pixel from up to eight 2-byte reads of that pixel's (contiguous, cached) source row.
+constexpr int kScatterMaxC = 8192;
+__global__ __launch_bounds__(256) void k_scatter_nhwc(const uint16_t* __restrict__ x, int64_t pixels, int Cp, int x_cpitch,
+                                                      const int* __restrict__ idx, int C, uint16_t* __restrict__ out,
+                                                      int out_cpitch, int vec_ok) {
+    __shared__ short inv[kScatterMaxC];
+    for (int c = threadIdx.x; c < C; c += 256) inv[c] = -1;
+    __syncthreads();
+    for (int b = threadIdx.x; b < Cp; b += 256) inv[idx[b]] = (short)b;
+    __syncthreads();
+    const int cv = (C + 7) >> 3;
+    const int64_t work = pixels * cv;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < work; t += (int64_t)gridDim.x * 256) {
+        const int64_t pix = t / cv;
+        const int c0 = (int)(t - pix * cv) * 8;
+        const uint16_t* src = x + pix * (int64_t)x_cpitch;
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int c = c0 + e;
+            const int b = c < C ? inv[c] : -1;
+            v[e] = b >= 0 ? src[b] : (uint16_t)0;
+        }
+        uint16_t* dst = out + pix * (int64_t)out_cpitch + c0;
+        if (vec_ok && c0 + 7 < C) {
+            uint4 o;
+            o.x = v[0] | ((uint32_t)v[1] << 16);
+            o.y = v[2] | ((uint32_t)v[3] << 16);
+            o.z = v[4] | ((uint32_t)v[5] << 16);
+            o.w = v[6] | ((uint32_t)v[7] << 16);
+            *reinterpret_cast<uint4*>(dst) = o;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (c0 + e < C) dst[e] = v[e];
+        }
+    }
+}
+
+// Largest |w| per filter and per input channel.  |w| >= 0, so the bit patterns order like the values and the
+// maxima can be combined with integer atomic max: exact and independent of the order of arrival.
+__global__ void k_fill_u32(uint32_t* __restrict__ p, int n, uint32_t v) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+constexpr int kMaxAbsMaxC = 2048;  // 256 threads x 8 columns each
+__global__ __launch_bounds__(256) void k_group_maxabs(const float* __restrict__ w, int K, int RS, int C, int cpitch,
+                                                      uint32_t* __restrict__ out_max, uint32_t* __restrict__ in_max,
+                                                      int rows_per_block) {
+    // a workgroup owns rows_per_block consecutive (k, rs) rows; thread t keeps columns t, t+256, ... in registers
+    const int64_t rows = (int64_t)K * RS;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r1 = min(rows, r0 + rows_per_block);
+    uint32_t cm[kMaxAbsMaxC / 256];
+#pragma unroll
+    for (int j = 0; j < kMaxAbsMaxC / 256; ++j) cm[j] = 0u;
+    for (int64_t r = r0; r < r1; ++r) {
+        uint32_t rm = 0u;
+#pragma unroll
+        for (int j = 0; j < kMaxAbsMaxC / 256; ++j) {
+            const int c = threadIdx.x + j * 256;
+            if (c < C) {
+                const uint32_t a = __float_as_uint(fabsf(w[r * cpitch + c]));
+                cm[j] = max(cm[j], a);
+                rm = max(rm, a);
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1) rm = max(rm, (uint32_t)__shfl_xor((int)rm, off));
+        if ((threadIdx.x & 63) == 0) atomicMax(&out_max[r / RS], rm);
+    }
+#pragma unroll
+    for (int j = 0; j < kMaxAbsMaxC / 256; ++j) {
+        const int c = threadIdx.x + j * 256;
+        if (c < C) atomicMax(&in_max[c], cm[j]);
+    }
+}
+
+// w[k][rs][c] = 0 where zero_out[k] or zero_in[c] (either mask may be null).
+__global__ void k_apply_zero(float* __restrict__ w, int64_t rows, int RS, int C, int cpitch,
+                             const uint8_t* __restrict__ zero_out, const uint8_t* __restrict__ zero_in) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= rows * C) return;
+    const int64_t r = t / C;
+    const int c = (int)(t - r * C);
+    const bool z = (zero_out && zero_out[r / RS]) || (zero_in && zero_in[c]);
+    if (z) w[r * cpitch + c] = 0.f;
+}
+
 }  // namespace pt
 
 using namespace pt;
@@ -702,4 +794,56 @@ extern "C" int32_t pt_compact_weights_batched(const pt_gather_weights* jobs, int
         }
     }
     return flush();
+}
+
+// ---- channel scatter, max-abs criterion, zeroing of flagged groups -------------------------------------
+extern "C" int32_t pt_scatter_nhwc(const uint16_t* x, int64_t pixels, int32_t Cp, int32_t x_cpitch, const int32_t* idx,
+                                   int32_t C, uint16_t* out, int32_t out_cpitch, void* stream) {
+    if (pixels < 0 || C <= 0 || Cp <= 0 || Cp > C || x_cpitch < Cp || out_cpitch < C) return PT_ERR_SHAPE;
+    if (C > kScatterMaxC) return PT_ERR_UNSUPPORTED;
+    if (pixels == 0) return PT_OK;
+    if (!x || !idx || !out) return PT_ERR_NULL;
+    const int64_t work = pixels * ((C + 7) / 8);
+    int64_t nblk = ceil_div(work, 256);
+    if (nblk > 256 * 16) nblk = 256 * 16;  // grid-stride: the inverse map is built once per workgroup
+    const int vec_ok = (out_cpitch % 8 == 0) && (((uintptr_t)out & 15) == 0);
+    hipLaunchKernelGGL(k_scatter_nhwc, dim3((unsigned)nblk), dim3(256), 0, (hipStream_t)stream, x, pixels, Cp, x_cpitch, idx,
+                       C, out, out_cpitch, vec_ok);
+    return launch_status();
+}
+
+extern "C" int32_t pt_group_maxabs(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, float* out_max,
+                                   float* in_max, void* stream) {
+    if (K <= 0 || RS <= 0 || C <= 0 || w_cpitch < C) return PT_ERR_SHAPE;
+    if (C > kMaxAbsMaxC) return PT_ERR_UNSUPPORTED;
+    if (!w || !out_max || !in_max) return PT_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)ceil_div(K, 256)), dim3(256), 0, st, (uint32_t*)out_max, K, 0u);
+    int32_t rc = launch_status();
+    if (rc != PT_OK) return rc;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)ceil_div(C, 256)), dim3(256), 0, st, (uint32_t*)in_max, C, 0u);
+    rc = launch_status();
+    if (rc != PT_OK) return rc;
+    const int64_t rows = (int64_t)K * RS;
+    int rpb = (int)(16384 / C);  // about 16K elements per workgroup
+    if (rpb < 1) rpb = 1;
+    if (rpb > 256) rpb = 256;
+    const int64_t nblk = ceil_div(rows, rpb);
+    if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_group_maxabs, dim3((unsigned)nblk), dim3(256), 0, st, w, K, RS, C, w_cpitch, (uint32_t*)out_max,
+                       (uint32_t*)in_max, rpb);
+    return launch_status();
+}
+
+extern "C" int32_t pt_apply_zero(float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, const uint8_t* zero_out,
+                                 const uint8_t* zero_in, void* stream) {
+    if (K <= 0 || RS <= 0 || C <= 0 || w_cpitch < C) return PT_ERR_SHAPE;
+    if (!w) return PT_ERR_NULL;
+    if (!zero_out && !zero_in) return PT_OK;
+    const int64_t rows = (int64_t)K * RS;
+    const int64_t nblk = ceil_div(rows * C, 256);
+    if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_apply_zero, dim3((unsigned)nblk), dim3(256), 0, (hipStream_t)stream, w, rows, RS, C, w_cpitch,
+                       zero_out, zero_in);
+    return launch_status();
 }

@@ -151,3 +151,17 @@ def test_activation_gather_batched_validates_on_the_host(lib):
     assert lib.pt_compact_nhwc_batched(j, 1, None) == -1
     j = (B.GatherNhwc * 1)(B.GatherNhwc(None, None, None, 0, 8, 8, 4, 4))
     assert lib.pt_compact_nhwc_batched(j, 1, None) == 0              # an empty tensor needs no pointers
+
+
+def test_gating_pieces_validate_on_the_host(lib):
+    fake = 256
+    assert lib.pt_scatter_nhwc(fake, 10, 5, 8, fake, 4, fake, 8, None) == -2      # Cp > C
+    assert lib.pt_scatter_nhwc(fake, 10, 4, 8, fake, 9000, fake, 9000, None) == -4
+    assert lib.pt_scatter_nhwc(None, 10, 4, 8, fake, 8, fake, 8, None) == -1
+    assert lib.pt_scatter_nhwc(None, 0, 4, 8, None, 8, None, 8, None) == 0
+    assert lib.pt_group_maxabs(fake, 4, 1, 8, 4, fake, fake, None) == -2            # pitch < C
+    assert lib.pt_group_maxabs(fake, 4, 1, 4096, 4096, fake, fake, None) == -4
+    assert lib.pt_group_maxabs(None, 4, 1, 8, 8, fake, fake, None) == -1
+    assert lib.pt_apply_zero(None, 4, 1, 8, 8, fake, fake, None) == -1
+    assert lib.pt_apply_zero(fake, 4, 1, 8, 4, fake, fake, None) == -2
+    assert lib.pt_apply_zero(fake, 4, 1, 8, 8, None, None, None) == 0               # nothing flagged: nothing to do

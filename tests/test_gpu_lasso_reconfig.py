@@ -406,3 +406,76 @@ def test_regulariser_value_matches_oracle_and_is_deterministic():
     # the coefficient that makes the regulariser 25 % of the total loss at a classification loss of 6.9
     lam = B.lasso_set_coeff(6.9, got, 0.25)
     assert abs(lam * got / (6.9 + lam * got) - 0.25) < 1e-12
+
+
+@pytest.mark.parametrize("pixels,C,pad", [(4 * 16 * 16, 16, False), (3 * 7 * 7, 203, True), (1000, 64, True),
+                                          (129, 811, True), (50, 5, False), (1, 8, False), (70000, 72, True)])
+def test_scatter_nhwc_bit_exact_and_inverts_the_gather(pixels, C, pad):
+    from gpu_util import DEV, pitch8
+    rng = np.random.Generator(np.random.PCG64(5000 + pixels + C))
+    idx = np.sort(rng.choice(C, max(1, int(C * 0.6)), replace=False)).astype(np.int32)
+    Cp = idx.size
+    x = rng.integers(1, 65536, size=(pixels, Cp)).astype(np.uint16)
+    xp = pitch8(Cp) if pad else Cp
+    op = pitch8(C) if pad else C
+    xfull = np.full((pixels, xp), 0xDEAD, dtype=np.uint16)
+    xfull[:, :Cp] = x
+    xd = torch.from_numpy(xfull.view(np.int16)).to(DEV).view(torch.bfloat16)
+    idd = torch.from_numpy(idx).to(DEV)
+    out = torch.empty((pixels, op), dtype=torch.bfloat16, device=DEV)
+    out.view(torch.int16).fill_(0x1234)
+    B.scatter_nhwc(xd, pixels, Cp, xp, idd, C, out, op)
+    back = torch.empty((pixels, xp), dtype=torch.bfloat16, device=DEV)
+    back.view(torch.int16).fill_(0x4321)
+    B.compact_nhwc(out, pixels, C, op, idd, Cp, back, xp)
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got[:, :C], oracle.scatter_nhwc(x, idx, C))
+    assert np.all(got[:, C:] == 0x1234)                                     # pitch padding untouched
+    assert np.array_equal(back.view(torch.int16).cpu().numpy().view(np.uint16)[:, :Cp], x)
+
+
+@pytest.mark.parametrize("shape,pad", [((16, 3, 3, 16), False), ((40, 1, 1, 203), True), ((7, 7, 7, 3), False),
+                                       ((300, 3, 3, 37), True), ((5, 1, 1, 2048), False)])
+def test_group_maxabs_is_exact(shape, pad):
+    from gpu_util import DEV, dev_f32, pitch8
+    rng = np.random.Generator(np.random.PCG64(6000 + sum(shape)))
+    w = rng.standard_normal(shape).astype(np.float32)
+    w[1] = 0.0
+    w[..., 0] = 0.0
+    K, C = shape[0], shape[-1]
+    RS = shape[1] * shape[2]
+    pitch = pitch8(C) if pad else C
+    wd = dev_f32(w, pitch)                      # padding is NaN: it must not enter the maxima
+    om = torch.full((K,), float("nan"), device=DEV)
+    im = torch.full((C,), float("nan"), device=DEV)
+    B.group_maxabs(wd, K, RS, C, pitch, om, im)
+    torch.cuda.synchronize()
+    rom, rim = oracle.group_maxabs(w)
+    assert np.array_equal(om.cpu().numpy(), rom.astype(np.float32))          # fp32 maxima of fp32 data: exact
+    assert np.array_equal(im.cpu().numpy(), rim.astype(np.float32))
+    z = torch.zeros(K, dtype=torch.uint8, device=DEV)
+    B.zero_groups(om, K, 1e-4, z)
+    torch.cuda.synchronize()
+    assert np.array_equal(z.cpu().numpy(), oracle.zero_groups(rom, 1e-4))
+
+
+def test_apply_zero_bit_exact():
+    from gpu_util import DEV, dev_f32, pitch8
+    rng = np.random.Generator(np.random.PCG64(7001))
+    for shape, pad in (((12, 3, 3, 10), True), ((5, 1, 1, 64), False), ((33, 2, 2, 7), False)):
+        w = rng.standard_normal(shape).astype(np.float32)
+        K, C = shape[0], shape[-1]
+        RS = shape[1] * shape[2]
+        zo = (rng.random(K) < 0.3).astype(np.uint8)
+        zi = (rng.random(C) < 0.3).astype(np.uint8)
+        pitch = pitch8(C) if pad else C
+        for mo, mi in ((zo, zi), (None, zi), (zo, None)):
+            wd = dev_f32(w, pitch)
+            B.apply_zero(wd, K, RS, C, pitch, None if mo is None else torch.from_numpy(mo).to(DEV),
+                         None if mi is None else torch.from_numpy(mi).to(DEV))
+            torch.cuda.synchronize()
+            got = wd.cpu().numpy()
+            assert np.array_equal(got[..., :C], oracle.apply_zero(w, mo, mi).astype(np.float32))
+            if pitch != C:
+                assert np.isnan(got[..., C:]).all()                            # padding untouched
