@@ -268,3 +268,16 @@ def apply_zero(w, zero_out=None, zero_in=None) -> np.ndarray:
     _check(_load().oracle_apply_zero(_p(out), K, RS, Cc, None if zo is None else _p(zo), None if zi is None else _p(zi)),
            "apply_zero")
     return out
+
+
+def sgd_momentum_lasso(w, dw, mom, out_norm, in_norm, lam, lr, mu, wd, flags):
+    """Returns (w_new, mom_new); inputs are not modified."""
+    w2, m2, g = _d(w).copy(), _d(mom).copy(), _d(dw)
+    K, Cc = w2.shape[0], w2.shape[-1]
+    RS = w2.size // (K * Cc)
+    on, inn = _d(out_norm), _d(in_norm)
+    assert g.size == w2.size and m2.size == w2.size and on.size == K and inn.size == Cc
+    _check(_load().oracle_sgd_momentum_lasso(_p(w2), _p(g), _p(m2), _p(on), _p(inn), C.c_double(lam), C.c_double(lr),
+                                             C.c_double(mu), C.c_double(wd), C.c_uint32(flags), K, RS, Cc),
+           "sgd_momentum_lasso")
+    return w2, m2

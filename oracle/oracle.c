@@ -379,3 +379,22 @@ int oracle_apply_zero(double* w, int32_t K, int32_t RS, int32_t C, const uint8_t
                 if ((zero_out && zero_out[k]) || (zero_in && zero_in[c])) w[((size_t)k * RS + j) * C + c] = 0.0;
     return 0;
 }
+
+int oracle_sgd_momentum_lasso(double* w, const double* dw, double* mom, const double* out_norm, const double* in_norm,
+                              double lambda, double lr, double mu, double wd, uint32_t flags, int32_t K, int32_t RS,
+                              int32_t C) {
+    if (!w || !dw || !mom || !out_norm || !in_norm) return -1;
+    if (K <= 0 || RS <= 0 || C <= 0) return -2;
+    const int reg_out = (flags & 1u) != 0, reg_in = (flags & 2u) != 0;
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < RS; ++j)
+            for (int c = 0; c < C; ++c) {
+                size_t i = ((size_t)k * RS + j) * C + c;
+                double g = dw[i] + wd * w[i];
+                if (reg_out && out_norm[k] > 0.0) g += lambda * w[i] / out_norm[k];
+                if (reg_in && in_norm[c] > 0.0) g += lambda * w[i] / in_norm[c];
+                mom[i] = mu * mom[i] + g;
+                w[i] -= lr * mom[i];
+            }
+    return 0;
+}

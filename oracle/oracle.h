@@ -114,6 +114,15 @@ int oracle_group_maxabs(const double* w, int32_t K, int32_t RS, int32_t C, doubl
  * are zeroed out): w[k,:,:,c] = 0 where zero_out[k] or zero_in[c]; either mask may be NULL. */
 int oracle_apply_zero(double* w, int32_t K, int32_t RS, int32_t C, const uint8_t* zero_out, const uint8_t* zero_in);
 
+/* Optimizer step of Alg. 1 with the regulariser's gradient folded in, in place.  The paper names the step
+ * (Optimizer(W, dW, LR)) and its ResNet baseline's hyper-parameters but not the rule; the reading used here
+ * is stochastic gradient descent with momentum in its common form:
+ *   g = dw + wd*w + lambda*w*(a/out_norm[k] + b/in_norm[c])   (a zero norm contributes 0)
+ *   mom = mu*mom + g ;  w = w - lr*mom. */
+int oracle_sgd_momentum_lasso(double* w, const double* dw, double* mom, const double* out_norm, const double* in_norm,
+                              double lambda, double lr, double mu, double wd, uint32_t flags, int32_t K, int32_t RS,
+                              int32_t C);
+
 #ifdef __cplusplus
 }
 #endif

@@ -185,3 +185,43 @@ def test_set_coeff_solves_the_penalty_ratio_equation():
     for bad in ((1.0, 10.0, 0.0), (1.0, 10.0, 1.0), (1.0, 0.0, 0.2), (-1.0, 10.0, 0.2)):
         with pytest.raises(Exception):
             oracle.set_coeff(*bad)
+
+
+def test_optimizer_step_reduces_to_known_rules():
+    """SGD-with-momentum step with the regulariser folded in: special cases with textbook closed forms."""
+    w, dw, m = _rand((4, 3, 3, 5), 70), _rand((4, 3, 3, 5), 71), _rand((4, 3, 3, 5), 72)
+    on, inn = oracle.group_norms(w)
+    # no momentum, no decay, no regulariser: plain gradient descent
+    w2, m2 = oracle.sgd_momentum_lasso(w, dw, m, on, inn, 0.0, 0.1, 0.0, 0.0, 3)
+    np.testing.assert_allclose(w2, w - 0.1 * dw, rtol=0, atol=1e-15)
+    np.testing.assert_array_equal(m2, dw)
+    # the regulariser's part equals the separately pinned lasso gradient; the rest is v = mu*v + g, w -= lr*v
+    lam, lr, mu, wd = 1e-2, 0.05, 0.9, 1e-4
+    g = oracle.group_lasso_grad(w, on, inn, lam, 3, dw) + wd * w
+    w2, m2 = oracle.sgd_momentum_lasso(w, dw, m, on, inn, lam, lr, mu, wd, 3)
+    np.testing.assert_allclose(m2, mu * m + g, rtol=1e-14)
+    np.testing.assert_allclose(w2, w - lr * (mu * m + g), rtol=1e-14, atol=1e-15)
+    # constant gradient, zero start: after n steps the velocity is g*(1 - mu^n)/(1 - mu) (geometric series)
+    wc, mc = np.zeros((2, 1, 1, 2)), np.zeros((2, 1, 1, 2))
+    gc = np.full((2, 1, 1, 2), 2.0)
+    ones = np.ones(2)
+    for n in range(1, 6):
+        wc, mc = oracle.sgd_momentum_lasso(wc, gc, mc, ones, ones, 0.0, 0.1, 0.5, 0.0, 0)
+        np.testing.assert_allclose(mc, 2.0 * (1 - 0.5 ** n) / 0.5, rtol=1e-14)
+
+
+def test_optimizer_step_keeps_zeroed_groups_zero_and_descends_the_regularised_loss():
+    w = _rand((6, 2, 2, 4), 73)
+    w[1] = 0.0
+    w[..., 2] = 0.0
+    on, inn = oracle.group_norms(w)
+    dw = _rand((6, 2, 2, 4), 74)
+    dw[1] = 0.0            # a zeroed filter receives no loss gradient through a zero weight path in these tests
+    dw[..., 2] = 0.0
+    m = np.zeros_like(w)
+    w2, m2 = oracle.sgd_momentum_lasso(w, dw, m, on, inn, 0.1, 0.1, 0.9, 1e-4, 3)
+    assert not w2[1].any() and not w2[..., 2].any() and not m2[1].any()        # zero sub-gradient at zero groups
+    # with dw = 0 a small step decreases the penalty (descent direction of lambda * sum of norms)
+    pen = lambda v: oracle.group_lasso_penalty([(*oracle.group_norms(v), 3)])
+    w3, _ = oracle.sgd_momentum_lasso(w, np.zeros_like(w), m, on, inn, 0.1, 1e-3, 0.0, 0.0, 3)
+    assert pen(w3) < pen(w)
