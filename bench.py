@@ -217,6 +217,8 @@ def main():
             "bwd_weight": timed(lambda: [l.bwd_weight(net.ws) for l in L], 3),
             "group_norms": timed(lambda: B.group_norms_batched(net.norm_jobs, net.ws_norms), 5),
             "group_lasso_grad": timed(lambda: B.group_lasso_grad_batched(net.lasso_jobs, LAMBDA), 5),
+            # not part of the timed step: the optimizer step with the regulariser folded in (lr = 0: weights unchanged)
+            "optimizer_step_fused": timed(lambda: net.optimizer_step(LAMBDA, 0.0, 0.9, 1e-4), 5),
         }
     fl = {tag: {"fwd": sum(l.spec.flops for l in net.layers),
                 "bwd_data": sum(l.spec.flops for l in net.layers if l.dx is not None),
@@ -275,6 +277,9 @@ def main():
                               "frac_hbm_peak": round(6 * params[tag] / (tn * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
         out["group_lasso_grad"] = {"ms": round(tl, 4), "GBps": round(12 * params[tag] / (tl * 1e-3) / 1e9, 1),
                                    "frac_hbm_peak": round(12 * params[tag] / (tl * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        to = fam[tag]["optimizer_step_fused"]
+        out["optimizer_step_fused(not in step)"] = {"ms": round(to, 4), "GBps": round(20 * params[tag] / (to * 1e-3) / 1e9, 1),
+                                                    "frac_hbm_peak": round(20 * params[tag] / (to * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
         return out
 
     out = {

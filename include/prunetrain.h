@@ -152,6 +152,26 @@ int32_t pt_group_norms_batched_workspace_bytes(const pt_layer_weights* layers, i
 int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_t n, void* ws, size_t ws_bytes, void* stream);
 int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int32_t n, float lambda, void* stream);
 
+/* Optimizer step of Alg. 1 with the regulariser's gradient folded in (one pass over w, dw, mom instead of a
+ * gradient pass plus an update pass).  The paper names the step but not the rule; this is stochastic gradient
+ * descent with momentum in its common form, per layer and in place:
+ *   g = dw + weight_decay*w + lambda*w*(a/out_norm[k] + b/in_norm[c])     (a zero norm contributes 0)
+ *   mom = momentum*mom + g ;   w = w - lr*mom.
+ * dw is the loss gradient WITHOUT the regulariser (what pt_conv_bwd_weight wrote) and is not modified; the norms
+ * are those of the weights before the step.  `layers`: HOST array, device pointers inside; 32 layers per launch. */
+typedef struct pt_layer_update {
+    float* w;              /* [K][RS][w_cpitch] */
+    const float* dw;       /* same shape */
+    float* mom;            /* same shape */
+    const float* out_norm; /* [K] */
+    const float* in_norm;  /* [C] */
+    int32_t K, RS, C, w_cpitch;
+    uint32_t flags;        /* PT_LASSO_OUT | PT_LASSO_IN */
+    uint32_t reserved;
+} pt_layer_update;
+int32_t pt_sgd_momentum_lasso_batched(const pt_layer_update* layers, int32_t n, float lambda, float lr, float momentum,
+                                      float weight_decay, void* stream);
+
 /* Value of the regulariser over a whole network (GroupLassoReg of Alg. 1, Eq. 1-2):
  *   *penalty_dev = sum over layers of ( a * sum_k out_norm[k] + b * sum_c in_norm[c] ),  a, b = flags bits.
  * No weighting by group size (one global coefficient, Sec. 3.1).  The norms are those pt_group_norms wrote;

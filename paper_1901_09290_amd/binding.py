@@ -29,7 +29,7 @@ EXPORTS = [
     "pt_compact_weights", "pt_compact_vector", "pt_compact_nhwc",
     "pt_weights_to_crsk_batched", "pt_conv_bwd_data_crsk",
     "pt_group_lasso_penalty_batched", "pt_lasso_set_coeff", "pt_compact_nhwc_batched",
-    "pt_scatter_nhwc", "pt_group_maxabs", "pt_apply_zero",
+    "pt_scatter_nhwc", "pt_group_maxabs", "pt_apply_zero", "pt_sgd_momentum_lasso_batched",
     "pt_zero_groups_batched", "pt_reconcile_plan_batched", "pt_compact_vector_batched", "pt_compact_weights_batched",
 ]
 
@@ -71,6 +71,12 @@ class LayerPenalty(C.Structure):
 class GatherNhwc(C.Structure):
     _fields_ = [("x", C.c_void_p), ("idx", C.c_void_p), ("out", C.c_void_p), ("pixels", C.c_int64),
                 ("C", C.c_int32), ("x_cpitch", C.c_int32), ("Cp", C.c_int32), ("out_cpitch", C.c_int32)]
+
+
+class LayerUpdate(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("dw", C.c_void_p), ("mom", C.c_void_p), ("out_norm", C.c_void_p),
+                ("in_norm", C.c_void_p), ("K", C.c_int32), ("RS", C.c_int32), ("C", C.c_int32), ("w_cpitch", C.c_int32),
+                ("flags", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class NormMask(C.Structure):
@@ -128,6 +134,7 @@ def lib() -> C.CDLL:
             "pt_group_lasso_penalty_batched": [C.POINTER(LayerPenalty), i32, vp, vp],
             "pt_lasso_set_coeff": [C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)],
             "pt_compact_nhwc_batched": [C.POINTER(GatherNhwc), i32, vp],
+            "pt_sgd_momentum_lasso_batched": [C.POINTER(LayerUpdate), i32, f32, f32, f32, f32, vp],
             "pt_scatter_nhwc": [vp, i64, i32, i32, vp, i32, vp, i32, vp],
             "pt_group_maxabs": [vp, i32, i32, i32, i32, vp, vp, vp],
             "pt_apply_zero": [vp, i32, i32, i32, i32, vp, vp, vp],
@@ -388,3 +395,13 @@ def group_maxabs(w, K, RS, Cc, w_cpitch, out_max, in_max, stream=None) -> None:
 def apply_zero(w, K, RS, Cc, w_cpitch, zero_out=None, zero_in=None, stream=None) -> None:
     _ck("pt_apply_zero", lib().pt_apply_zero(_ptr(w), K, RS, Cc, w_cpitch, _ptr(zero_out), _ptr(zero_in),
                                              _stream(stream)))
+
+
+def layer_update(w, dw, mom, out_norm, in_norm, K, RS, Cc, w_cpitch, flags) -> LayerUpdate:
+    return LayerUpdate(_ptr(w), _ptr(dw), _ptr(mom), _ptr(out_norm), _ptr(in_norm), K, RS, Cc, w_cpitch, flags, 0)
+
+
+def sgd_momentum_lasso_batched(layers, lam: float, lr: float, momentum: float, weight_decay: float, stream=None) -> None:
+    arr = _array(layers, LayerUpdate)
+    _ck("pt_sgd_momentum_lasso_batched",
+        lib().pt_sgd_momentum_lasso_batched(arr, len(layers), lam, lr, momentum, weight_decay, _stream(stream)))

@@ -13,6 +13,7 @@
 // Two levels, fixed order, no atomics: a workgroup owns whole rows of a chunk and writes one
 // sum-of-squares per row and one partial per column; the finish kernel adds the R*S row sums of each
 // filter and the per-chunk column partials in ascending order.
+#include <vector>
 #include "common.h"
 
 namespace pt {
@@ -42,6 +43,7 @@ struct LassoJob {
     const float* out_norm;
     const float* in_norm;
     float* dw;
+    float* mom;  // optimizer step only: momentum buffer; then w is updated in place and dw is read-only
     int K, RS, C, cpitch;
     int first_block, n_chunks, rows_per_chunk, txlog2;
     uint32_t flags;
@@ -177,8 +179,13 @@ __global__ __launch_bounds__(kThreads) void k_group_norms_finish(const NormJobs 
     }
 }
 
-template <int VEC>
-__global__ __launch_bounds__(kThreads) void k_group_lasso_grad(const LassoJobs jobs, float lambda) {
+// UPDATE = false: dw += lambda * d(penalty)/dw.   UPDATE = true: the optimizer step with the regulariser folded in,
+//   g = dw + wd*w + lambda*w*(a/out_norm + b/in_norm);  mom = mu*mom + g;  w -= lr*mom   (one pass over w, dw, mom).
+struct StepParams {
+    float lr, mu, wd;
+};
+template <int VEC, bool UPDATE>
+__global__ __launch_bounds__(kThreads) void k_group_lasso_grad(const LassoJobs jobs, float lambda, StepParams sp) {
     const int ji = find_job(jobs, blockIdx.x);
     const LassoJob& J = jobs.j[ji];
     const int chunk = blockIdx.x - J.first_block;
@@ -191,8 +198,9 @@ __global__ __launch_bounds__(kThreads) void k_group_lasso_grad(const LassoJobs j
     const int64_t r0 = (int64_t)chunk * J.rows_per_chunk;
     const int64_t r1 = min(rows, r0 + J.rows_per_chunk);
     const bool reg_out = J.flags & PT_LASSO_OUT, reg_in = J.flags & PT_LASSO_IN;
-    const float* __restrict__ w = J.w;
+    float* __restrict__ w = const_cast<float*>(J.w);
     float* __restrict__ dw = J.dw;
+    float* __restrict__ mom = J.mom;
 
     for (int cg = tx; cg < Lv; cg += TX) {
         float inv_in[VEC];
@@ -213,15 +221,36 @@ __global__ __launch_bounds__(kThreads) void k_group_lasso_grad(const LassoJobs j
             load_vec<VEC>(dw + off, g);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) g[e] += lambda * (v[e] * (inv_out + inv_in[e]));
+            float* dst = dw;
+            if constexpr (UPDATE) {
+                float m[VEC];
+                load_vec<VEC>(mom + off, m);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    m[e] = sp.mu * m[e] + (g[e] + sp.wd * v[e]);
+                    g[e] = v[e] - sp.lr * m[e];  // g now holds the new weight
+                }
+                if constexpr (VEC == 4) {
+                    if (cg * 4 + 3 < C) {
+                        *reinterpret_cast<float4*>(mom + off) = make_float4(m[0], m[1], m[2], m[3]);
+                    } else {
+                        for (int e = 0; e < 4; ++e)
+                            if (cg * 4 + e < C) mom[off + e] = m[e];
+                    }
+                } else {
+                    mom[off] = m[0];
+                }
+                dst = w;
+            }
             if constexpr (VEC == 4) {
                 if (cg * 4 + 3 < C) {
-                    *reinterpret_cast<float4*>(dw + off) = make_float4(g[0], g[1], g[2], g[3]);
+                    *reinterpret_cast<float4*>(dst + off) = make_float4(g[0], g[1], g[2], g[3]);
                 } else {
                     for (int e = 0; e < 4; ++e)
-                        if (cg * 4 + e < C) dw[off + e] = g[e];
+                        if (cg * 4 + e < C) dst[off + e] = g[e];
                 }
             } else {
-                dw[off] = g[0];
+                dst[off] = g[0];
             }
         }
     }
@@ -386,17 +415,17 @@ extern "C" int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_
     return PT_OK;
 }
 
-extern "C" int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int32_t n, float lambda, void* stream) {
-    if (n < 0) return PT_ERR_SHAPE;
-    if (n == 0) return PT_OK;
-    if (!layers) return PT_ERR_NULL;
-    for (int i = 0; i < n; ++i) {
-        const pt_layer_lasso& L = layers[i];
-        if (!L.w || !L.out_norm || !L.in_norm || !L.dw) return PT_ERR_NULL;
-        if (L.K <= 0 || L.RS <= 0 || L.C <= 0 || L.w_cpitch < L.C) return PT_ERR_SHAPE;
-        if (L.flags & ~3u) return PT_ERR_UNSUPPORTED;
-    }
-    hipStream_t st = (hipStream_t)stream;
+// Shared launcher of the gradient pass and of the optimizer step (mom == nullptr in every layer <=> gradient pass).
+struct LassoLayer {
+    const float* w;
+    const float* out_norm;
+    const float* in_norm;
+    float* dw;
+    float* mom;
+    int32_t K, RS, C, w_cpitch;
+    uint32_t flags;
+};
+static int32_t launch_lasso(const LassoLayer* layers, int n, bool update, float lambda, StepParams sp, hipStream_t st) {
     for (int pass = 0; pass < 2; ++pass) {
         const bool want_vec = pass == 0;
         LassoJobs jobs;
@@ -404,21 +433,26 @@ extern "C" int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int
         int blocks = 0;
         auto flush = [&]() -> int32_t {
             if (jobs.n == 0) return PT_OK;
-            if (want_vec)
-                hipLaunchKernelGGL(k_group_lasso_grad<4>, dim3(blocks), dim3(kThreads), 0, st, jobs, lambda);
+            if (want_vec && update)
+                hipLaunchKernelGGL((k_group_lasso_grad<4, true>), dim3(blocks), dim3(kThreads), 0, st, jobs, lambda, sp);
+            else if (want_vec)
+                hipLaunchKernelGGL((k_group_lasso_grad<4, false>), dim3(blocks), dim3(kThreads), 0, st, jobs, lambda, sp);
+            else if (update)
+                hipLaunchKernelGGL((k_group_lasso_grad<1, true>), dim3(blocks), dim3(kThreads), 0, st, jobs, lambda, sp);
             else
-                hipLaunchKernelGGL(k_group_lasso_grad<1>, dim3(blocks), dim3(kThreads), 0, st, jobs, lambda);
+                hipLaunchKernelGGL((k_group_lasso_grad<1, false>), dim3(blocks), dim3(kThreads), 0, st, jobs, lambda, sp);
             jobs.n = 0;
             blocks = 0;
             return launch_status();
         };
         for (int i = 0; i < n; ++i) {
-            const pt_layer_lasso& L = layers[i];
-            const bool vec = (L.w_cpitch % 4 == 0) && (((uintptr_t)L.w & 15) == 0) && (((uintptr_t)L.dw & 15) == 0);
+            const LassoLayer& L = layers[i];
+            const bool vec = (L.w_cpitch % 4 == 0) && (((uintptr_t)L.w & 15) == 0) && (((uintptr_t)L.dw & 15) == 0) &&
+                             (!update || ((uintptr_t)L.mom & 15) == 0);
             if (vec != want_vec) continue;
             const ChunkPlan cp = plan_chunks((int64_t)L.K * L.RS, L.C, vec);
             LassoJob& J = jobs.j[jobs.n++];
-            J.w = L.w; J.out_norm = L.out_norm; J.in_norm = L.in_norm; J.dw = L.dw;
+            J.w = L.w; J.out_norm = L.out_norm; J.in_norm = L.in_norm; J.dw = L.dw; J.mom = L.mom;
             J.K = L.K; J.RS = L.RS; J.C = L.C; J.cpitch = L.w_cpitch;
             J.first_block = blocks; J.n_chunks = cp.n_chunks; J.rows_per_chunk = cp.rows_per_chunk; J.txlog2 = cp.txlog2;
             J.flags = L.flags; J.pad = 0;
@@ -432,6 +466,43 @@ extern "C" int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int
         if (rc != PT_OK) return rc;
     }
     return PT_OK;
+}
+
+extern "C" int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int32_t n, float lambda, void* stream) {
+    if (n < 0) return PT_ERR_SHAPE;
+    if (n == 0) return PT_OK;
+    if (!layers) return PT_ERR_NULL;
+    for (int i = 0; i < n; ++i) {
+        const pt_layer_lasso& L = layers[i];
+        if (!L.w || !L.out_norm || !L.in_norm || !L.dw) return PT_ERR_NULL;
+        if (L.K <= 0 || L.RS <= 0 || L.C <= 0 || L.w_cpitch < L.C) return PT_ERR_SHAPE;
+        if (L.flags & ~3u) return PT_ERR_UNSUPPORTED;
+    }
+    std::vector<LassoLayer> v((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        const pt_layer_lasso& L = layers[i];
+        v[i] = LassoLayer{L.w, L.out_norm, L.in_norm, L.dw, nullptr, L.K, L.RS, L.C, L.w_cpitch, L.flags};
+    }
+    return launch_lasso(v.data(), n, false, lambda, StepParams{0.f, 0.f, 0.f}, (hipStream_t)stream);
+}
+
+extern "C" int32_t pt_sgd_momentum_lasso_batched(const pt_layer_update* layers, int32_t n, float lambda, float lr,
+                                                 float momentum, float weight_decay, void* stream) {
+    if (n < 0) return PT_ERR_SHAPE;
+    if (n == 0) return PT_OK;
+    if (!layers) return PT_ERR_NULL;
+    for (int i = 0; i < n; ++i) {
+        const pt_layer_update& L = layers[i];
+        if (!L.w || !L.dw || !L.mom || !L.out_norm || !L.in_norm) return PT_ERR_NULL;
+        if (L.K <= 0 || L.RS <= 0 || L.C <= 0 || L.w_cpitch < L.C) return PT_ERR_SHAPE;
+        if (L.flags & ~3u) return PT_ERR_UNSUPPORTED;
+    }
+    std::vector<LassoLayer> v((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        const pt_layer_update& L = layers[i];
+        v[i] = LassoLayer{L.w, L.out_norm, L.in_norm, const_cast<float*>(L.dw), L.mom, L.K, L.RS, L.C, L.w_cpitch, L.flags};
+    }
+    return launch_lasso(v.data(), n, true, lambda, StepParams{lr, momentum, weight_decay}, (hipStream_t)stream);
 }
 
 // ---- single-layer forms: the batched calls with one entry ------------------------------------- //

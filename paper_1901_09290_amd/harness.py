@@ -194,6 +194,16 @@ class Network:
         coefficient through binding.lasso_set_coeff (SetCoeff)."""
         B.group_lasso_penalty_batched(self.penalty_jobs, self.penalty)
 
+    def optimizer_step(self, lam: float, lr: float, momentum: float, weight_decay: float) -> None:
+        """Optimizer of Alg. 1 with the regulariser's gradient folded in: one pass over w, dw and the momentum
+        buffers of all layers (instead of group_lasso_grad_batched followed by an update pass)."""
+        if not hasattr(self, "update_jobs"):
+            self.mom = [torch.zeros_like(l.w_master) for l in self.layers]
+            jobs = [B.layer_update(l.w_master, l.dw, m, l.out_norm, l.in_norm, l.spec.K, l.RS, l.spec.C, l.wp,
+                                   l.lasso_flags) for l, m in zip(self.layers, self.mom)]
+            self.update_jobs = (B.LayerUpdate * len(jobs))(*jobs)
+        B.sgd_momentum_lasso_batched(self.update_jobs, lam, lr, momentum, weight_decay)
+
     @property
     def step_flops(self) -> int:
         return sum(l.step_flops for l in self.layers)

@@ -165,3 +165,15 @@ def test_gating_pieces_validate_on_the_host(lib):
     assert lib.pt_apply_zero(None, 4, 1, 8, 8, fake, fake, None) == -1
     assert lib.pt_apply_zero(fake, 4, 1, 8, 4, fake, fake, None) == -2
     assert lib.pt_apply_zero(fake, 4, 1, 8, 8, None, None, None) == 0               # nothing flagged: nothing to do
+
+
+def test_optimizer_step_validates_on_the_host(lib):
+    fake = 256
+    assert lib.pt_sgd_momentum_lasso_batched(None, 0, 0.1, 0.1, 0.9, 0.0, None) == 0
+    assert lib.pt_sgd_momentum_lasso_batched(None, 1, 0.1, 0.1, 0.9, 0.0, None) == -1
+    j = (B.LayerUpdate * 1)(B.LayerUpdate(fake, fake, None, fake, fake, 4, 1, 8, 8, 3, 0))
+    assert lib.pt_sgd_momentum_lasso_batched(j, 1, 0.1, 0.1, 0.9, 0.0, None) == -1      # no momentum buffer
+    j = (B.LayerUpdate * 1)(B.LayerUpdate(fake, fake, fake, fake, fake, 4, 1, 8, 4, 3, 0))
+    assert lib.pt_sgd_momentum_lasso_batched(j, 1, 0.1, 0.1, 0.9, 0.0, None) == -2      # pitch < C
+    j = (B.LayerUpdate * 1)(B.LayerUpdate(fake, fake, fake, fake, fake, 4, 1, 8, 8, 4, 0))
+    assert lib.pt_sgd_momentum_lasso_batched(j, 1, 0.1, 0.1, 0.9, 0.0, None) == -4      # unknown flag bit

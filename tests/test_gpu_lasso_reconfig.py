@@ -479,3 +479,53 @@ def test_apply_zero_bit_exact():
             assert np.array_equal(got[..., :C], oracle.apply_zero(w, mo, mi).astype(np.float32))
             if pitch != C:
                 assert np.isnan(got[..., C:]).all()                            # padding untouched
+
+
+def test_optimizer_step_matches_oracle():
+    """One launch updates several layers (vector and element-wise loaders, padded pitches, first-layer
+    exemption): weights and momentum against the fp64 oracle at 1e-5; dw and pitch padding untouched; a second
+    step from the device's own state also matches (momentum carries over)."""
+    from gpu_util import DEV, F32_TOL, dev_f32, pitch8, rel_err
+    rng = np.random.Generator(np.random.PCG64(8100))
+    shapes = [((16, 3, 3, 3), False, 1), ((40, 1, 1, 203), True, 3), ((64, 3, 3, 64), True, 3), ((7, 5, 5, 11), False, 3),
+              ((300, 1, 1, 37), True, 2)]
+    lam, lr, mu, wd = 1e-3, 0.1, 0.9, 1e-4
+    state = []
+    for shape, pad, flags in shapes:
+        K, C = shape[0], shape[-1]
+        RS = shape[1] * shape[2]
+        w = (rng.standard_normal(shape) * 0.1).astype(np.float32)
+        w[0] = 0.0                                   # an exactly zero filter
+        dw = (rng.standard_normal(shape) * 0.01).astype(np.float32)
+        dw[0] = 0.0
+        m = (rng.standard_normal(shape) * 0.01).astype(np.float32)
+        m[0] = 0.0
+        pitch = pitch8(C) if pad else C
+        wd_, on, inn, _ = _norms_gpu(w, pitch if pad else None, shadow=False)
+        state.append(dict(shape=shape, K=K, RS=RS, C=C, pitch=pitch, flags=flags, w=w, dw=dw, m=m,
+                          wd=wd_, dwd=dev_f32(dw, pitch), md=dev_f32(m, pitch), on=on, inn=inn))
+    for step in range(2):
+        jobs = [B.layer_update(s["wd"], s["dwd"], s["md"], s["on"], s["inn"], s["K"], s["RS"], s["C"], s["pitch"],
+                               s["flags"]) for s in state]
+        B.sgd_momentum_lasso_batched(jobs, lam, lr, mu, wd)
+        torch.cuda.synchronize()
+        for s in state:
+            on64, in64 = oracle.group_norms(s["w"])
+            w_ref, m_ref = oracle.sgd_momentum_lasso(s["w"], s["dw"], s["m"], on64, in64, lam, lr, mu, wd, s["flags"])
+            gw, gm = s["wd"].cpu().numpy(), s["md"].cpu().numpy()
+            C = s["C"]
+            assert rel_err(gw[..., :C], w_ref) <= F32_TOL and rel_err(gm[..., :C], m_ref) <= F32_TOL, s["shape"]
+            assert not gw[0, ..., :C].any() and not gm[0, ..., :C].any()          # the zero filter stays exactly zero
+            assert np.array_equal(s["dwd"].cpu().numpy()[..., :C], s["dw"])       # the loss gradient is read-only
+            if s["pitch"] != C:
+                assert np.isnan(gw[..., C:]).all() and np.isnan(gm[..., C:]).all()
+            # next step starts from the device's fp32 state and fresh norms of it
+            s["w"], s["m"] = gw[..., :C].copy(), gm[..., :C].copy()
+            ws = workspace_for(s)
+            B.group_norms(s["wd"], s["K"], s["RS"], C, s["pitch"], s["on"], s["inn"], None, ws)
+        torch.cuda.synchronize()
+
+
+def workspace_for(s):
+    from gpu_util import workspace
+    return workspace(B.group_norms_workspace_bytes(s["K"], s["RS"], s["C"]))
