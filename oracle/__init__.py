@@ -281,3 +281,32 @@ def sgd_momentum_lasso(w, dw, mom, out_norm, in_norm, lam, lr, mu, wd, flags):
                                              C.c_double(mu), C.c_double(wd), C.c_uint32(flags), K, RS, Cc),
            "sgd_momentum_lasso")
     return w2, m2
+
+
+def bn_fwd(x, gamma, beta, eps: float):
+    """x [..., C] -> (y, mean[C], invstd[C]) with batch statistics over all leading axes."""
+    x = _d(x)
+    Cc = x.shape[-1]
+    pixels = x.size // Cc
+    g, b = _d(gamma), _d(beta)
+    assert g.size == Cc and b.size == Cc
+    y = np.empty_like(x)
+    mean = np.empty(Cc, dtype=np.float64)
+    invstd = np.empty(Cc, dtype=np.float64)
+    _check(_load().oracle_bn_fwd(_p(x), C.c_int64(pixels), Cc, _p(g), _p(b), C.c_double(eps), _p(y), _p(mean), _p(invstd)),
+           "bn_fwd")
+    return y, mean, invstd
+
+
+def bn_bwd(x, dy, gamma, mean, invstd):
+    """-> (dx, dgamma[C], dbeta[C])."""
+    x, dy = _d(x), _d(dy)
+    Cc = x.shape[-1]
+    pixels = x.size // Cc
+    g, m, s = _d(gamma), _d(mean), _d(invstd)
+    dx = np.empty_like(x)
+    dg = np.empty(Cc, dtype=np.float64)
+    db = np.empty(Cc, dtype=np.float64)
+    _check(_load().oracle_bn_bwd(_p(x), _p(dy), C.c_int64(pixels), Cc, _p(g), _p(m), _p(s), _p(dx), _p(dg), _p(db)),
+           "bn_bwd")
+    return dx, dg, db

@@ -398,3 +398,45 @@ int oracle_sgd_momentum_lasso(double* w, const double* dw, double* mom, const do
             }
     return 0;
 }
+
+int oracle_bn_fwd(const double* x, int64_t pixels, int32_t C, const double* gamma, const double* beta, double eps,
+                  double* y, double* mean, double* invstd) {
+    if (!x || !gamma || !beta || !y || !mean || !invstd) return -1;
+    if (pixels <= 0 || C <= 0 || !(eps >= 0.0)) return -2;
+    for (int c = 0; c < C; ++c) {
+        double m = 0.0;
+        for (int64_t p = 0; p < pixels; ++p) m += x[(size_t)p * C + c];
+        m /= (double)pixels;
+        double v = 0.0;
+        for (int64_t p = 0; p < pixels; ++p) {
+            double d = x[(size_t)p * C + c] - m;
+            v += d * d;
+        }
+        v /= (double)pixels; /* biased variance: the batch statistic used for normalisation */
+        mean[c] = m;
+        invstd[c] = 1.0 / sqrt(v + eps);
+        for (int64_t p = 0; p < pixels; ++p) y[(size_t)p * C + c] = (x[(size_t)p * C + c] - m) * invstd[c] * gamma[c] + beta[c];
+    }
+    return 0;
+}
+
+int oracle_bn_bwd(const double* x, const double* dy, int64_t pixels, int32_t C, const double* gamma, const double* mean,
+                  const double* invstd, double* dx, double* dgamma, double* dbeta) {
+    if (!x || !dy || !gamma || !mean || !invstd || !dx || !dgamma || !dbeta) return -1;
+    if (pixels <= 0 || C <= 0) return -2;
+    for (int c = 0; c < C; ++c) {
+        double sg = 0.0, sb = 0.0;
+        for (int64_t p = 0; p < pixels; ++p) {
+            double xh = (x[(size_t)p * C + c] - mean[c]) * invstd[c];
+            sg += dy[(size_t)p * C + c] * xh;
+            sb += dy[(size_t)p * C + c];
+        }
+        dgamma[c] = sg;
+        dbeta[c] = sb;
+        for (int64_t p = 0; p < pixels; ++p) {
+            double xh = (x[(size_t)p * C + c] - mean[c]) * invstd[c];
+            dx[(size_t)p * C + c] = gamma[c] * invstd[c] * (dy[(size_t)p * C + c] - sb / (double)pixels - xh * sg / (double)pixels);
+        }
+    }
+    return 0;
+}

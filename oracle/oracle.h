@@ -123,6 +123,19 @@ int oracle_sgd_momentum_lasso(double* w, const double* dw, double* mom, const do
                               double lambda, double lr, double mu, double wd, uint32_t flags, int32_t K, int32_t RS,
                               int32_t C);
 
+/* Feature (batch) normalisation over the N*H*W pixels of an NHWC tensor, training mode (Sec. 2.1: the
+ * bandwidth-bound layers next to the convolutions; their cost scales with the compacted channel count):
+ *   mean[c], var[c] = batch mean and biased variance of channel c;  invstd[c] = 1/sqrt(var[c] + eps);
+ *   y[p,c] = (x[p,c] - mean[c]) * invstd[c] * gamma[c] + beta[c]. */
+int oracle_bn_fwd(const double* x, int64_t pixels, int32_t C, const double* gamma, const double* beta, double eps,
+                  double* y, double* mean, double* invstd);
+
+/* Its gradients for an upstream gradient dy (the statistics depend on x):  xh = (x - mean)*invstd,
+ *   dgamma[c] = sum_p dy*xh,  dbeta[c] = sum_p dy,
+ *   dx[p,c] = gamma[c]*invstd[c] * (dy[p,c] - dbeta[c]/M - xh[p,c]*dgamma[c]/M),  M = pixels. */
+int oracle_bn_bwd(const double* x, const double* dy, int64_t pixels, int32_t C, const double* gamma, const double* mean,
+                  const double* invstd, double* dx, double* dgamma, double* dbeta);
+
 #ifdef __cplusplus
 }
 #endif
