@@ -219,6 +219,9 @@ def main():
             "group_lasso_grad": timed(lambda: B.group_lasso_grad_batched(net.lasso_jobs, LAMBDA), 5),
             # not part of the timed step: the optimizer step with the regulariser folded in (lr = 0: weights unchanged)
             "optimizer_step_fused": timed(lambda: net.optimizer_step(LAMBDA, 0.0, 0.9, 1e-4), 5),
+            # not part of the timed step either: feature normalisation of every convolution output, forward and backward
+            "bn_fwd": timed(net.bn_fwd_all, 3),
+            "bn_bwd": timed(net.bn_bwd_all, 3),
         }
     fl = {tag: {"fwd": sum(l.spec.flops for l in net.layers),
                 "bwd_data": sum(l.spec.flops for l in net.layers if l.dx is not None),
@@ -280,8 +283,13 @@ def main():
         to = fam[tag]["optimizer_step_fused"]
         out["optimizer_step_fused(not in step)"] = {"ms": round(to, 4), "GBps": round(20 * params[tag] / (to * 1e-3) / 1e9, 1),
                                                     "frac_hbm_peak": round(20 * params[tag] / (to * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        for k, bpe in (("bn_fwd", 6), ("bn_bwd", 10)):
+            t = fam[tag][k]
+            out[k + "(not in step)"] = {"ms": round(t, 4), "GBps": round(bpe * net_of[tag].bn_elements / (t * 1e-3) / 1e9, 1),
+                                        "frac_hbm_peak": round(bpe * net_of[tag].bn_elements / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
         return out
 
+    net_of = {"full": full, "pruned": pruned}
     out = {
         "metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",

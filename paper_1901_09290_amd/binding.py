@@ -31,6 +31,7 @@ EXPORTS = [
     "pt_group_lasso_penalty_batched", "pt_lasso_set_coeff", "pt_compact_nhwc_batched",
     "pt_scatter_nhwc", "pt_group_maxabs", "pt_apply_zero", "pt_sgd_momentum_lasso_batched",
     "pt_zero_groups_batched", "pt_reconcile_plan_batched", "pt_compact_vector_batched", "pt_compact_weights_batched",
+    "pt_bn_workspace_bytes", "pt_bn_fwd", "pt_bn_bwd",
 ]
 
 
@@ -142,6 +143,9 @@ def lib() -> C.CDLL:
             "pt_reconcile_plan_batched": [C.POINTER(EdgePlan), i32, vp],
             "pt_compact_vector_batched": [C.POINTER(GatherVector), i32, vp],
             "pt_compact_weights_batched": [C.POINTER(GatherWeights), i32, vp],
+            "pt_bn_workspace_bytes": [i64, i32, C.POINTER(sz)],
+            "pt_bn_fwd": [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, sz, vp],
+            "pt_bn_bwd": [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp],
         }
         for name, args in sig.items():
             fn = getattr(_lib, name)
@@ -405,3 +409,24 @@ def sgd_momentum_lasso_batched(layers, lam: float, lr: float, momentum: float, w
     arr = _array(layers, LayerUpdate)
     _ck("pt_sgd_momentum_lasso_batched",
         lib().pt_sgd_momentum_lasso_batched(arr, len(layers), lam, lr, momentum, weight_decay, _stream(stream)))
+
+
+def bn_workspace_bytes(pixels: int, Cc: int) -> int:
+    n = C.c_size_t(0)
+    _ck("pt_bn_workspace_bytes", lib().pt_bn_workspace_bytes(pixels, Cc, C.byref(n)))
+    return n.value
+
+
+def bn_fwd(x, pixels: int, Cc: int, x_cpitch: int, gamma, beta, eps: float, y, y_cpitch: int, mean, invstd, ws,
+           stream=None) -> None:
+    p, n = _ws(ws)
+    _ck("pt_bn_fwd", lib().pt_bn_fwd(_ptr(x), pixels, Cc, x_cpitch, _ptr(gamma), _ptr(beta), eps, _ptr(y), y_cpitch,
+                                     _ptr(mean), _ptr(invstd), p, n, _stream(stream)))
+
+
+def bn_bwd(x, dy, pixels: int, Cc: int, x_cpitch: int, dy_cpitch: int, gamma, mean, invstd, dx, dx_cpitch: int,
+           dgamma, dbeta, ws, stream=None) -> None:
+    p, n = _ws(ws)
+    _ck("pt_bn_bwd", lib().pt_bn_bwd(_ptr(x), _ptr(dy), pixels, Cc, x_cpitch, dy_cpitch, _ptr(gamma), _ptr(mean),
+                                     _ptr(invstd), _ptr(dx), dx_cpitch, _ptr(dgamma), _ptr(dbeta), p, n,
+                                     _stream(stream)))

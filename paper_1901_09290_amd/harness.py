@@ -204,6 +204,40 @@ class Network:
             self.update_jobs = (B.LayerUpdate * len(jobs))(*jobs)
         B.sgd_momentum_lasso_batched(self.update_jobs, lam, lr, momentum, weight_decay)
 
+    def _bn_state(self):
+        if not hasattr(self, "bn"):
+            C = max(l.spec.K for l in self.layers)
+            elems = max(l.y.numel() for l in self.layers)
+            pix = max(l.spec.N * l.spec.P * l.spec.Q for l in self.layers)
+            self.bn = {
+                "out": torch.empty(elems, dtype=torch.bfloat16, device=DEV),
+                "gamma": torch.ones(C, device=DEV), "beta": torch.zeros(C, device=DEV),
+                "stat": [torch.empty((2, l.spec.K), device=DEV) for l in self.layers],
+                "grad": torch.empty((2, C), device=DEV),
+                "ws": torch.empty(max(B.bn_workspace_bytes(l.spec.N * l.spec.P * l.spec.Q, l.spec.K)
+                                      for l in self.layers), dtype=torch.uint8, device=DEV),
+            }
+        return self.bn
+
+    def bn_fwd_all(self, eps: float = 1e-5) -> None:
+        """Feature normalisation (training mode) of every convolution's output, layer by layer."""
+        st = self._bn_state()
+        for l, ms in zip(self.layers, st["stat"]):
+            s = l.spec
+            B.bn_fwd(l.y, s.N * s.P * s.Q, s.K, l.yp, st["gamma"], st["beta"], eps, st["out"], l.yp, ms[0], ms[1], st["ws"])
+
+    def bn_bwd_all(self) -> None:
+        """Its backward pass with each layer's dy as the upstream gradient (after bn_fwd_all)."""
+        st = self._bn_state()
+        for l, ms in zip(self.layers, st["stat"]):
+            s = l.spec
+            B.bn_bwd(l.y, l.dy, s.N * s.P * s.Q, s.K, l.yp, l.yp, st["gamma"], ms[0], ms[1], st["out"], l.yp,
+                     st["grad"][0], st["grad"][1], st["ws"])
+
+    @property
+    def bn_elements(self) -> int:
+        return sum(l.spec.N * l.spec.P * l.spec.Q * l.spec.K for l in self.layers)
+
     @property
     def step_flops(self) -> int:
         return sum(l.step_flops for l in self.layers)

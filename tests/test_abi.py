@@ -177,3 +177,36 @@ def test_optimizer_step_validates_on_the_host(lib):
     assert lib.pt_sgd_momentum_lasso_batched(j, 1, 0.1, 0.1, 0.9, 0.0, None) == -2      # pitch < C
     j = (B.LayerUpdate * 1)(B.LayerUpdate(fake, fake, fake, fake, fake, 4, 1, 8, 8, 4, 0))
     assert lib.pt_sgd_momentum_lasso_batched(j, 1, 0.1, 0.1, 0.9, 0.0, None) == -4      # unknown flag bit
+
+
+def test_feature_normalisation_validates_on_the_host(lib):
+    import ctypes as C
+    fake = 256
+    n = C.c_size_t(0)
+    assert lib.pt_bn_workspace_bytes(1000, 64, C.byref(n)) == 0 and n.value >= 2 * 64 * 4
+    assert lib.pt_bn_workspace_bytes(1000, 64, None) == -1
+    assert lib.pt_bn_workspace_bytes(0, 64, C.byref(n)) == -2
+    assert lib.pt_bn_workspace_bytes(1000, 4096, C.byref(n)) == -4
+    ok = (fake, 1000, 60, 64, fake, fake, 1e-5, fake, 64, fake, fake, fake, 1 << 30, None)
+
+    def fwd(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return lib.pt_bn_fwd(*a)
+    assert fwd(a0=None) == -1 and fwd(a4=None) == -1 and fwd(a11=None) == -1
+    assert fwd(a3=56) == -2                  # pitch < C
+    assert fwd(a3=68) == -4                  # rows not 16-byte
+    assert fwd(a0=258) == -4                 # base not 16-byte aligned
+    assert fwd(a6=-1.0) == -2
+    assert fwd(a12=16) == -3
+    okb = (fake, fake, 1000, 60, 64, 64, fake, fake, fake, fake, 64, fake, fake, fake, 1 << 30, None)
+
+    def bwd(**kw):
+        a = list(okb)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return lib.pt_bn_bwd(*a)
+    assert bwd(a1=None) == -1 and bwd(a12=None) == -1
+    assert bwd(a5=32) == -2 and bwd(a10=72 + 4) == -4 and bwd(a14=0) == -3
+    assert bwd(a3=4096, a4=4096, a5=4096, a10=4096) == -4
