@@ -58,7 +58,15 @@ typedef struct pt_conv_desc {
     int32_t x_cpitch;     /* channel pitch of x and dx (>= C) */
     int32_t y_cpitch;     /* channel pitch of y and dy (>= K) */
     int32_t w_cpitch;     /* channel pitch of w (bf16) and of dw (fp32) (>= C) */
+    uint32_t flags;       /* PT_CONV_* bits, 0 = none; unknown bits give PT_ERR_UNSUPPORTED */
 } pt_conv_desc;
+
+/* The caller vouches that the padding channels of the call's bf16 INPUT tensors hold zeros: c in [C, x_cpitch) of x,
+ * k in [K, y_cpitch) of dy, c in [C, w_cpitch) of w.  Without the flag padding may hold anything (NaN included) and
+ * the kernels clear it on the fly, which costs time whenever C (forward) or K (input gradient) is not a multiple
+ * of 8.  Buffers that start out zeroed and are only ever written by this library keep zero padding: no call writes
+ * padding channels.  With the flag set and non-zero padding the results are undefined (never out of bounds). */
+#define PT_CONV_PAD_ZERO 1u
 
 /* Library version (major*10000 + minor*100 + patch) and the last failing HIP error code (0 if none). */
 int32_t pt_version(void);

@@ -18,6 +18,7 @@ PT_OK = 0
 STATUS = {0: "PT_OK", -1: "PT_ERR_NULL", -2: "PT_ERR_SHAPE", -3: "PT_ERR_WORKSPACE", -4: "PT_ERR_UNSUPPORTED",
           -5: "PT_ERR_LAUNCH", -6: "PT_ERR_EMPTY"}
 LASSO_OUT, LASSO_IN = 1, 2
+CONV_PAD_ZERO = 1  # pt_conv_desc.flags: padding channels of the input tensors are zero
 
 EXPORTS = [
     "pt_version", "pt_last_hip_error",
@@ -45,7 +46,7 @@ class PruneTrainError(RuntimeError):
 class ConvDesc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_int32) for n in (
         "N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "P", "Q",
-        "x_cpitch", "y_cpitch", "w_cpitch")]
+        "x_cpitch", "y_cpitch", "w_cpitch")] + [("flags", C.c_uint32)]
 
 
 class LayerWeights(C.Structure):
@@ -170,16 +171,16 @@ def _stream(stream) -> Optional[int]:
     return getattr(stream, "cuda_stream", stream) or None
 
 
-def conv_desc(N, H, W, Cc, K, R, S, stride, pad, x_cpitch=None, y_cpitch=None, w_cpitch=None) -> ConvDesc:
+def conv_desc(N, H, W, Cc, K, R, S, stride, pad, x_cpitch=None, y_cpitch=None, w_cpitch=None, flags=0) -> ConvDesc:
     P = (H + 2 * pad - R) // stride + 1
     Q = (W + 2 * pad - S) // stride + 1
     return ConvDesc(C.sizeof(ConvDesc), N, H, W, Cc, K, R, S, stride, stride, pad, pad, P, Q,
-                    x_cpitch or Cc, y_cpitch or K, w_cpitch or Cc)
+                    x_cpitch or Cc, y_cpitch or K, w_cpitch or Cc, flags)
 
 
-def desc_of(spec, x_cpitch=None, y_cpitch=None, w_cpitch=None) -> ConvDesc:
+def desc_of(spec, x_cpitch=None, y_cpitch=None, w_cpitch=None, flags=0) -> ConvDesc:
     return conv_desc(spec.N, spec.H, spec.W, spec.C, spec.K, spec.R, spec.S, spec.stride, spec.pad,
-                     x_cpitch, y_cpitch, w_cpitch)
+                     x_cpitch, y_cpitch, w_cpitch, flags)
 
 
 def version() -> int:

@@ -15,6 +15,7 @@ inline int32_t check_desc(const pt_conv_desc* d) {
     if (d->P != (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1) return PT_ERR_SHAPE;
     if (d->Q != (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1) return PT_ERR_SHAPE;
     if (d->x_cpitch < d->C || d->y_cpitch < d->K || d->w_cpitch < d->C) return PT_ERR_SHAPE;
+    if (d->flags & ~PT_CONV_PAD_ZERO) return PT_ERR_UNSUPPORTED;
     // limits of the 16/32-bit pixel arithmetic inside the kernels
     if (d->H > 16384 || d->W > 16384 || d->R > 255 || d->S > 255 || d->pad_h > 255 || d->pad_w > 255 ||
         d->stride_h > 255 || d->stride_w > 255)
@@ -37,6 +38,7 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 inline IgemmArgs make_fwd_args(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, uint16_t* y) {
     IgemmArgs a{};
     a.A = x; a.B = w; a.D = y;
+    a.pad_zero = (d->flags & PT_CONV_PAD_ZERO) != 0;
     a.M = d->N * d->P * d->Q;
     a.gW = make_fastdiv((uint32_t)d->Q); a.gH = make_fastdiv((uint32_t)d->P);
     a.srcH = d->H; a.srcW = d->W; a.apitch = d->x_cpitch;
@@ -75,6 +77,7 @@ inline IgemmArgs make_bwd_data_args(const pt_conv_desc* d, const BwdClass& c, in
     const int kpitch = (int)round_up(d->K, 8);
     IgemmArgs a{};
     a.A = dy; a.B = wt; a.D = dx;
+    a.pad_zero = (d->flags & PT_CONV_PAD_ZERO) != 0;  // the k-innermost weight copy always has zero padding
     a.M = d->N * c.gH * c.gW;
     a.gW = make_fastdiv((uint32_t)c.gW); a.gH = make_fastdiv((uint32_t)c.gH);
     a.srcH = d->P; a.srcW = d->Q; a.apitch = d->y_cpitch;
@@ -208,9 +211,9 @@ inline hipError_t launch_wgrad(WgradArgs& a, const WgradPlan& p, bool vec, hipSt
     }
     // wave grids and pipeline depths from measurements on ResNet-50 shapes
     if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKP, 4, 2, 3>(a, st);
-    if (p.BM == 64 && p.BN == 128) return launch_wgrad_dl_cfg<64, 128, kWgDlBKP, 2, 2, 3>(a, st);
-    if (p.BM == 128 && p.BN == 64) return launch_wgrad_dl_cfg<128, 64, kWgDlBKP, 2, 2, 3>(a, st);
-    return launch_wgrad_dl_cfg<64, 64, kWgDlBKP, 2, 2, 4>(a, st);
+    if (p.BM == 64 && p.BN == 128) return launch_wgrad_dl_cfg<64, 128, kWgDlBKP, 2, 2, 3, 2>(a, st);
+    if (p.BM == 128 && p.BN == 64) return launch_wgrad_dl_cfg<128, 64, kWgDlBKP, 2, 2, 3, 2>(a, st);
+    return launch_wgrad_dl_cfg<64, 64, kWgDlBKP, 2, 2, 4, 2>(a, st);
 }
 
 }  // namespace pt

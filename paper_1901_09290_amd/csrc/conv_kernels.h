@@ -51,6 +51,47 @@ __device__ __forceinline__ uint4 mask8(uint4 v, bool ok, const Mask8& k) {
     return v;
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// the same mask applied to an 8-element MFMA operand fragment held in registers
+template <typename F>
+__device__ __forceinline__ F mask_frag(F v, const Mask8& k) {
+    static_assert(sizeof(F) == 16, "fragment of eight 16-bit elements");
+    u32x4 u = __builtin_bit_cast(u32x4, v);
+    u[0] &= k.m[0];
+    u[1] &= k.m[1];
+    u[2] &= k.m[2];
+    u[3] &= k.m[3];
+    return __builtin_bit_cast(F, u);
+}
+
+// LDS reads issued as inline assembly are ordered only by explicit waits: the compiler neither moves them nor
+// adds waits of its own.  The result registers must not be touched before lds_wait() has been applied to them.
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) {
+    static_assert(OFF >= 0 && OFF < 65536, "DS offset field");
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+// Waits until at most N of this wave's LDS reads are outstanding (they return in order) and makes `first`
+// depend on the wait; lds_tie() extends the dependence to further registers.
+template <int N, typename V>
+__device__ __forceinline__ void lds_wait(V& first) {
+    static_assert(N >= 0 && N < 16, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(first) : "n"(N));
+}
+template <typename V>
+__device__ __forceinline__ void lds_tie(V& v) {
+    asm volatile("" : "+v"(v));
+}
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 #ifdef PT_KERNEL_TIMING
 // Working-build instrumentation (never defined for the library): per-workgroup phase time stamps.
 __device__ unsigned long long pt_dbg_times[4 * 16384];
@@ -107,7 +148,31 @@ struct IgemmArgs {
     int tiles_n;
     int d_vec;    // 8-byte stores allowed (pitch % 4 == 0, base 8-byte aligned)
     int d_vec16;  // 16-byte stores allowed (pitch % 8 == 0, base 16-byte aligned)
+    // Direct kernel, channel counts that are not multiples of 8: which operand fragments hold the 8-chunk with the
+    // undefined tail.  Bit (block * 4 + sub-step) for folded runs (block = 64-channel block of the run), bit
+    // (sub-step) of the last block otherwise; _lo for lanes 0..31 (even chunks), _hi for lanes 32..63.
+    uint64_t tail_lo, tail_hi;
+    int tail_nvalid;  // defined elements of the tail chunk (1..7), 8 when there is none
+    int pad_zero;     // the caller vouches that the padding channels of both operands hold zeros
 };
+
+// Fills tail_lo / tail_hi / tail_nvalid (see IgemmArgs) for the direct kernel's 64-channel blocks.
+inline void set_tail_tables(IgemmArgs& a) {
+    a.tail_lo = a.tail_hi = 0;
+    a.tail_nvalid = 8;
+    const int creal = a.fold ? a.Creal : a.Cred;
+    if ((creal & 7) == 0) return;
+    a.tail_nvalid = creal & 7;
+    const int tail_chunk = creal >> 3;                              // chunk index of the tail inside one run
+    const int nblk = a.fold ? (a.CredP + 63) >> 6 : 1;              // folded: every block; else the last block only
+    const int base = a.fold ? 0 : ((a.CredP - 1) >> 6) << 3;        // first chunk of the last block
+    const int per = a.fold ? (int)(a.Cfold.d >> 3) : 0x7fffffff;    // chunks per run
+    for (int i = 0; i < nblk * 4; ++i) {                            // i = block * 4 + sub-step: chunks 2i, 2i + 1
+        const int c0 = base + 2 * i, c1 = c0 + 1;
+        if ((a.fold ? c0 % per : c0) == tail_chunk) a.tail_lo |= 1ull << i;
+        if ((a.fold ? c1 % per : c1) == tail_chunk) a.tail_hi |= 1ull << i;
+    }
+}
 
 // VEC: every operand row is 16-byte aligned (pitches are multiples of 8 elements).
 template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, int MINB, bool VEC>
@@ -367,7 +432,8 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED>
+// TAIL = some run of channels ends inside an 8-chunk whose remaining elements are undefined.
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED, bool TAIL = RAGGED>
 __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int NW = WGM * WGN, NT = 64 * NW, BK = 64;
@@ -456,29 +522,18 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
             if (++i_ts == a.TS) { i_ts = 0; ++i_tr; }
         }
     };
-    // zero the channel tail of this lane's own vectors of `stage` (their data has landed for this wave)
-    auto fixup = [&](int stage) {
-        if constexpr (RAGGED) {
-            const int cpos = c_cb + kvoff;
-            const int nvalid = a.fold ? a.Creal - (cpos - (int)fdiv((uint32_t)cpos, a.Cfold) * (int)a.Cfold.d) : a.Cred - cpos;
-            if (cpos < a.Cred && nvalid < 8) {
-                const Mask8 k = make_mask8(nvalid);
-                uint8_t* sbase = smem_b + stage * STAGE_BYTES + lane * 16;
-#pragma unroll
-                for (int j = 0; j < LA + LB; ++j) {
-                    uint4* p = reinterpret_cast<uint4*>(sbase + (j < LA ? (wave + NW * j) * 1024
-                                                                        : BM * 128 + (wave + NW * (j - LA)) * 1024));
-                    *p = mask8(*p, true, k);
-                }
-            }
-        }
-    };
-
     // ---- MFMA state ---------------------------------------------------------------------------
     const int wm = wave % WGM, wn = wave / WGM;
     const int l32 = lane & 31;
     const int swz = (l32 >> 1) & 7;  // all operand rows of this lane are l32 (mod 32)
     const int kc0 = lane >> 5;
+    // A channel count that is not a multiple of 8 leaves undefined elements (memory padding) at the end of the last
+    // 8-chunk of every run of channels.  Those elements are cleared in registers, in both operands, before they reach
+    // the matrix pipe.  Which (block, sub-step) fragments hold such a chunk is fixed per kernel: one bit each, for this
+    // lane (tail_mine) and for any lane of the wave (tail_any, uniform); the host fills the tables (set_tail_tables).
+    const uint64_t tail_any = a.tail_lo | a.tail_hi;
+    const uint64_t tail_mine = kc0 ? a.tail_hi : a.tail_lo;
+    const Mask8 tail_mask = make_mask8(TAIL ? a.tail_nvalid : 8);
     f32x16 acc[TN][TM];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
@@ -503,31 +558,58 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
         constexpr bool CHECK = decltype(check_tag)::value;
         const uint8_t* sA = smem_b + stage * STAGE_BYTES;
         const uint8_t* sB = sA + BM * 128;
-        const int nks = RAGGED ? min(BK / 16, (a.Cred - c_cb + 15) >> 4) : BK / 16;
-        // operand fragments are double-buffered in registers: the LDS reads of k-step ks+1 are issued
-        // before the MFMAs of k-step ks, so LDS latency hides behind the matrix pipe
-        bf16x8 fw[2][TN], fp[2][TM];
-        auto read_frags = [&](int ks, int b) {
-            const int pc = (((ks * 2 + kc0) ^ swz) << 4);
+        // One stage = BK/16 sub-steps of (fragment reads, MFMAs); all sub-steps always run (chunks past the channel
+        // count were fetched from the zero page).  MASKED: the fragments of this stage that hold a tail chunk are
+        // cleared first.  The body is free of branches either way: a branch per sub-step costs the compiler's
+        // schedule far more than the masking does.
+        auto body = [&](auto masked_tag, int bit0) {
+            constexpr bool MASKED = decltype(masked_tag)::value;
+            Mask8 km[BK / 16];
+            if constexpr (MASKED) {
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                fw[b][tn] = *reinterpret_cast<const bf16x8*>(sB + (wn * WTN + tn * 32 + l32) * 128 + pc);
+                for (int ks = 0; ks < BK / 16; ++ks) {
+                    const bool mine = (tail_mine >> (bit0 + ks)) & 1;
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                fp[b][tm] = *reinterpret_cast<const bf16x8*>(sA + (wm * WTM + tm * 32 + l32) * 128 + pc);
-        };
-        read_frags(0, 0);
+                    for (int w = 0; w < 4; ++w) km[ks].m[w] = mine ? tail_mask.m[w] : 0xffffffffu;
+                }
+            }
+            bf16x8 fw[2][TN], fp[2][TM];
+            auto read_frags = [&](int ks, int b) {
+                const int pc = (((ks * 2 + kc0) ^ swz) << 4);
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            if (RAGGED && ks >= nks) break;
-            if (ks + 1 < BK / 16 && (!RAGGED || ks + 1 < nks)) read_frags(ks + 1, (ks + 1) & 1);
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
+                for (int tn = 0; tn < TN; ++tn)
+                    fw[b][tn] = *reinterpret_cast<const bf16x8*>(sB + (wn * WTN + tn * 32 + l32) * 128 + pc);
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
-                    if (!CHECK || (n_live[tn] && m_live[tm]))
-                        acc[tn][tm] =
-                            __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][tn], fp[ks & 1][tm], acc[tn][tm], 0, 0, 0);
+                    fp[b][tm] = *reinterpret_cast<const bf16x8*>(sA + (wm * WTM + tm * 32 + l32) * 128 + pc);
+            };
+            read_frags(0, 0);
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
+                if constexpr (MASKED) {
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) fw[ks & 1][tn] = mask_frag(fw[ks & 1][tn], km[ks]);
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) fp[ks & 1][tm] = mask_frag(fp[ks & 1][tm], km[ks]);
+                }
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+                        if (!CHECK || (n_live[tn] && m_live[tm]))
+                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][tn], fp[ks & 1][tm],
+                                                                                  acc[tn][tm], 0, 0, 0);
+            }
+        };
+        if constexpr (TAIL) {
+            // bits of this stage's sub-steps in tail_any / tail_mine: folded runs index by (64-channel block,
+            // sub-step); otherwise only the last block of a tap has a tail
+            const int bit0 = a.fold ? (c_cb >> 6) * 4 : (c_cb + BK > a.Cred ? 0 : 32);
+            if ((tail_any >> bit0) & 15) body(std::true_type{}, bit0);  // wave-uniform
+            else body(std::false_type{}, 0);
+        } else {
+            body(std::false_type{}, 0);
         }
         c_cb += BK;
         if (c_cb >= a.CredP) c_cb = 0;
@@ -543,8 +625,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
                     // loads of steps kt+1 .. kt+STAGES-2 may stay in flight; near the end just drain
                     if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * LPT>();
                     else wait_vmcnt<0>();
-                    fixup(s);
-                    if constexpr (RAGGED) wait_lgkmcnt0();
                     barrier_nofence();  // stage s complete for every wave; stage (s-1) free again
                     if (kt + STAGES - 1 < nk) issue((s + STAGES - 1) % STAGES);
                     compute(s, check_tag);
@@ -609,27 +689,34 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 }
 
 template <int BM, int BN, int WGM, int WGN, int STAGES>
-inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
+inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st, int force_ragged = -1) {
     constexpr int NT = 64 * WGM * WGN;
     constexpr size_t lds = (size_t)STAGES * (BM + BN) * 128;
     static_assert(lds <= 160 * 1024, "LDS capacity");
     // last channel block of a tap is short and/or some chunk has a masked tail
-    const bool ragged = (a.Cred % 64) != 0 || (a.fold && a.Creal % 8 != 0);
-    const void* kern = ragged ? reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true>)
-                              : reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false>);
-    static bool attr_set[2] = {false, false};  // one-time opt-in to more than 64 KiB of dynamic LDS
-    if (lds > 65536 && !attr_set[ragged]) {
+    const bool ragged = force_ragged >= 0 ? force_ragged != 0 : ((a.Cred % 64) != 0 || (a.fold && a.Creal % 8 != 0));
+    a.nk = a.TR * a.TS * (int)ceil_div(a.CredP, 64);  // steps are (tap, block of 64 channels)
+    a.tiles_n = (int)ceil_div(a.Nout, BN);
+    set_tail_tables(a);
+    // variant: 0 = whole 64-channel blocks, 1 = partial blocks but no undefined elements (channel count a multiple
+    // of 8, or the caller vouches for zero padding), 2 = partial blocks with tails to clear
+    const int variant = !ragged ? 0 : ((a.tail_lo | a.tail_hi) == 0 || a.pad_zero ? 1 : 2);
+    const void* kern = variant == 0   ? reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false>)
+                       : variant == 1 ? reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false>)
+                                      : reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true>);
+    static bool attr_set[3] = {false, false, false};  // one-time opt-in to more than 64 KiB of dynamic LDS
+    if (lds > 65536 && !attr_set[variant]) {
         hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set[ragged] = true;
+        attr_set[variant] = true;
     }
-    const int tiles_m = (int)ceil_div(a.M, BM);
-    a.tiles_n = (int)ceil_div(a.Nout, BN);
-    a.nk = a.TR * a.TS * (int)ceil_div(a.CredP, 64);  // steps are (tap, block of 64 channels)
-    if (ragged)
-        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true>), dim3(tiles_m * a.tiles_n), dim3(NT), lds, st, a);
+    const dim3 grid((unsigned)(ceil_div(a.M, BM) * a.tiles_n)), block(NT);
+    if (variant == 0)
+        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false>), grid, block, lds, st, a);
+    else if (variant == 1)
+        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false>), grid, block, lds, st, a);
     else
-        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, false>), dim3(tiles_m * a.tiles_n), dim3(NT), lds, st, a);
+        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true>), grid, block, lds, st, a);
     return hipSuccess;
 }
 
@@ -876,29 +963,18 @@ __device__ __forceinline__ s16x4 lds_read_tr16_b64(uint32_t addr) {
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
     return v;
 }
-// Waits until at most N of this wave's LDS reads are outstanding (they return in order) and makes `first`
-// depend on the wait; lds_tie() extends the dependence to further registers.
-template <int N>
-__device__ __forceinline__ void lds_wait(s16x4& first) {
-    static_assert(N >= 0 && N < 16, "lgkmcnt range");
-    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(first) : "n"(N));
-}
-__device__ __forceinline__ void lds_tie(s16x4& v) { asm volatile("" : "+v"(v)); }
 __device__ __forceinline__ bf16x8 join_halves(s16x4 lo, s16x4 hi) {
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
 
-template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES>
-__global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs a) {
+// KSPLIT wave groups share one tile: group g multiplies the g-th part of every stage's pixel sub-steps, and the
+// groups' accumulators are added through LDS before the store.  More waves per SIMD to hide LDS and barrier
+// latency, with the same LDS footprint, loads and partial-sum traffic as one group.
+template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1>
+__global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const WgradArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
-    constexpr int NW = WGM * WGN;
+    constexpr int NWT = WGM * WGN;       // waves of one group: the wave grid over the tile
+    constexpr int NW = NWT * KSPLIT;     // all waves: they share the loads
     constexpr int RBX = BM * 2, RBY = BN * 2;              // bytes per pixel row
     constexpr int CPRX = RBX / 16, CPRY = RBY / 16;        // 16-byte chunks per row
     constexpr int RPLX = 64 / CPRX, RPLY = 64 / CPRY;      // pixel rows per wave-level load
@@ -910,10 +986,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
     static_assert((RBX == 128 || RBX == 256) && (RBY == 128 || RBY == 256), "row size");
     static_assert(NW % 2 == 0 && LX >= 1 && LY >= 1 && BKP % (RPLX * NW) == 0 && BKP % (RPLY * NW) == 0, "tile config");
     static_assert(TM >= 1 && TN >= 1 && BKP % 16 == 0 && STAGES >= 2 && (STAGES - 2) * LPT < 64, "tile config");
+    static_assert(KSPLIT >= 1 && (BKP / 16) % KSPLIT == 0 && NW <= 16, "wave groups");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_b[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kg = wave / NWT, wave_t = wave - kg * NWT;  // wave group, wave inside the group
     PT_STAMP(0);
     // Workgroup ids are dealt round-robin to the 8 XCDs.  All tiles of one pixel split read the same x and dy
     // slabs, so each XCD gets a contiguous range of the split-major (split, tile) order: a split's tiles run
@@ -973,7 +1051,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
     };
 
     // ---- MFMA state ---------------------------------------------------------------------------
-    const int wm = wave % WGM, wn = wave / WGM;
+    const int wm = wave_t % WGM, wn = wave_t / WGM;
     // transpose-read geometry: 16-lane group g16, lane t16; source lane t16 points at pixel row (t16 >> 2)
     // and channel quad (t16 & 3); the result is 4 consecutive pixels for channel 16*(g16 & 1) + t16.
     const int g16 = lane >> 4, t16 = lane & 15;
@@ -991,22 +1069,23 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
     // 32-bit LDS addresses of this lane's transposing reads: per 32-wide tile the 4-pixel halves at rows r, r+4.
     // The swizzle term does not depend on the 16-pixel sub-step, which therefore is an immediate offset.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem_b;
+    constexpr int NKS = BKP / 16 / KSPLIT, NRD = 2 * (TM + TN);  // sub-steps per stage and group, LDS reads per sub-step
     uint32_t ax[TM][2], ay[TN][2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int r = tr_row + 4 * h;
+        const int r0 = kg * NKS * 16;  // first pixel row of this group's sub-steps (a multiple of 16: same swizzle)
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int u = (wm * WTM + tm * 32) / 16 + tr_u;
-            ax[tm][h] = lds_base + (uint32_t)(r * RBX + ((u ^ swz(r, RBX)) << 5) + tr_b);
+            ax[tm][h] = lds_base + (uint32_t)((r0 + r) * RBX + ((u ^ swz(r, RBX)) << 5) + tr_b);
         }
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const int u = (wn * WTN + tn * 32) / 16 + tr_u;
-            ay[tn][h] = lds_base + (uint32_t)(r * RBY + ((u ^ swz(r, RBY)) << 5) + tr_b);
+            ay[tn][h] = lds_base + (uint32_t)((r0 + r) * RBY + ((u ^ swz(r, RBY)) << 5) + tr_b);
         }
     }
-    constexpr int NKS = BKP / 16, NRD = 2 * (TM + TN);  // sub-steps per stage, LDS reads per sub-step
     static_assert(NRD < 16, "fragment reads per sub-step must fit the lgkmcnt field");
     // One stage: the reads of sub-step ks+1 are in flight while the MFMAs of sub-step ks run.
     auto compute = [&](int stage) {
@@ -1054,7 +1133,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
     };
 
     const int nk = it1 - it0;
-    const bool late = STAGES >= 3 && NW == 8 && (wave & 4) != 0;
+    const bool late = STAGES >= 3 && NW >= 8 && (wave & 4) != 0;
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < nk) issue(it0 + s, s);
@@ -1080,6 +1159,34 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
     }
 
     PT_STAMP(2);
+    if constexpr (KSPLIT > 1) {
+        // groups 1.. park their accumulators in LDS (the stage buffers are dead: every load was waited for and the
+        // barrier below follows every wave's last read), group 0 adds them in group order and stores
+        float* red = reinterpret_cast<float*>(smem_b);
+        constexpr int PER_WAVE = TM * TN * 16 * 64;
+        __syncthreads();
+        if (kg > 0) {
+            float* dst = red + ((kg - 1) * NWT + wave_t) * PER_WAVE + lane;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) dst[((tm * TN + tn) * 16 + v) * 64] = acc[tm][tn][v];
+        }
+        __syncthreads();
+        if (kg > 0) return;
+#pragma unroll
+        for (int g = 1; g < KSPLIT; ++g) {
+            const float* src = red + ((g - 1) * NWT + wave_t) * PER_WAVE + lane;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[tm][tn][v] += src[((tm * TN + tn) * 16 + v) * 64];
+        }
+    }
     // ---- epilogue: lane holds k (column) = lane%32 and rows 8g + 4*(lane/32) + {0..3} = 4 consecutive c
     float* out = a.OUT + (a.direct ? 0 : (int64_t)split * a.K * a.out_row_pitch);
 #pragma unroll
@@ -1119,12 +1226,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_wgrad_dl(const WgradArgs 
 #endif
 }
 
-template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES>
+template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1>
 inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
-    constexpr int NT = 64 * WGM * WGN;
-    constexpr size_t lds = (size_t)STAGES * BKP * (BM + BN) * 2;
+    constexpr int NT = 64 * WGM * WGN * KSPLIT;
+    constexpr size_t ring = (size_t)STAGES * BKP * (BM + BN) * 2, red = (size_t)(KSPLIT - 1) * BM * BN * 4;
+    constexpr size_t lds = ring > red ? ring : red;
     static_assert(lds <= 160 * 1024, "LDS capacity");
-    auto kern = k_wgrad_dl<BM, BN, BKP, WGM, WGN, STAGES>;
+    auto kern = k_wgrad_dl<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT>;
     static bool attr_set = false;
     if (lds > 65536 && !attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -46,7 +46,8 @@ class ConvLayer:
                  host: Optional[Dict[str, np.ndarray]] = None, w_master: Optional[np.ndarray] = None):
         s = self.spec = spec
         self.xp, self.yp, self.wp = pitch8(s.C), pitch8(s.K), pitch8(s.C)
-        self.desc = B.desc_of(s, self.xp, self.yp, self.wp)
+        # every buffer below starts zeroed and no library call writes padding channels: the padding stays zero
+        self.desc = B.desc_of(s, self.xp, self.yp, self.wp, B.CONV_PAD_ZERO)
         self.RS = s.R * s.S
         bf, f32 = torch.bfloat16, torch.float32
         if host is not None:

@@ -29,12 +29,12 @@ def rel_err(got, ref) -> float:
     return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
 
 
-def dev_bf16(a: np.ndarray, pitch=None) -> torch.Tensor:
+def dev_bf16(a: np.ndarray, pitch=None, pad=0x7FC0) -> torch.Tensor:
     """fp32 values on the bf16 grid -> device bf16 tensor; optional innermost pitch (padding = NaN so
-    that any use of padding as data poisons the result)."""
+    that any use of padding as data poisons the result, unless `pad` says otherwise)."""
     bits = wl.bf16_bits(a)
     if pitch is not None and pitch != a.shape[-1]:
-        full = np.full(a.shape[:-1] + (pitch,), 0x7FC0, dtype=np.uint16)
+        full = np.full(a.shape[:-1] + (pitch,), pad, dtype=np.uint16)
         full[..., : a.shape[-1]] = bits
         bits = full
     return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
@@ -71,12 +71,14 @@ def pitch8(n: int) -> int:
     return (n + 7) // 8 * 8
 
 
-def run_conv_all(spec, x, w, dy, xp=None, yp=None, wp=None):
+def run_conv_all(spec, x, w, dy, xp=None, yp=None, wp=None, pad_zero=False):
     """Runs fwd, bwd_data, bwd_weight through the C ABI. Returns (y, dx, dw) as fp32 numpy, logical extents.
-    Output buffers are pre-filled with a sentinel so unwritten elements are caught."""
+    Output buffers are pre-filled with a sentinel so unwritten elements are caught.  pad_zero: the inputs'
+    padding channels hold zeros and the descriptor says so (otherwise they hold NaN)."""
     xp, yp, wp = xp or spec.C, yp or spec.K, wp or spec.C
-    d = B.desc_of(spec, xp, yp, wp)
-    xd, wd, dyd = dev_bf16(x, xp), dev_bf16(w, wp), dev_bf16(dy, yp)
+    d = B.desc_of(spec, xp, yp, wp, B.CONV_PAD_ZERO if pad_zero else 0)
+    pad = 0 if pad_zero else 0x7FC0
+    xd, wd, dyd = dev_bf16(x, xp, pad), dev_bf16(w, wp, pad), dev_bf16(dy, yp, pad)
     y = empty_bf16((spec.N, spec.P, spec.Q, yp), fill=0x7FC0)
     dx = empty_bf16((spec.N, spec.H, spec.W, xp), fill=0x7FC0)
     dw = torch.full((spec.K, spec.R, spec.S, wp), float("nan"), dtype=torch.float32, device=DEV)

@@ -54,6 +54,10 @@ def test_workspace_queries_validate_descriptor(lib):
     bad.struct_size = 12
     with pytest.raises(B.PruneTrainError):
         B.conv_bwd_weight_workspace_bytes(bad)
+    assert B.conv_fwd_workspace_bytes(B.conv_desc(4, 16, 16, 16, 16, 3, 3, 1, 1, flags=B.CONV_PAD_ZERO)) == 0
+    with pytest.raises(B.PruneTrainError) as e:
+        B.conv_fwd_workspace_bytes(B.conv_desc(4, 16, 16, 16, 16, 3, 3, 1, 1, flags=2))     # unknown flag bit
+    assert e.value.status == -4
     n = C.c_size_t(0)
     assert lib.pt_conv_fwd_workspace_bytes(None, C.byref(n)) == -1
     assert lib.pt_conv_fwd_workspace_bytes(C.byref(d), None) == -1

@@ -15,11 +15,11 @@ def _spec(N, H, W, C, K, R, st, pad):
     return ConvSpec("t", N, H, W, C, K, R, R, st, pad, None, None)
 
 
-def _check_full(spec, seed, xp=None, yp=None, wp=None):
+def _check_full(spec, seed, xp=None, yp=None, wp=None, pad_zero=False):
     from gpu_util import CONV_TOL, rel_err, run_conv_all
     rng = np.random.Generator(np.random.PCG64(seed))
     t = wl.conv_tensors(spec, rng)
-    y, dx, dw = run_conv_all(spec, t["x"], t["w"], t["dy"], xp, yp, wp)
+    y, dx, dw = run_conv_all(spec, t["x"], t["w"], t["dy"], xp, yp, wp, pad_zero)
     s = oracle.shape_of(spec)
     errs = (rel_err(y, oracle.conv_fwd(s, t["x"], t["w"])),
             rel_err(dx, oracle.conv_bwd_data(s, t["dy"], t["w"])),
@@ -73,6 +73,9 @@ RAGGED = [
     ((3, 13, 13, 5, 24, 3, 1, 1), True),
     ((2, 11, 11, 12, 40, 5, 1, 2), True),  # pitch 16 with 12 real channels: a masked chunk inside every tap
     ((2, 9, 9, 32, 48, 2, 1, 0), True),    # folded run of exactly 64 elements
+    ((2, 20, 20, 45, 38, 3, 1, 1), True),  # folded runs of 48 with 45 real channels: a tail in every 64-block
+    ((2, 20, 20, 63, 40, 3, 1, 1), True),  # one 64-block per tap, tail in its last chunk
+    ((2, 14, 14, 209, 45, 1, 1, 0), True),  # tail only in the last of four blocks
     # same shapes stored dense: pitches are odd, element-wise path
     ((2, 10, 10, 37, 51, 3, 1, 1), False),
     ((1, 9, 9, 19, 131, 3, 2, 1), False),
@@ -88,6 +91,16 @@ def test_ragged_channel_counts(case, padded):
         _check_full(spec, 200 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C))
     else:
         _check_full(spec, 300 + sum(case))
+
+
+@pytest.mark.parametrize("case", [c for c, padded in RAGGED if padded] + [(2, 20, 20, 45, 38, 3, 1, 1),
+                                                                          (2, 20, 20, 63, 40, 3, 1, 1),
+                                                                          (2, 14, 14, 209, 45, 1, 1, 0)])
+def test_ragged_channel_counts_with_zero_padding_vouched(case):
+    """PT_CONV_PAD_ZERO: the inputs' padding channels are zero and the kernels skip clearing them."""
+    from gpu_util import pitch8
+    spec = _spec(*case)
+    _check_full(spec, 400 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=True)
 
 
 def test_results_are_run_to_run_identical():
