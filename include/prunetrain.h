@@ -64,8 +64,10 @@ typedef struct pt_conv_desc {
 /* The caller vouches that the padding channels of the call's bf16 INPUT tensors hold zeros: c in [C, x_cpitch) of x,
  * k in [K, y_cpitch) of dy, c in [C, w_cpitch) of w.  Without the flag padding may hold anything (NaN included) and
  * the kernels clear it on the fly, which costs time whenever C (forward) or K (input gradient) is not a multiple
- * of 8.  Buffers that start out zeroed and are only ever written by this library keep zero padding: no call writes
- * padding channels.  With the flag set and non-zero padding the results are undefined (never out of bounds). */
+ * of 8.  Buffers that start out zeroed and are only ever written by this library keep zero padding: without the
+ * flag no call writes padding channels, and with it pt_conv_fwd / pt_conv_bwd_data[_crsk] write only zeros there
+ * (the last 8-channel chunk of y / dx goes out as one 16-byte store).  With the flag set and non-zero input
+ * padding the results are undefined (never out of bounds). */
 #define PT_CONV_PAD_ZERO 1u
 
 /* Library version (major*10000 + minor*100 + patch) and the last failing HIP error code (0 if none). */

@@ -673,6 +673,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
                         uint16_t* dst = a.D + dpix + ch;
                         if (a.d_vec16 && ch + 7 < a.Nout) {
                             *reinterpret_cast<uint4*>(dst) = make_uint4(ps[0], qs[0], ps[1], qs[1]);
+                        } else if (a.d_vec16 && a.pad_zero && ch + 8 <= a.dpitch) {
+                            // zero-padded tensors: the last chunk goes out as one vector too, zeros in its padding
+                            *reinterpret_cast<uint4*>(dst) =
+                                mask8(make_uint4(ps[0], qs[0], ps[1], qs[1]), true, make_mask8(a.Nout - ch));
                         } else {
                             const uint32_t w[4] = {ps[0], qs[0], ps[1], qs[1]};
 #pragma unroll
