@@ -310,3 +310,31 @@ def bn_bwd(x, dy, gamma, mean, invstd):
     _check(_load().oracle_bn_bwd(_p(x), _p(dy), C.c_int64(pixels), Cc, _p(g), _p(m), _p(s), _p(dx), _p(dg), _p(db)),
            "bn_bwd")
     return dx, dg, db
+
+
+def plan_layer_removal(n_layers: int, edges):
+    """Layer removal after a plan (Sec. 3.1, "Layer Removal by Overlapping Regularization Groups"), as sets.
+
+    edges: one (producers, consumers, n_keep, fed_outside, read_outside) per channel edge.  An edge with no
+    survivors carries nothing, so the layers on either side of it go; an edge whose listed producers are all
+    gone (and that nothing outside feeds) carries nothing, one whose listed consumers are all gone (and that
+    nothing outside reads) is read by nobody.  Iterated to the fixed point.  Returns (removed layer set, dead
+    edge set, cut) where cut says that an edge read outside the listed layers has died."""
+    dead = {e for e, ed in enumerate(edges) if ed[2] == 0}
+    removed = set()
+    while True:
+        new_removed = set(removed)
+        for e in dead:
+            new_removed |= set(edges[e][0]) | set(edges[e][1])
+        new_dead = set(dead)
+        for e, (prod, cons, _, fed_outside, read_outside) in enumerate(edges):
+            starved = len(prod) > 0 and not fed_outside and set(prod) <= new_removed
+            unread = len(cons) > 0 and not read_outside and set(cons) <= new_removed
+            if starved or unread:
+                new_dead.add(e)
+        if new_removed == removed and new_dead == dead:
+            break
+        removed, dead = new_removed, new_dead
+    assert all(0 <= l < n_layers for l in removed)
+    cut = any(edges[e][4] for e in dead)
+    return removed, dead, cut
