@@ -44,7 +44,7 @@ typedef enum pt_status {
     PT_ERR_WORKSPACE = -3,   /* workspace smaller than the matching *_workspace_bytes() */
     PT_ERR_UNSUPPORTED = -4, /* valid but outside this build's limits (see each call) */
     PT_ERR_LAUNCH = -5,      /* a HIP call failed; pt_last_hip_error() holds its code */
-    PT_ERR_EMPTY = -6        /* reserved: a keep mask with no survivors (layer removal is the caller's job) */
+    PT_ERR_EMPTY = -6        /* pt_plan_layer_removal: an edge that is read outside the listed layers has died */
 } pt_status;
 
 /* Convolution problem: cross-correlation with zero padding, dilation 1, one group, no bias.
@@ -333,6 +333,28 @@ int32_t pt_bn_fwd(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch
 int32_t pt_bn_bwd(const uint16_t* x, const uint16_t* dy, int64_t pixels, int32_t C, int32_t x_cpitch,
                   int32_t dy_cpitch, const float* gamma, const float* mean, const float* invstd, uint16_t* dx,
                   int32_t dx_cpitch, float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- layer removal: Sec. 3.1 ("Layer Removal by Overlapping Regularization Groups") --------------------------- */
+
+/* HOST-only graph logic, no device work.  After a plan, an edge with no survivors (n_keep == 0) carries nothing: the
+ * layers writing it and the layers reading it are removed.  Removal propagates: an edge all of whose producers are
+ * removed carries nothing, an edge all of whose consumers are removed is read by nobody - unless it is also fed
+ * (PT_EDGE_FED_OUTSIDE: the network input, an identity shortcut from elsewhere) or read (PT_EDGE_READ_OUTSIDE: the
+ * classifier behind the last stage) outside the listed layers.  An edge with no listed producers counts as fed, one
+ * with no listed consumers as read.  removed_layers[n_layers] and dead_edges[n_edges] (host, 0/1) receive the fixed
+ * point.  Returns PT_ERR_EMPTY (outputs still filled) if an edge that is read outside has died: the network is cut.
+ * In a residual network the result is whole branches taken out with the shortcut left in place. */
+#define PT_EDGE_FED_OUTSIDE 1
+#define PT_EDGE_READ_OUTSIDE 2
+typedef struct pt_removal_edge {
+    const int32_t* producers; /* host: ids of the layers whose output channels are this edge */
+    const int32_t* consumers; /* host: ids of the layers whose input channels are this edge */
+    int32_t n_prod, n_cons;
+    int32_t n_keep;           /* survivors in the latest plan (host copy of the plan's device count) */
+    int32_t external;         /* PT_EDGE_* bits */
+} pt_removal_edge;
+int32_t pt_plan_layer_removal(const pt_removal_edge* edges, int32_t n_edges, int32_t n_layers, uint8_t* removed_layers,
+                              uint8_t* dead_edges);
 
 #ifdef __cplusplus
 }

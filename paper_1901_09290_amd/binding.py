@@ -18,6 +18,7 @@ PT_OK = 0
 STATUS = {0: "PT_OK", -1: "PT_ERR_NULL", -2: "PT_ERR_SHAPE", -3: "PT_ERR_WORKSPACE", -4: "PT_ERR_UNSUPPORTED",
           -5: "PT_ERR_LAUNCH", -6: "PT_ERR_EMPTY"}
 LASSO_OUT, LASSO_IN = 1, 2
+EDGE_FED_OUTSIDE, EDGE_READ_OUTSIDE = 1, 2
 CONV_PAD_ZERO = 1  # pt_conv_desc.flags: padding channels of the input tensors are zero
 
 EXPORTS = [
@@ -32,7 +33,7 @@ EXPORTS = [
     "pt_group_lasso_penalty_batched", "pt_lasso_set_coeff", "pt_compact_nhwc_batched",
     "pt_scatter_nhwc", "pt_group_maxabs", "pt_apply_zero", "pt_sgd_momentum_lasso_batched",
     "pt_zero_groups_batched", "pt_reconcile_plan_batched", "pt_compact_vector_batched", "pt_compact_weights_batched",
-    "pt_bn_workspace_bytes", "pt_bn_fwd", "pt_bn_bwd",
+    "pt_bn_workspace_bytes", "pt_bn_fwd", "pt_bn_bwd", "pt_plan_layer_removal",
 ]
 
 
@@ -91,6 +92,11 @@ class EdgePlan(C.Structure):
                 ("keep", C.c_void_p), ("idx", C.c_void_p), ("n_keep_dev", C.c_void_p)]
 
 
+class RemovalEdge(C.Structure):
+    _fields_ = [("producers", C.POINTER(C.c_int32)), ("consumers", C.POINTER(C.c_int32)), ("n_prod", C.c_int32),
+                ("n_cons", C.c_int32), ("n_keep", C.c_int32), ("external", C.c_int32)]
+
+
 class GatherVector(C.Structure):
     _fields_ = [("v", C.c_void_p), ("idx", C.c_void_p), ("out", C.c_void_p), ("n_keep", C.c_int32),
                 ("elem_bytes", C.c_int32)]
@@ -144,6 +150,7 @@ def lib() -> C.CDLL:
             "pt_reconcile_plan_batched": [C.POINTER(EdgePlan), i32, vp],
             "pt_compact_vector_batched": [C.POINTER(GatherVector), i32, vp],
             "pt_compact_weights_batched": [C.POINTER(GatherWeights), i32, vp],
+            "pt_plan_layer_removal": [C.POINTER(RemovalEdge), i32, i32, vp, vp],
             "pt_bn_workspace_bytes": [i64, i32, C.POINTER(sz)],
             "pt_bn_fwd": [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, sz, vp],
             "pt_bn_bwd": [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp],
@@ -431,3 +438,19 @@ def bn_bwd(x, dy, pixels: int, Cc: int, x_cpitch: int, dy_cpitch: int, gamma, me
     _ck("pt_bn_bwd", lib().pt_bn_bwd(_ptr(x), _ptr(dy), pixels, Cc, x_cpitch, dy_cpitch, _ptr(gamma), _ptr(mean),
                                      _ptr(invstd), _ptr(dx), dx_cpitch, _ptr(dgamma), _ptr(dbeta), p, n,
                                      _stream(stream)))
+
+
+def plan_layer_removal(edges: Sequence, n_layers: int):
+    """edges: (producers, consumers, n_keep, external) per edge, all host values.  Returns (removed_layers,
+    dead_edges, status) as lists of 0/1 and the call's status (PT_OK, or PT_ERR_EMPTY when the network is cut)."""
+    keep_alive = []
+    arr = (RemovalEdge * max(1, len(edges)))()
+    for i, (prod, cons, n_keep, external) in enumerate(edges):
+        p, c = (C.c_int32 * max(1, len(prod)))(*prod), (C.c_int32 * max(1, len(cons)))(*cons)
+        keep_alive += [p, c]
+        arr[i] = RemovalEdge(p, c, len(prod), len(cons), n_keep, external)
+    removed, dead = (C.c_uint8 * max(1, n_layers))(), (C.c_uint8 * max(1, len(edges)))()
+    rc = lib().pt_plan_layer_removal(arr, len(edges), n_layers, removed, dead)
+    if rc not in (PT_OK, -6):
+        raise PruneTrainError("pt_plan_layer_removal", rc)
+    return list(removed)[:n_layers], list(dead)[:len(edges)], rc
