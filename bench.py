@@ -298,7 +298,7 @@ def main():
                                f"(cfg3) + reconfiguration sweep at {int(args.sparsity * 100)}% zeroed groups (cfg5) + "
                                "train step at ragged pruned widths (cfg4)",
                    "lambda": LAMBDA, "threshold": THRESHOLD, "hip_graphs": use_graph,
-                   "wgrad_on_second_stream": not args.no_overlap},
+                   "wgrad_side_streams": 0 if args.no_overlap else hz.WGRAD_STREAMS},
         "roofline": roofline,
         "breakdown": {
             "wall_ms_per_step": round(wall_ms, 4),
