@@ -133,7 +133,12 @@ struct WgradPlan {
 };
 constexpr int kWgBM = 128, kWgBN = 128, kWgBK = 32;  // register-staged kernel
 constexpr int kWgDlBKP = 64;                          // direct kernel: pixels per reduction step
-constexpr int kWgTargetBlocks = 512;                  // workgroups per launch the split count aims at
+// Workgroups per launch the split count aims at (128x128 tiles: kWgTargetBlocksBig).  Well below the 512 resident
+// slots on purpose: weight gradients of different layers are independent and are meant to run side by side on
+// several streams, so one launch need not fill the chip, and every split costs a tile of fp32 partial sums written
+// and read again.  Measured on the ResNet-50 step with four side streams: 512/256 -> 245, 256/96 -> 264 TFLOP/s
+// (run one after the other on a single stream the same launches are ~25 % slower than with 512/256).
+constexpr int kWgTargetBlocks = 256, kWgTargetBlocksBig = 96;
 
 // 64-wide tiles when 128-wide ones would waste more than ~20 % of their rows
 inline int pick_tile(int n) {
@@ -165,11 +170,10 @@ inline WgradPlan plan_wgrad(const pt_conv_desc* d, bool dl) {
         p.tiles_n = (int)ceil_div(d->K, kWgBN);
         p.iters_total = (int)ceil_div(pixels, kWgBK);
     }
-    // One resident set of workgroups (2 per CU x 256 CUs): more would run as a second, partly empty round.
     // At least 4 reduction steps per workgroup.
     const int tiles = p.tiles_m * p.tiles_n;
     // 128x128 tiles run three stages deep (96 KiB of LDS: one workgroup per CU), the smaller tiles two per CU
-    const int target = (dl && p.BM == 128 && p.BN == 128) ? kWgTargetBlocks / 2 : kWgTargetBlocks;
+    const int target = (dl && p.BM == 128 && p.BN == 128) ? kWgTargetBlocksBig : kWgTargetBlocks;
     int64_t splits = target / tiles;
     const int64_t max_splits = p.iters_total / 4 > 0 ? p.iters_total / 4 : 1;
     if (splits > max_splits) splits = max_splits;
