@@ -230,37 +230,49 @@ def main():
                 for k in ("fwd", "bwd_data", "bwd_weight")} for tag, net in (("full", full), ("pruned", pruned))}
     params = {tag: sum(l.spec.params for l in net.layers) for tag, net in (("full", full), ("pruned", pruned))}
 
-    # dominant kernel family of the step = the conv family with the largest time over both widths
+    # dominant kernel of the step: k_igemm_dl serves conv_fwd and conv_bwd_data, k_wgrad_dl (+ k_wgrad_reduce)
+    # conv_bwd_weight; the one with the larger time over both widths is reported against its roof
+    nets = (full, pruned)
     tot = {k: fam["full"][k] + fam["pruned"][k] for k in ("fwd", "bwd_data", "bwd_weight")}
-    dom = max(tot, key=tot.get)
-    kernel_of = {"fwd": "k_igemm_dl (conv_fwd launches)", "bwd_data": "k_igemm_dl (conv_bwd_data launches)",
-                 "bwd_weight": "k_wgrad_dl + k_wgrad_reduce (conv_bwd_weight launches)"}
-    n_launch = sum(1 for net in (full, pruned) for l in net.layers if not (dom == "bwd_data" and l.dx is None))
-    dom_flops = fl["full"][dom] + fl["pruned"][dom]
-    dom_bytes = by["full"][dom] + by["pruned"][dom]
-    dom_s = tot[dom] * 1e-3
-    # which roof bounds this family on this workload: time at the HBM peak vs time at the bf16 MFMA peak
+    kernels = {"k_igemm_dl (conv_fwd + conv_bwd_data launches)": ("fwd", "bwd_data"),
+               "k_wgrad_dl + k_wgrad_reduce (conv_bwd_weight launches)": ("bwd_weight",)}
+    dom_kernel = max(kernels, key=lambda k: sum(tot[f] for f in kernels[k]))
+    fams = kernels[dom_kernel]
+
+    def has(l, f):
+        return not (f == "bwd_data" and l.dx is None)
+
+    def launches(l, f):  # the input gradient is one launch per stride-parity class that holds a filter tap
+        s = l.spec
+        return min(s.stride, s.R) * min(s.stride, s.S) if f == "bwd_data" else 1
+    n_launch = sum(launches(l, f) for f in fams for net in nets for l in net.layers if has(l, f))
+    dom_flops = sum(fl[t][f] for f in fams for t in ("full", "pruned"))
+    dom_bytes = sum(by[t][f] for f in fams for t in ("full", "pruned"))
+    dom_s = sum(tot[f] for f in fams) * 1e-3
+    # which roof bounds this kernel on this workload: time at the HBM peak vs time at the bf16 MFMA peak
     t_hbm, t_mfma = dom_bytes / (PEAK_HBM_GBS * 1e9), dom_flops / (PEAK_BF16_TFLOPS * 1e12)
     # per-layer roof: a layer cannot finish before max(its bytes at the HBM peak, its flops at the MFMA peak)
-    t_roof = sum(max(conv_bytes(l.spec, dom) / (PEAK_HBM_GBS * 1e9), l.spec.flops / (PEAK_BF16_TFLOPS * 1e12))
-                 for net in (full, pruned) for l in net.layers if not (dom == "bwd_data" and l.dx is None))
+    t_roof = sum(max(conv_bytes(l.spec, f) / (PEAK_HBM_GBS * 1e9), l.spec.flops / (PEAK_BF16_TFLOPS * 1e12))
+                 for f in fams for net in nets for l in net.layers if has(l, f))
     if t_hbm >= t_mfma:
         ach, peak, unit, bound = dom_bytes / dom_s / 1e9, PEAK_HBM_GBS, "GB/s", "hbm"
     else:
         ach, peak, unit, bound = dom_flops / dom_s / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s", "mfma"
-    roofline = {"bound": bound, "kernel": kernel_of[dom], "achieved": round(ach, 2), "peak": peak, "unit": unit,
+    roofline = {"bound": bound, "kernel": dom_kernel, "achieved": round(ach, 2), "peak": peak, "unit": unit,
                 "frac": round(ach / peak, 4), "traffic": None,
-                "avg_launch_ms": round(tot[dom] / n_launch, 5), "launches_per_step": n_launch,
+                "avg_launch_ms": round(dom_s * 1e3 / n_launch, 5), "launches_per_step": n_launch,
                 "bytes_per_launch": dom_bytes / n_launch, "flops_per_launch": dom_flops / n_launch,
                 "tflops": round(dom_flops / dom_s / 1e12, 2), "frac_mfma_peak": round(dom_flops / dom_s / 1e12 / PEAK_BF16_TFLOPS, 4),
                 "frac_of_per_layer_roof": round(t_roof / dom_s, 4)}
 
-    # HBM traffic of the dominant family, measured separately with hardware counters (this file is written from
+    # HBM traffic of the dominant kernel, measured separately with hardware counters (this file is written from
     # two `rocprofv3 --pmc` runs of this script; see its header for the commands and the scale factors)
     tpath = os.path.join(ROOT, "profiles", "bench_resnet50_b64_hbm_traffic.txt")
-    if dom == "bwd_weight" and os.path.exists(tpath):
+    if os.path.exists(tpath):
         import re
-        m = re.search(r"per pt_conv_bwd_weight call .*?= ([0-9.]+) MB of HBM traffic", open(tpath).read())
+        pat = (r"per k_igemm_dl launch .*?= ([0-9.]+) MB of HBM traffic" if "k_igemm_dl" in dom_kernel
+               else r"per pt_conv_bwd_weight call .*?= ([0-9.]+) MB of HBM traffic")
+        m = re.search(pat, open(tpath).read())
         if m:
             roofline["traffic"] = float(m.group(1)) * 1e6
             roofline["traffic_unit"] = "bytes per launch (FETCH_SIZE x 2.0 + WRITE_SIZE, from profiles/)"
