@@ -18,6 +18,7 @@ DEV = "cuda:0"
 # 4 streams 245 TFLOP/s (8 the same; odd counts fall back to ~230, the caller's stream then shares a hardware queue
 # with a busy side stream).
 WGRAD_STREAMS = 4
+NORMS_HEAD_LAYERS = 11  # group norms of this many leading layers precede the forward pass; the rest run beside it
 
 
 def pitch8(n: int) -> int:
@@ -149,10 +150,16 @@ class Network:
     def __init__(self, layers: Sequence[ConvLayer]):
         self.layers = list(layers)
         self.norm_jobs = (B.LayerWeights * len(self.layers))(*[l.norms_job() for l in self.layers])
+        # the same jobs in two batches: the forward pass may start once the first layers' bf16 weights exist
+        nj = [l.norms_job() for l in self.layers]
+        self.norm_head = min(NORMS_HEAD_LAYERS, len(nj))
+        self.norm_jobs_head = (B.LayerWeights * self.norm_head)(*nj[: self.norm_head])
+        self.norm_jobs_tail = (B.LayerWeights * (len(nj) - self.norm_head))(*nj[self.norm_head:]) if len(nj) > self.norm_head else None
         self.lasso_jobs = (B.LayerLasso * len(self.layers))(*[l.lasso_job() for l in self.layers])
         self.ws_norms = torch.empty(max(256, B.group_norms_batched_workspace_bytes(self.norm_jobs)), dtype=torch.uint8,
                                     device=DEV)
         self.ws = make_workspace(self.layers)
+        self.ws_norms_tail = torch.empty_like(self.ws_norms)
         crsk = [B.layer_crsk(l.w_bf16, l.w_crsk, l.spec.K, l.RS, l.spec.C, l.wp) for l in self.layers
                 if l.w_crsk is not None]
         self.crsk_jobs = (B.LayerCrsk * len(crsk))(*crsk) if crsk else None
@@ -176,11 +183,31 @@ class Network:
         they alternate between WGRAD_STREAMS side streams (each with its own split workspace): one layer's short
         reduction pass and the ramp-down of its main kernel overlap the next layer's main kernel.  All streams
         join before the regulariser's gradient."""
-        B.group_norms_batched(self.norm_jobs, self.ws_norms)
-        if self.crsk_jobs is not None:
-            B.weights_to_crsk_batched(self.crsk_jobs)
-        for l in self.layers:
-            l.fwd(self.ws)
+        if not self.overlap_wgrad:
+            B.group_norms_batched(self.norm_jobs, self.ws_norms)
+            if self.crsk_jobs is not None:
+                B.weights_to_crsk_batched(self.crsk_jobs)
+            for l in self.layers:
+                l.fwd(self.ws)
+        else:
+            # The forward pass needs layer l's bf16 weights only when it reaches layer l, and the k-innermost copies
+            # only in the backward pass: the first layers' norms run on the caller's stream, the remaining norms and
+            # the copies beside the first forward convolutions.
+            main, side = torch.cuda.current_stream(), self.sides[0]
+            side.wait_stream(main)
+            B.group_norms_batched(self.norm_jobs_head, self.ws_norms)
+            with torch.cuda.stream(side):
+                if self.norm_jobs_tail is not None:
+                    B.group_norms_batched(self.norm_jobs_tail, self.ws_norms_tail)
+                tail_ready = torch.cuda.Event()
+                tail_ready.record(side)
+                if self.crsk_jobs is not None:
+                    B.weights_to_crsk_batched(self.crsk_jobs)
+            for i, l in enumerate(self.layers):
+                if i == self.norm_head:
+                    main.wait_event(tail_ready)
+                l.fwd(self.ws)
+            main.wait_stream(side)                 # the k-innermost weight copies are final
         if not self.overlap_wgrad:
             for l in reversed(self.layers):
                 l.bwd_data_crsk()
