@@ -115,7 +115,7 @@ inline hipError_t launch_igemm(IgemmArgs& a, bool vec, hipStream_t st) {
     if (a.TR * a.TSm > 64) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, true>(a, st);
     // 128x128 tiles when they still fill the chip, else 128x64 tiles (more workgroups, deeper pipeline)
     const int64_t tiles128 = ceil_div(a.M, 128) * ceil_div(a.Nout, 128);
-    if (a.Nout <= 64 || tiles128 < 160) return launch_igemm_dl_cfg<128, 64, 4, 2, 3>(a, st);
+    if (a.Nout <= 64 || tiles128 < 256) return launch_igemm_dl_cfg<128, 64, 4, 2, 3>(a, st);
     return launch_igemm_dl_cfg<128, 128, 2, 4, 2>(a, st);
 }
 
@@ -214,7 +214,7 @@ inline hipError_t launch_wgrad(WgradArgs& a, const WgradPlan& p, bool vec, hipSt
         return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2>(a, st);
     }
     // wave grids and pipeline depths from measurements on ResNet-50 shapes
-    if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKP, 4, 2, 3>(a, st);
+    if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKP, 2, 2, 3, 2>(a, st);
     if (p.BM == 64 && p.BN == 128) return launch_wgrad_dl_cfg<64, 128, kWgDlBKP, 2, 2, 3, 2>(a, st);
     if (p.BM == 128 && p.BN == 64) return launch_wgrad_dl_cfg<128, 64, kWgDlBKP, 2, 2, 3, 2>(a, st);
     return launch_wgrad_dl_cfg<64, 64, kWgDlBKP, 2, 2, 4, 2>(a, st);
