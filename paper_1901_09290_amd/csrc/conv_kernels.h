@@ -416,7 +416,6 @@ __device__ __forceinline__ void barrier_nofence() {
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 }
-__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xc07f); }  // lgkmcnt(0) only
 
 // Per-lane choice between two global addresses, kept opaque so that it stays one load instruction.
 __device__ __forceinline__ glb_void_ptr pick_ptr(bool ok, const uint16_t* p, const uint16_t* z) {
@@ -436,7 +435,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED, bool TAIL = RAGGED>
 __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
-    constexpr int NW = WGM * WGN, NT = 64 * NW, BK = 64;
+    constexpr int NW = WGM * WGN, BK = 64;
     constexpr int GA = BM / 8, GB = BN / 8;    // 8-row groups = wave-level loads per stage
     constexpr int LA = GA / NW, LB = GB / NW;  // loads per lane per stage
     constexpr int LPT = LA + LB;
@@ -693,12 +692,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 }
 
 template <int BM, int BN, int WGM, int WGN, int STAGES>
-inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st, int force_ragged = -1) {
+inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
     constexpr int NT = 64 * WGM * WGN;
     constexpr size_t lds = (size_t)STAGES * (BM + BN) * 128;
     static_assert(lds <= 160 * 1024, "LDS capacity");
     // last channel block of a tap is short and/or some chunk has a masked tail
-    const bool ragged = force_ragged >= 0 ? force_ragged != 0 : ((a.Cred % 64) != 0 || (a.fold && a.Creal % 8 != 0));
+    const bool ragged = (a.Cred % 64) != 0 || (a.fold && a.Creal % 8 != 0);
     a.nk = a.TR * a.TS * (int)ceil_div(a.CredP, 64);  // steps are (tap, block of 64 channels)
     a.tiles_n = (int)ceil_div(a.Nout, BN);
     set_tail_tables(a);
