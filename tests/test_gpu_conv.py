@@ -150,3 +150,31 @@ def test_bwd_data_from_pretransposed_weights(case):
     o = other.float().cpu().numpy()
     assert np.array_equal(o[:, 0, :5], np.arange(35, dtype=np.float32).reshape(5, 7).T) and not o[:, 0, 5:].any()
     assert torch.equal(dx_a.view(torch.int16), dx_b.view(torch.int16))
+
+
+def _random_specs(n, seed):
+    """Seeded random small layers: arbitrary (pruned-looking) channel counts, filter sizes 1/3/5/7, strides 1-3."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    while len(out) < n:
+        R = int(rng.choice([1, 1, 3, 3, 5, 7]))
+        stride = int(rng.choice([1, 1, 2, 3]))
+        pad = int(rng.integers(0, R // 2 + 1))
+        H, W = int(rng.integers(max(R, 4), 24)), int(rng.integers(max(R, 4), 24))
+        C = int(rng.choice([rng.integers(1, 16), rng.integers(16, 80), rng.integers(80, 300)]))
+        K = int(rng.choice([rng.integers(1, 16), rng.integers(16, 80), rng.integers(80, 300)]))
+        N = int(rng.integers(1, 5))
+        if H + 2 * pad < R or W + 2 * pad < R:
+            continue
+        out.append((N, H, W, C, K, R, stride, pad))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_specs(36, 20260101), ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("pad_zero", [False, True])
+def test_random_ragged_layers(case, pad_zero):
+    """Arbitrary widths on 8-padded pitches, padding NaN (kernels clear the tails) or vouched zero."""
+    from gpu_util import pitch8
+    N, H, W, C, K, R, stride, pad = case
+    spec = _spec(N, H, W, C, K, R, stride, pad)
+    _check_full(spec, 500 + sum(case), pitch8(C), pitch8(K), pitch8(C), pad_zero=pad_zero)
