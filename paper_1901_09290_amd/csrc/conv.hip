@@ -193,10 +193,25 @@ extern "C" int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const u
 static int32_t bwd_data_classes(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* wt, uint16_t* dx,
                                 hipStream_t st) {
     int32_t rc = PT_OK;
+    // A filter no larger than the stride reaches only some stride-parity classes of input pixels.  When class
+    // (0, 0) is the only one with taps, its launch also clears the other classes (they tile into cells anchored at
+    // its pixels), which saves up to stride_h * stride_w - 1 small launches; this needs the vector store path and a
+    // channel count whose last 8-chunk may be written whole.
+    int with_taps = 0;
+    for (int ca = 0; ca < d->stride_h; ++ca)
+        for (int cb = 0; cb < d->stride_w; ++cb) {
+            const BwdClass c = bwd_data_class(d, ca, cb);
+            if (c.gH > 0 && c.gW > 0 && c.TR > 0 && c.TS > 0) ++with_taps;
+        }
+    const BwdClass c00 = bwd_data_class(d, 0, 0);
+    const bool vec_all = d->x_cpitch % 8 == 0 && d->y_cpitch % 8 == 0 && aligned16(dx) && aligned16(dy);
+    const bool fuse_zero = with_taps == 1 && c00.TR > 0 && c00.TS > 0 && d->stride_h * d->stride_w > 1 && vec_all &&
+                           (d->C % 8 == 0 || (d->flags & PT_CONV_PAD_ZERO)) && c00.TR * c00.TS <= 64;
     for (int ca = 0; ca < d->stride_h; ++ca) {
         for (int cb = 0; cb < d->stride_w; ++cb) {
             BwdClass c = bwd_data_class(d, ca, cb);
             if (c.gH == 0 || c.gW == 0) continue;
+            if (fuse_zero && (ca != 0 || cb != 0)) continue;  // cleared by the launch of class (0, 0)
             if (c.TR == 0 || c.TS == 0) {
                 const int64_t pixels = (int64_t)d->N * c.gH * c.gW;
                 const int64_t nblk = ceil_div(pixels * ceil_div(d->C, 8), 256);
@@ -207,6 +222,10 @@ static int32_t bwd_data_classes(const pt_conv_desc* d, const uint16_t* dy, const
                 rc = launch_status();
             } else {
                 IgemmArgs a = make_bwd_data_args(d, c, ca, cb, dy, wt, dx);
+                if (fuse_zero) {
+                    a.zf_h = d->stride_h;
+                    a.zf_w = d->stride_w;
+                }
                 rc = hip_status(launch_igemm(a, d->y_cpitch % 8 == 0 && aligned16(dy), st));
             }
             if (rc != PT_OK) return rc;

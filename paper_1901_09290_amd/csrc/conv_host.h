@@ -39,6 +39,7 @@ inline IgemmArgs make_fwd_args(const pt_conv_desc* d, const uint16_t* x, const u
     IgemmArgs a{};
     a.A = x; a.B = w; a.D = y;
     a.pad_zero = (d->flags & PT_CONV_PAD_ZERO) != 0;
+    a.zf_h = a.zf_w = 1;
     a.M = d->N * d->P * d->Q;
     a.gW = make_fastdiv((uint32_t)d->Q); a.gH = make_fastdiv((uint32_t)d->P);
     a.srcH = d->H; a.srcW = d->W; a.apitch = d->x_cpitch;
@@ -78,6 +79,7 @@ inline IgemmArgs make_bwd_data_args(const pt_conv_desc* d, const BwdClass& c, in
     IgemmArgs a{};
     a.A = dy; a.B = wt; a.D = dx;
     a.pad_zero = (d->flags & PT_CONV_PAD_ZERO) != 0;  // the k-innermost weight copy always has zero padding
+    a.zf_h = a.zf_w = 1;
     a.M = d->N * c.gH * c.gW;
     a.gW = make_fastdiv((uint32_t)c.gW); a.gH = make_fastdiv((uint32_t)c.gH);
     a.srcH = d->P; a.srcW = d->Q; a.apitch = d->y_cpitch;

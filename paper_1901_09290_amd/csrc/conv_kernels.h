@@ -154,6 +154,10 @@ struct IgemmArgs {
     uint64_t tail_lo, tail_hi;
     int tail_nvalid;  // defined elements of the tail chunk (1..7), 8 when there is none
     int pad_zero;     // the caller vouches that the padding channels of both operands hold zeros
+    // Input gradient of a strided layer whose only stride-parity class with filter taps is (0, 0): every destination
+    // pixel lies in the zf_h x zf_w cell anchored at one pixel of that class, and the launch clears the rest of each
+    // cell itself (1 x 1 = off).  Direct kernel, 16-byte stores only.
+    int zf_h, zf_w;
 };
 
 // Fills tail_lo / tail_hi / tail_nvalid (see IgemmArgs) for the direct kernel's 64-channel blocks.
@@ -648,13 +652,17 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
         for (int tm = 0; tm < TM; ++tm) {
             const int m = m0 + wm * WTM + tm * 32 + l32;
             int64_t dpix;
+            int cell_h = 1, cell_w = 1;  // pixels of this lane's cell inside the destination image
             if (a.d_linear) {
                 dpix = (int64_t)m * a.dpitch;
             } else {
                 const uint32_t mm = (uint32_t)min(m, a.M - 1);
                 const uint32_t row = fdiv(mm, a.gW), gj = mm - row * a.gW.d;
                 const uint32_t n = fdiv(row, a.gH), gi = row - n * a.gH.d;
-                dpix = (((int64_t)n * a.DH + (int)gi * a.d_hmul + a.d_hadd) * a.DW + (int)gj * a.d_wmul + a.d_wadd) * a.dpitch;
+                const int dh = (int)gi * a.d_hmul + a.d_hadd, dw = (int)gj * a.d_wmul + a.d_wadd;
+                dpix = (((int64_t)n * a.DH + dh) * a.DW + dw) * a.dpitch;
+                cell_h = min(a.zf_h, a.DH - dh);
+                cell_w = min(a.zf_w, a.DW - dw);
             }
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
@@ -670,6 +678,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
                     const int ch = chb + 16 * gp + 8 * hi;
                     if (m < a.M && ch < a.Nout) {
                         uint16_t* dst = a.D + dpix + ch;
+                        if (a.zf_h * a.zf_w > 1) {  // uniform: clear the other pixels of the cell (vector stores only)
+                            for (int zh = 0; zh < cell_h; ++zh)
+                                for (int zw = zh == 0 ? 1 : 0; zw < cell_w; ++zw)
+                                    *reinterpret_cast<uint4*>(dst + ((int64_t)zh * a.DW + zw) * a.dpitch) = make_uint4(0u, 0u, 0u, 0u);
+                        }
                         if (a.d_vec16 && ch + 7 < a.Nout) {
                             *reinterpret_cast<uint4*>(dst) = make_uint4(ps[0], qs[0], ps[1], qs[1]);
                         } else if (a.d_vec16 && a.pad_zero && ch + 8 <= a.dpitch) {
