@@ -220,6 +220,8 @@ def main():
             # not part of the timed step: the optimizer step with the regulariser folded in (lr = 0: weights unchanged)
             "optimizer_step_fused": timed(lambda: net.optimizer_step(LAMBDA, 0.0, 0.9, 1e-4), 5),
             # not part of the timed step either: feature normalisation of every convolution output, forward and backward
+            "fwd+bn": timed(lambda: net.fwd_bn_all(False), 3),
+            "fwd+bn_fused": timed(lambda: net.fwd_bn_all(True), 3),
             "bn_fwd": timed(net.bn_fwd_all, 3),
             "bn_bwd": timed(net.bn_bwd_all, 3),
         }
@@ -295,6 +297,8 @@ def main():
         to = fam[tag]["optimizer_step_fused"]
         out["optimizer_step_fused(not in step)"] = {"ms": round(to, 4), "GBps": round(20 * params[tag] / (to * 1e-3) / 1e9, 1),
                                                     "frac_hbm_peak": round(20 * params[tag] / (to * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        out["fwd+bn(not in step)"] = {"separate_ms": round(fam[tag]["fwd+bn"], 4),
+                                      "statistics_in_conv_epilogue_ms": round(fam[tag]["fwd+bn_fused"], 4)}
         for k, bpe in (("bn_fwd", 6), ("bn_bwd", 10)):
             t = fam[tag][k]
             out[k + "(not in step)"] = {"ms": round(t, 4), "GBps": round(bpe * net_of[tag].bn_elements / (t * 1e-3) / 1e9, 1),

@@ -334,6 +334,22 @@ int32_t pt_bn_bwd(const uint16_t* x, const uint16_t* dy, int64_t pixels, int32_t
                   int32_t dy_cpitch, const float* gamma, const float* mean, const float* invstd, uint16_t* dx,
                   int32_t dx_cpitch, float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream);
 
+/* Forward convolution that also reduces its output for the normalisation layer behind it (Sec. 2.1 notes that these
+ * layers read their input several times; this removes one of the reads).  Same y as pt_conv_fwd; in addition
+ * `sums` (device, fp32) receives, per tile of 128 output pixels, the per-channel sums of the STORED outputs (the
+ * bf16-rounded values) and of their squares: sums[(q * n_partial + t) * K + k], q = 0 / 1.  The workspace query
+ * returns the size of `sums` and n_partial.  pt_bn_fwd_from_sums then finishes the statistics (fp64, fixed order)
+ * and normalises: the results of pt_bn_fwd up to the summation order (the sums are taken about 0, not about a
+ * pivot, so a channel whose mean is large against its spread loses the digits it would lose in any one-pass
+ * variance).  PT_ERR_UNSUPPORTED when the layer does not take the direct kernel: pitches not multiples of 8 or bases
+ * not 16-byte aligned, more than 64 filter taps, or C not a multiple of 8 without PT_CONV_PAD_ZERO. */
+int32_t pt_conv_fwd_stats_workspace_bytes(const pt_conv_desc* d, size_t* bytes, int32_t* n_partial);
+int32_t pt_conv_fwd_stats(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, uint16_t* y, float* sums,
+                          size_t sums_bytes, void* stream);
+int32_t pt_bn_fwd_from_sums(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const float* sums,
+                            int32_t n_partial, const float* gamma, const float* beta, float eps, uint16_t* y,
+                            int32_t y_cpitch, float* mean, float* invstd, void* stream);
+
 /* ---- layer removal: Sec. 3.1 ("Layer Removal by Overlapping Regularization Groups") --------------------------- */
 
 /* HOST-only graph logic, no device work.  After a plan, an edge with no survivors (n_keep == 0) carries nothing: the

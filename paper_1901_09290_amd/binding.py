@@ -34,6 +34,7 @@ EXPORTS = [
     "pt_scatter_nhwc", "pt_group_maxabs", "pt_apply_zero", "pt_sgd_momentum_lasso_batched",
     "pt_zero_groups_batched", "pt_reconcile_plan_batched", "pt_compact_vector_batched", "pt_compact_weights_batched",
     "pt_bn_workspace_bytes", "pt_bn_fwd", "pt_bn_bwd", "pt_plan_layer_removal",
+    "pt_conv_fwd_stats_workspace_bytes", "pt_conv_fwd_stats", "pt_bn_fwd_from_sums",
 ]
 
 
@@ -151,6 +152,9 @@ def lib() -> C.CDLL:
             "pt_compact_vector_batched": [C.POINTER(GatherVector), i32, vp],
             "pt_compact_weights_batched": [C.POINTER(GatherWeights), i32, vp],
             "pt_plan_layer_removal": [C.POINTER(RemovalEdge), i32, i32, vp, vp],
+            "pt_conv_fwd_stats_workspace_bytes": [dp, C.POINTER(sz), C.POINTER(i32)],
+            "pt_conv_fwd_stats": [dp, vp, vp, vp, vp, sz, vp],
+            "pt_bn_fwd_from_sums": [vp, i64, i32, i32, vp, i32, vp, vp, f32, vp, i32, vp, vp, vp],
             "pt_bn_workspace_bytes": [i64, i32, C.POINTER(sz)],
             "pt_bn_fwd": [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, sz, vp],
             "pt_bn_bwd": [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp],
@@ -454,3 +458,22 @@ def plan_layer_removal(edges: Sequence, n_layers: int):
     if rc not in (PT_OK, -6):
         raise PruneTrainError("pt_plan_layer_removal", rc)
     return list(removed)[:n_layers], list(dead)[:len(edges)], rc
+
+
+def conv_fwd_stats_workspace(d: ConvDesc):
+    """-> (bytes of the sums buffer, number of partial rows per statistic)."""
+    n, k = C.c_size_t(0), C.c_int32(0)
+    _ck("pt_conv_fwd_stats_workspace_bytes", lib().pt_conv_fwd_stats_workspace_bytes(C.byref(d), C.byref(n), C.byref(k)))
+    return n.value, k.value
+
+
+def conv_fwd_stats(d: ConvDesc, x, w, y, sums, stream=None) -> None:
+    p, n = _ws(sums)
+    _ck("pt_conv_fwd_stats", lib().pt_conv_fwd_stats(C.byref(d), _ptr(x), _ptr(w), _ptr(y), p, n, _stream(stream)))
+
+
+def bn_fwd_from_sums(x, pixels: int, Cc: int, x_cpitch: int, sums, n_partial: int, gamma, beta, eps: float, y,
+                     y_cpitch: int, mean, invstd, stream=None) -> None:
+    _ck("pt_bn_fwd_from_sums", lib().pt_bn_fwd_from_sums(_ptr(x), pixels, Cc, x_cpitch, _ptr(sums), n_partial, _ptr(gamma),
+                                                         _ptr(beta), eps, _ptr(y), y_cpitch, _ptr(mean), _ptr(invstd),
+                                                         _stream(stream)))

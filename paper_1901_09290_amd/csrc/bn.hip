@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256) void k_bn_finish(const float* __restrict__ par
         s1 += red[1][i][cx];
     }
     if (MODE == 0) {
-        const double pivot = (double)__uint_as_float((uint32_t)x[c] << 16);
+        const double pivot = x ? (double)__uint_as_float((uint32_t)x[c] << 16) : 0.0;  // no x: plain sums
         const double m = s0 / (double)g.pixels;           // mean of (x - pivot)
         double var = s1 / (double)g.pixels - m * m;       // biased variance
         if (var < 0.0) var = 0.0;
@@ -307,5 +307,28 @@ extern "C" int32_t pt_bn_bwd(const uint16_t* x, const uint16_t* dy, int64_t pixe
     const unsigned grid = (unsigned)(passes < 256 * 8 ? passes : 256 * 8);
     hipLaunchKernelGGL(k_bn_apply<1>, dim3(grid), dim3(kBnThreads), 0, st, x, x_cpitch, dy, dy_cpitch, g, mean, invstd, dbeta,
                        dgamma, gamma, dx, dx_cpitch);
+    return launch_status();
+}
+
+// Normalisation whose statistics pass was done by the producing convolution (pt_conv_fwd_stats): finish + apply.
+extern "C" int32_t pt_bn_fwd_from_sums(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const float* sums,
+                                       int32_t n_partial, const float* gamma, const float* beta, float eps, uint16_t* y,
+                                       int32_t y_cpitch, float* mean, float* invstd, void* stream) {
+    int32_t rc = bn_check(pixels, C, x_cpitch, y_cpitch, x_cpitch);
+    if (rc != PT_OK) return rc;
+    if (!(eps >= 0.f) || n_partial <= 0) return PT_ERR_SHAPE;
+    if (!x || !sums || !gamma || !beta || !y || !mean || !invstd) return PT_ERR_NULL;
+    if (!al16(x) || !al16(y)) return PT_ERR_UNSUPPORTED;
+    BnGeom g = bn_geom(pixels, C);
+    g.nblocks = n_partial;  // rows of `sums` per statistic
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_bn_finish<0>, dim3((unsigned)ceil_div(C, 8)), dim3(256), 0, st, sums, (const uint16_t*)nullptr, g,
+                       eps, mean, invstd);
+    rc = launch_status();
+    if (rc != PT_OK) return rc;
+    const int64_t passes = ceil_div(pixels, g.ty);
+    const unsigned grid = (unsigned)(passes < 256 * 8 ? passes : 256 * 8);
+    hipLaunchKernelGGL(k_bn_apply<0>, dim3(grid), dim3(kBnThreads), 0, st, x, x_cpitch, (const uint16_t*)nullptr, 0, g, mean,
+                       invstd, beta, (const float*)nullptr, gamma, y, y_cpitch);
     return launch_status();
 }

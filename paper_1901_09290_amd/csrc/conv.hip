@@ -234,6 +234,38 @@ static int32_t bwd_data_classes(const pt_conv_desc* d, const uint16_t* dy, const
     return PT_OK;
 }
 
+// Forward convolution with the statistics epilogue: only the direct kernel has it.
+static int32_t fwd_stats_supported(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, const uint16_t* y) {
+    const bool vec = d->x_cpitch % 8 == 0 && d->w_cpitch % 8 == 0 && d->y_cpitch % 8 == 0 && aligned16(x) && aligned16(w) &&
+                     aligned16(y);
+    if (!vec || d->R * d->S > 64) return PT_ERR_UNSUPPORTED;
+    if (d->C % 8 != 0 && !(d->flags & PT_CONV_PAD_ZERO)) return PT_ERR_UNSUPPORTED;
+    return PT_OK;
+}
+
+extern "C" int32_t pt_conv_fwd_stats_workspace_bytes(const pt_conv_desc* d, size_t* bytes, int32_t* n_partial) {
+    const int32_t rc = check_desc(d);
+    if (rc != PT_OK) return rc;
+    if (!bytes || !n_partial) return PT_ERR_NULL;
+    *n_partial = (int32_t)ceil_div((int64_t)d->N * d->P * d->Q, 128);
+    *bytes = (size_t)round_up((int64_t)2 * *n_partial * d->K * 4, 256);
+    return PT_OK;
+}
+
+extern "C" int32_t pt_conv_fwd_stats(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, uint16_t* y, float* sums,
+                                     size_t sums_bytes, void* stream) {
+    int32_t rc = check_desc(d);
+    if (rc != PT_OK) return rc;
+    if (!x || !w || !y || !sums) return PT_ERR_NULL;
+    rc = fwd_stats_supported(d, x, w, y);
+    if (rc != PT_OK) return rc;
+    const int64_t n_partial = ceil_div((int64_t)d->N * d->P * d->Q, 128);
+    if (sums_bytes < (size_t)(2 * n_partial * d->K * 4)) return PT_ERR_WORKSPACE;
+    IgemmArgs a = make_fwd_args(d, x, w, y);
+    a.stats = sums;
+    return hip_status(launch_igemm(a, true, (hipStream_t)stream));
+}
+
 extern "C" int32_t pt_conv_bwd_data(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* w, uint16_t* dx,
                                     void* ws, size_t ws_bytes, void* stream) {
     int32_t rc = check_desc(d);

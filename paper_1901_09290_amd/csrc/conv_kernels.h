@@ -158,6 +158,11 @@ struct IgemmArgs {
     // pixel lies in the zf_h x zf_w cell anchored at one pixel of that class, and the launch clears the rest of each
     // cell itself (1 x 1 = off).  Direct kernel, 16-byte stores only.
     int zf_h, zf_w;
+    // STATS instantiations (forward only): per-channel sums of the stored (bf16-rounded) outputs and of their
+    // squares over the tile's valid pixels, one row per pixel tile: stats[(q * tiles_m + tile_m) * Nout + channel],
+    // q = 0 sums, q = 1 sums of squares - the layout the normalisation's finish pass reads.
+    float* stats;
+    int tiles_m;
 };
 
 // Fills tail_lo / tail_hi / tail_nvalid (see IgemmArgs) for the direct kernel's 64-channel blocks.
@@ -436,7 +441,8 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // TAIL = some run of channels ends inside an 8-chunk whose remaining elements are undefined.
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED, bool TAIL = RAGGED>
+// STATS = also reduce the stored outputs to per-channel sums and sums of squares (see IgemmArgs::stats).
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED, bool TAIL = RAGGED, bool STATS = false>
 __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int NW = WGM * WGN, BK = 64;
@@ -700,6 +706,61 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
             }
         }
     }
+    if constexpr (STATS) {
+        // Every lane holds 16 channel values per 32x32 block (channels 8g + 4*(lane/32) + i, v = 4g + i) of one
+        // pixel.  A halving butterfly over the 32 pixel lanes of each half-wave leaves lane l with the total of the
+        // one value v(l) = bits (16, 8, 4, 2) of l: 16 exchanges per block and statistic instead of 80.
+        float* red = reinterpret_cast<float*>(smem_b);  // [2][WGM][BN]; the stage buffers are dead after the barrier
+        __syncthreads();
+        const int hi = lane >> 5;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            float sv[16], qv[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sv[v] = 0.f, qv[v] = 0.f;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const bool valid = m0 + wm * WTM + tm * 32 + l32 < a.M;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    // the value as stored: rounded to bf16
+                    const float r = __uint_as_float(cvt_pk_bf16(acc[tn][tm][v], 0.f) << 16);
+                    const float rv = valid ? r : 0.f;
+                    sv[v] += rv;
+                    qv[v] += rv * rv;
+                }
+            }
+            static_for<0, 4>([&](auto step_c) {  // halves 8, 4, 2, 1 exchanged across lane bits 16, 8, 4, 2
+                constexpr int HALF = 8 >> decltype(step_c)::value, BIT = 16 >> decltype(step_c)::value;
+                const bool up = (l32 & BIT) != 0;
+                static_for<0, HALF>([&](auto i_c) {
+                    constexpr int I = decltype(i_c)::value;
+                    const float ss = up ? sv[I] : sv[I + HALF], sq = up ? qv[I] : qv[I + HALF];
+                    const float ks = up ? sv[I + HALF] : sv[I], kq = up ? qv[I + HALF] : qv[I];
+                    sv[I] = ks + __shfl_xor(ss, BIT, 64);
+                    qv[I] = kq + __shfl_xor(sq, BIT, 64);
+                });
+            });
+            sv[0] += __shfl_xor(sv[0], 1, 64);
+            qv[0] += __shfl_xor(qv[0], 1, 64);
+            if ((l32 & 1) == 0) {
+                const int v = ((l32 >> 4) & 1) * 8 + ((l32 >> 3) & 1) * 4 + ((l32 >> 2) & 1) * 2 + ((l32 >> 1) & 1);
+                const int chl = wn * WTN + tn * 32 + 8 * (v >> 2) + 4 * hi + (v & 3);
+                red[(0 * WGM + wm) * BN + chl] = sv[0];
+                red[(1 * WGM + wm) * BN + chl] = qv[0];
+            }
+        }
+        __syncthreads();
+        const int tile_m = m0 / BM;
+        for (int t = tid; t < 2 * BN; t += 64 * NW) {
+            const int q = t / BN, chl = t - q * BN;
+            if (n0 + chl >= a.Nout) continue;
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < WGM; ++w) tot += red[(q * WGM + w) * BN + chl];  // fixed order
+            a.stats[((size_t)q * a.tiles_m + tile_m) * a.Nout + n0 + chl] = tot;
+        }
+    }
     PT_STAMP(3);
 #endif
 }
@@ -716,23 +777,31 @@ inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
     set_tail_tables(a);
     // variant: 0 = whole 64-channel blocks, 1 = partial blocks but no undefined elements (channel count a multiple
     // of 8, or the caller vouches for zero padding), 2 = partial blocks with tails to clear
-    const int variant = !ragged ? 0 : ((a.tail_lo | a.tail_hi) == 0 || a.pad_zero ? 1 : 2);
-    const void* kern = variant == 0   ? reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false>)
-                       : variant == 1 ? reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false>)
-                                      : reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true>);
-    static bool attr_set[3] = {false, false, false};  // one-time opt-in to more than 64 KiB of dynamic LDS
+    int variant = !ragged ? 0 : ((a.tail_lo | a.tail_hi) == 0 || a.pad_zero ? 1 : 2);
+    if (a.stats) {  // statistics epilogue: variants 3, 4 = variants 0, 1 with it (the caller has ruled out tails)
+        if (variant == 2) return hipErrorInvalidValue;
+        variant += 3;
+        a.tiles_m = (int)ceil_div(a.M, BM);
+    }
+    const void* kerns[5] = {reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false>),
+                            reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false>),
+                            reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true>),
+                            reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, true>),
+                            reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, true>)};
+    static bool attr_set[5] = {false, false, false, false, false};  // one-time opt-in to more than 64 KiB of dynamic LDS
     if (lds > 65536 && !attr_set[variant]) {
-        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(kerns[variant], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set[variant] = true;
     }
     const dim3 grid((unsigned)(ceil_div(a.M, BM) * a.tiles_n)), block(NT);
-    if (variant == 0)
-        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false>), grid, block, lds, st, a);
-    else if (variant == 1)
-        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false>), grid, block, lds, st, a);
-    else
-        hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true>), grid, block, lds, st, a);
+    switch (variant) {
+        case 0: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false>), grid, block, lds, st, a); break;
+        case 1: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false>), grid, block, lds, st, a); break;
+        case 2: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true>), grid, block, lds, st, a); break;
+        case 3: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, true>), grid, block, lds, st, a); break;
+        default: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, true>), grid, block, lds, st, a); break;
+    }
     return hipSuccess;
 }
 

@@ -272,6 +272,25 @@ class Network:
             B.bn_bwd(l.y, l.dy, s.N * s.P * s.Q, s.K, l.yp, l.yp, st["gamma"], ms[0], ms[1], st["out"], l.yp,
                      st["grad"][0], st["grad"][1], st["ws"])
 
+    def fwd_bn_all(self, fused: bool, eps: float = 1e-5) -> None:
+        """Every layer's forward convolution followed by the normalisation of its output: as two separate calls
+        (three passes over the activation), or with the statistics reduced in the convolution's epilogue (two)."""
+        st = self._bn_state()
+        if "sums" not in st:
+            sizes = [B.conv_fwd_stats_workspace(l.desc) for l in self.layers]
+            st["sums"] = torch.empty(max(n for n, _ in sizes), dtype=torch.uint8, device=DEV)
+            st["n_partial"] = [k for _, k in sizes]
+        for l, ms, npart in zip(self.layers, st["stat"], st["n_partial"]):
+            s = l.spec
+            pixels = s.N * s.P * s.Q
+            if fused:
+                B.conv_fwd_stats(l.desc, l.x, l.w_bf16, l.y, st["sums"])
+                B.bn_fwd_from_sums(l.y, pixels, s.K, l.yp, st["sums"], npart, st["gamma"], st["beta"], eps, st["out"], l.yp,
+                                   ms[0], ms[1])
+            else:
+                l.fwd(self.ws)
+                B.bn_fwd(l.y, pixels, s.K, l.yp, st["gamma"], st["beta"], eps, st["out"], l.yp, ms[0], ms[1], st["ws"])
+
     @property
     def bn_elements(self) -> int:
         return sum(l.spec.N * l.spec.P * l.spec.Q * l.spec.K for l in self.layers)

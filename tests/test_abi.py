@@ -214,3 +214,28 @@ def test_feature_normalisation_validates_on_the_host(lib):
     assert bwd(a1=None) == -1 and bwd(a12=None) == -1
     assert bwd(a5=32) == -2 and bwd(a10=72 + 4) == -4 and bwd(a14=0) == -3
     assert bwd(a3=4096, a4=4096, a5=4096, a10=4096) == -4
+
+
+def test_fused_statistics_calls_validate_on_the_host(lib):
+    import ctypes as C
+    fake = 256
+    d = B.conv_desc(4, 16, 16, 16, 24, 3, 3, 1, 1)
+    n, k = C.c_size_t(0), C.c_int32(0)
+    assert lib.pt_conv_fwd_stats_workspace_bytes(C.byref(d), C.byref(n), C.byref(k)) == 0
+    assert k.value == 8 and n.value >= 2 * 8 * 24 * 4
+    assert lib.pt_conv_fwd_stats_workspace_bytes(C.byref(d), None, C.byref(k)) == -1
+    assert lib.pt_conv_fwd_stats(C.byref(d), fake, fake, fake, None, 1 << 20, None) == -1
+    assert lib.pt_conv_fwd_stats(C.byref(d), fake, fake, fake, fake, 16, None) == -3
+    odd = B.conv_desc(4, 16, 16, 13, 24, 3, 3, 1, 1, x_cpitch=16, w_cpitch=16)        # C % 8 != 0, padding not vouched for
+    assert lib.pt_conv_fwd_stats(C.byref(odd), fake, fake, fake, fake, 1 << 20, None) == -4
+    dense = B.conv_desc(4, 16, 16, 13, 24, 3, 3, 1, 1)                                  # pitch 13: element-wise path
+    assert lib.pt_conv_fwd_stats(C.byref(dense), fake, fake, fake, fake, 1 << 20, None) == -4
+    ok = (fake, 1000, 60, 64, fake, 8, fake, fake, 1e-5, fake, 64, fake, fake, None)
+
+    def f(**kw):
+        a = list(ok)
+        for key, v in kw.items():
+            a[int(key[1:])] = v
+        return lib.pt_bn_fwd_from_sums(*a)
+    assert f(a4=None) == -1 and f(a0=None) == -1
+    assert f(a5=0) == -2 and f(a3=56) == -2 and f(a3=68) == -4 and f(a2=4096, a3=4096, a10=4096) == -4

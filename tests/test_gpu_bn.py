@@ -112,3 +112,65 @@ def test_bn_is_run_to_run_identical_and_full_size():
         outs.append([t.clone() for t in (y.view(torch.int16), dx.view(torch.int16), mean, invstd, dgamma, dbeta)])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+FUSED = [
+    # N  H   W   C    K   R st pad
+    (2, 12, 12, 64, 64, 3, 1, 1),
+    (3, 9, 11, 24, 40, 3, 1, 1),
+    (2, 14, 14, 128, 96, 1, 1, 0),
+    (2, 15, 15, 40, 136, 3, 2, 1),
+    (2, 30, 30, 3, 28, 7, 2, 3),       # image-like input, zero padding vouched for
+    (2, 13, 13, 45, 38, 3, 1, 1),      # ragged both ways
+    (4, 28, 28, 128, 128, 3, 1, 1),    # several pixel tiles, two wave rows per tile
+    (1, 1, 1, 8, 8, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("case", FUSED, ids=lambda c: "x".join(map(str, c)))
+def test_conv_with_statistics_epilogue_feeds_the_normalisation(case):
+    """pt_conv_fwd_stats + pt_bn_fwd_from_sums against the oracle's convolution, rounded to bf16 as stored, followed
+    by the oracle's normalisation; and against the unfused GPU path (same y bit for bit, statistics to 1e-5)."""
+    from gpu_util import CONV_TOL, DEV, dev_bf16, empty_bf16, host_bf16, pitch8, rel_err, workspace
+    N, H, W, C, K, R, st, pad = case
+    spec = wl.ConvSpec("t", N, H, W, C, K, R, R, st, pad, None, None)
+    t = wl.conv_tensors(spec, np.random.Generator(np.random.PCG64(900 + sum(case))), want=("x", "w"))
+    xp, yp = pitch8(C), pitch8(K)
+    d = B.desc_of(spec, xp, yp, xp, B.CONV_PAD_ZERO)
+    xd, wd = dev_bf16(t["x"], xp, 0), dev_bf16(t["w"], xp, 0)
+    pixels = N * spec.P * spec.Q
+    rng = np.random.Generator(np.random.PCG64(7))
+    gamma = (1.0 + 0.2 * rng.standard_normal(K)).astype(np.float32)
+    beta = (0.1 * rng.standard_normal(K)).astype(np.float32)
+    gd, bd = torch.from_numpy(gamma).to(DEV), torch.from_numpy(beta).to(DEV)
+
+    nbytes, n_partial = B.conv_fwd_stats_workspace(d)
+    assert n_partial == (pixels + 127) // 128
+    sums = workspace(nbytes)
+    sums.fill_(0xFF)
+    y = empty_bf16((N, spec.P, spec.Q, yp), fill=0)
+    z = empty_bf16((pixels, yp), fill=0x7FC0)
+    mean, invstd = (torch.full((K,), float("nan"), device=DEV) for _ in range(2))
+    B.conv_fwd_stats(d, xd, wd, y, sums)
+    B.bn_fwd_from_sums(y, pixels, K, yp, sums, n_partial, gd, bd, EPS, z, yp, mean, invstd)
+    # unfused path on the same inputs
+    y2 = empty_bf16((N, spec.P, spec.Q, yp), fill=0)
+    z2 = empty_bf16((pixels, yp), fill=0x7FC0)
+    mean2, invstd2 = (torch.full((K,), float("nan"), device=DEV) for _ in range(2))
+    B.conv_fwd(d, xd, wd, y2)
+    ws = workspace(B.bn_workspace_bytes(pixels, K))
+    B.bn_fwd(y2, pixels, K, yp, gd, bd, EPS, z2, yp, mean2, invstd2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+    assert rel_err(mean.cpu().numpy(), mean2.cpu().numpy()) <= 1e-5
+    assert rel_err(invstd.cpu().numpy(), invstd2.cpu().numpy()) <= 1e-5
+
+    ry = oracle.conv_fwd(oracle.shape_of(spec), t["x"], t["w"])
+    assert rel_err(host_bf16(y, K), ry) <= CONV_TOL
+    ry_stored = wl.to_bf16_grid(ry.astype(np.float32)).astype(np.float64).reshape(pixels, K)
+    rz, rmean, rinv = oracle.bn_fwd(ry_stored, gamma, beta, EPS)
+    # the two sides round a few outputs to neighbouring bf16 values: the statistics agree to that (derived: one bf16
+    # step on a fraction of elements moves a mean by << 1e-3 of the channel's spread)
+    assert rel_err(mean.cpu().numpy(), rmean) <= 1e-3
+    assert rel_err(invstd.cpu().numpy(), rinv) <= 1e-3
+    assert rel_err(host_bf16(z, K), rz) <= CONV_TOL
