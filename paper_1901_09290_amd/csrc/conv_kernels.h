@@ -409,9 +409,9 @@ inline hipError_t launch_igemm_cfg(IgemmArgs& a, hipStream_t st) {
 // chunks of a row are XOR-swizzled with ((row >> 1) & 7) so that the MFMA operand reads (16 consecutive
 // rows, same logical chunk) fall into 16 different bank groups.  The swizzle is applied on the global
 // side: the lane that owns physical chunk p of a row fetches logical chunk p ^ swz(row).
-// Taps outside the image and chunks past the channel count fetch from a 16-byte zero page; a ragged
-// channel tail inside a chunk is zeroed in LDS by the lane that loaded it, after its data has landed
-// and before the workgroup barrier.  RAGGED = the channel count is not a multiple of 64.
+// Taps outside the image and chunks past the channel count fetch from a 16-byte zero page.  RAGGED = the channel
+// count is not a multiple of 64 (the last block of a run is partly zero page); TAIL = in addition some 8-chunk
+// ends in undefined padding elements, which are cleared in registers before the MFMAs (see the kernel).
 __device__ __attribute__((aligned(16))) uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
@@ -464,8 +464,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
     const int m0 = (tile / a.tiles_n) * BM;
 
     // A reduction step is (filter tap, block of 64 reduction channels): the same for every lane, so the
-    // tap offsets and the channel base live in scalar registers.  With a ragged channel count the last
-    // block of each tap is short: only ceil(rest/16) MFMA k-steps are executed for it.
+    // tap offsets and the channel base live in scalar registers.
     const int lrow = lane >> 3;                                      // row inside an 8-row group
     const int kv = (lane & 7) ^ ((((wave & 1) << 2) | (lane >> 4)));  // logical 8-element chunk this lane fetches
     const int kvoff = kv * 8;
