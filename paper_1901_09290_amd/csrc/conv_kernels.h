@@ -51,28 +51,8 @@ __device__ __forceinline__ uint4 mask8(uint4 v, bool ok, const Mask8& k) {
     return v;
 }
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-// the same mask applied to an 8-element MFMA operand fragment held in registers
-template <typename F>
-__device__ __forceinline__ F mask_frag(F v, const Mask8& k) {
-    static_assert(sizeof(F) == 16, "fragment of eight 16-bit elements");
-    u32x4 u = __builtin_bit_cast(u32x4, v);
-    u[0] &= k.m[0];
-    u[1] &= k.m[1];
-    u[2] &= k.m[2];
-    u[3] &= k.m[3];
-    return __builtin_bit_cast(F, u);
-}
-
 // LDS reads issued as inline assembly are ordered only by explicit waits: the compiler neither moves them nor
 // adds waits of its own.  The result registers must not be touched before lds_wait() has been applied to them.
-template <int OFF>
-__device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) {
-    static_assert(OFF >= 0 && OFF < 65536, "DS offset field");
-    u32x4 v;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
-    return v;
-}
 // Waits until at most N of this wave's LDS reads are outstanding (they return in order) and makes `first`
 // depend on the wait; lds_tie() extends the dependence to further registers.
 template <int N, typename V>
@@ -148,11 +128,11 @@ struct IgemmArgs {
     int tiles_n;
     int d_vec;    // 8-byte stores allowed (pitch % 4 == 0, base 8-byte aligned)
     int d_vec16;  // 16-byte stores allowed (pitch % 8 == 0, base 16-byte aligned)
-    // Direct kernel, channel counts that are not multiples of 8: which operand fragments hold the 8-chunk with the
-    // undefined tail.  Bit (block * 4 + sub-step) for folded runs (block = 64-channel block of the run), bit
-    // (sub-step) of the last block otherwise; _lo for lanes 0..31 (even chunks), _hi for lanes 32..63.
-    uint64_t tail_lo, tail_hi;
-    int tail_nvalid;  // defined elements of the tail chunk (1..7), 8 when there is none
+    // Direct kernel, channel counts that are not multiples of 8: which of the eight 16-byte chunks of a 64-channel block
+    // end in undefined padding elements.  Byte b of tail_kv = chunk bits of block b of a folded run; otherwise byte 0
+    // describes the last block of a tap (the only one with a tail) and byte 7 is zero.
+    uint64_t tail_kv;
+    int tail_nvalid;  // defined elements of a tail chunk (1..7), 8 when there is none
     int pad_zero;     // the caller vouches that the padding channels of both operands hold zeros
     // Input gradient of a strided layer whose only stride-parity class with filter taps is (0, 0): every destination
     // pixel lies in the zf_h x zf_w cell anchored at one pixel of that class, and the launch clears the rest of each
@@ -165,22 +145,22 @@ struct IgemmArgs {
     int tiles_m;
 };
 
-// Fills tail_lo / tail_hi / tail_nvalid (see IgemmArgs) for the direct kernel's 64-channel blocks.
+// Fills tail_kv / tail_nvalid (see IgemmArgs) for the direct kernel's 64-channel blocks.
 inline void set_tail_tables(IgemmArgs& a) {
-    a.tail_lo = a.tail_hi = 0;
+    a.tail_kv = 0;
     a.tail_nvalid = 8;
     const int creal = a.fold ? a.Creal : a.Cred;
     if ((creal & 7) == 0) return;
     a.tail_nvalid = creal & 7;
-    const int tail_chunk = creal >> 3;                              // chunk index of the tail inside one run
-    const int nblk = a.fold ? (a.CredP + 63) >> 6 : 1;              // folded: every block; else the last block only
-    const int base = a.fold ? 0 : ((a.CredP - 1) >> 6) << 3;        // first chunk of the last block
-    const int per = a.fold ? (int)(a.Cfold.d >> 3) : 0x7fffffff;    // chunks per run
-    for (int i = 0; i < nblk * 4; ++i) {                            // i = block * 4 + sub-step: chunks 2i, 2i + 1
-        const int c0 = base + 2 * i, c1 = c0 + 1;
-        if ((a.fold ? c0 % per : c0) == tail_chunk) a.tail_lo |= 1ull << i;
-        if ((a.fold ? c1 % per : c1) == tail_chunk) a.tail_hi |= 1ull << i;
+    const int tail_chunk = creal >> 3;  // chunk index of the tail inside one run
+    if (!a.fold) {
+        a.tail_kv = 1ull << (tail_chunk & 7);  // in the last block of the tap
+        return;
     }
+    const int per = (int)(a.Cfold.d >> 3);  // chunks per run
+    const int nblk = (a.CredP + 63) >> 6;   // <= 7
+    for (int c = 0; c < nblk * 8; ++c)
+        if (c % per == tail_chunk) a.tail_kv |= 1ull << c;
 }
 
 // VEC: every operand row is 16-byte aligned (pitches are multiples of 8 elements).
@@ -535,13 +515,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
     const int l32 = lane & 31;
     const int swz = (l32 >> 1) & 7;  // all operand rows of this lane are l32 (mod 32)
     const int kc0 = lane >> 5;
-    // A channel count that is not a multiple of 8 leaves undefined elements (memory padding) at the end of the last
-    // 8-chunk of every run of channels.  Those elements are cleared in registers, in both operands, before they reach
-    // the matrix pipe.  Which (block, sub-step) fragments hold such a chunk is fixed per kernel: one bit each, for this
-    // lane (tail_mine) and for any lane of the wave (tail_any, uniform); the host fills the tables (set_tail_tables).
-    const uint64_t tail_any = a.tail_lo | a.tail_hi;
-    const uint64_t tail_mine = kc0 ? a.tail_hi : a.tail_lo;
-    const Mask8 tail_mask = make_mask8(TAIL ? a.tail_nvalid : 8);
     f32x16 acc[TN][TM];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
@@ -567,60 +540,62 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
         const uint8_t* sA = smem_b + stage * STAGE_BYTES;
         const uint8_t* sB = sA + BM * 128;
         // One stage = BK/16 sub-steps of (fragment reads, MFMAs); all sub-steps always run (chunks past the channel
-        // count were fetched from the zero page).  MASKED: the fragments of this stage that hold a tail chunk are
-        // cleared first.  The body is free of branches either way: a branch per sub-step costs the compiler's
-        // schedule far more than the masking does.
-        auto body = [&](auto masked_tag, int bit0) {
-            constexpr bool MASKED = decltype(masked_tag)::value;
-            Mask8 km[BK / 16];
-            if constexpr (MASKED) {
+        // count were fetched from the zero page) and the body has no branches: a branch per sub-step costs the
+        // compiler's schedule far more than the work it would skip.
+        bf16x8 fw[2][TN], fp[2][TM];
+        auto read_frags = [&](int ks, int b) {
+            const int pc = (((ks * 2 + kc0) ^ swz) << 4);
 #pragma unroll
-                for (int ks = 0; ks < BK / 16; ++ks) {
-                    const bool mine = (tail_mine >> (bit0 + ks)) & 1;
+            for (int tn = 0; tn < TN; ++tn)
+                fw[b][tn] = *reinterpret_cast<const bf16x8*>(sB + (wn * WTN + tn * 32 + l32) * 128 + pc);
 #pragma unroll
-                    for (int w = 0; w < 4; ++w) km[ks].m[w] = mine ? tail_mask.m[w] : 0xffffffffu;
-                }
-            }
-            bf16x8 fw[2][TN], fp[2][TM];
-            auto read_frags = [&](int ks, int b) {
-                const int pc = (((ks * 2 + kc0) ^ swz) << 4);
+            for (int tm = 0; tm < TM; ++tm)
+                fp[b][tm] = *reinterpret_cast<const bf16x8*>(sA + (wm * WTM + tm * 32 + l32) * 128 + pc);
+        };
+        read_frags(0, 0);
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    fw[b][tn] = *reinterpret_cast<const bf16x8*>(sB + (wn * WTN + tn * 32 + l32) * 128 + pc);
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
-                    fp[b][tm] = *reinterpret_cast<const bf16x8*>(sA + (wm * WTM + tm * 32 + l32) * 128 + pc);
-            };
-            read_frags(0, 0);
-#pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
-                if constexpr (MASKED) {
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) fw[ks & 1][tn] = mask_frag(fw[ks & 1][tn], km[ks]);
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) fp[ks & 1][tm] = mask_frag(fp[ks & 1][tm], km[ks]);
-                }
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
-                        if (!CHECK || (n_live[tn] && m_live[tm]))
-                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][tn], fp[ks & 1][tm],
-                                                                                  acc[tn][tm], 0, 0, 0);
-            }
-        };
-        if constexpr (TAIL) {
-            // bits of this stage's sub-steps in tail_any / tail_mine: folded runs index by (64-channel block,
-            // sub-step); otherwise only the last block of a tap has a tail
-            const int bit0 = a.fold ? (c_cb >> 6) * 4 : (c_cb + BK > a.Cred ? 0 : 32);
-            if ((tail_any >> bit0) & 15) body(std::true_type{}, bit0);  // wave-uniform
-            else body(std::false_type{}, 0);
-        } else {
-            body(std::false_type{}, 0);
+                    if (!CHECK || (n_live[tn] && m_live[tm]))
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][tn], fp[ks & 1][tm], acc[tn][tm],
+                                                                              0, 0, 0);
         }
         c_cb += BK;
         if (c_cb >= a.CredP) c_cb = 0;
+    };
+
+    // TAIL: a channel count that is not a multiple of 8 leaves undefined elements (memory padding) at the end of the
+    // last 8-chunk of every run of channels, in both operands.  The lane that fetched such a chunk overwrites them
+    // with zeros in LDS once its loads have landed (writes only: nothing is read back) and before the barrier that
+    // publishes the stage.  Which chunks of the current block have a tail comes from a table in the arguments.
+    auto clear_tails = [&](int stage) {
+        asm volatile("" ::: "memory");  // keep the stores below behind the wait for the landed loads
+        const int slot = a.fold ? (c_cb >> 6) : (c_cb + BK > a.Cred ? 0 : 7);
+        const uint32_t bits = (uint32_t)(a.tail_kv >> (slot * 8)) & 0xffu;
+        if (bits == 0) return;  // wave-uniform
+        if ((bits >> kv) & 1u) {
+            const int n = a.tail_nvalid;  // uniform, 1..7: bytes [2n, 16) of the chunk are cleared with <= 3 stores
+            uint8_t* mine = smem_b + stage * STAGE_BYTES + wave * 1024 + lane * 16;
+#pragma unroll
+            for (int j = 0; j < LA + LB; ++j) {
+                uint8_t* p = mine + (j < LA ? NW * j * 1024 : BM * 128 + NW * (j - LA) * 1024);
+                int e = n;
+                if (e & 1) {
+                    *reinterpret_cast<uint16_t*>(p + 2 * e) = 0;
+                    ++e;
+                }
+                if (e & 2) {
+                    *reinterpret_cast<uint32_t*>(p + 2 * e) = 0u;
+                    e += 2;
+                }
+                if (e == 4) *reinterpret_cast<uint64_t*>(p + 8) = 0ull;
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the clears are in LDS before the barrier
     };
 
     const int nk = a.nk;
@@ -633,6 +608,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
                     // loads of steps kt+1 .. kt+STAGES-2 may stay in flight; near the end just drain
                     if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * LPT>();
                     else wait_vmcnt<0>();
+                    if constexpr (TAIL) clear_tails(s);
                     barrier_nofence();  // stage s complete for every wave; stage (s-1) free again
                     if (kt + STAGES - 1 < nk) issue((s + STAGES - 1) % STAGES);
                     compute(s, check_tag);
@@ -776,7 +752,7 @@ inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
     set_tail_tables(a);
     // variant: 0 = whole 64-channel blocks, 1 = partial blocks but no undefined elements (channel count a multiple
     // of 8, or the caller vouches for zero padding), 2 = partial blocks with tails to clear
-    int variant = !ragged ? 0 : ((a.tail_lo | a.tail_hi) == 0 || a.pad_zero ? 1 : 2);
+    int variant = !ragged ? 0 : (a.tail_kv == 0 || a.pad_zero ? 1 : 2);
     if (a.stats) {  // statistics epilogue: variants 3, 4 = variants 0, 1 with it (the caller has ruled out tails)
         if (variant == 2) return hipErrorInvalidValue;
         variant += 3;
