@@ -276,7 +276,10 @@ typedef struct pt_gather_weights {
 } pt_gather_weights;
 int32_t pt_compact_weights_batched(const pt_gather_weights* jobs, int32_t n_jobs, void* stream);
 
-/* out[pix][c'] = x[pix][idx[c']] for bf16 NHWC activations with `pixels` = N*H*W rows. */
+/* out[pix][c'] = x[pix][idx[c']] for bf16 NHWC activations with `pixels` = N*H*W rows.  Padding channels of out:
+ * those from Cp up to the next multiple of 8 (as far as they lie inside out_cpitch) are written as zero, so that
+ * rows are written whole and a convolution reading the result may be given PT_CONV_PAD_ZERO when out_cpitch is Cp
+ * rounded up to 8; channels beyond that multiple of 8 are left untouched. */
 int32_t pt_compact_nhwc(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch, const int32_t* idx,
                         int32_t Cp, uint16_t* out, int32_t out_cpitch, void* stream);
 

@@ -90,7 +90,8 @@ __global__ void k_compact_vector(const T* __restrict__ v, const int* __restrict_
 }
 
 // Activation gather along the innermost axis, element-wise form (any pitch / alignment): one thread
-// produces 8 consecutive output channels of one pixel.
+// produces 8 consecutive output channels of one pixel.  Padding channels of the last group of eight that lie
+// inside the row are written as zero (rows are then written without holes wherever the pitch allows it).
 __global__ void k_compact_nhwc(const uint16_t* __restrict__ x, int64_t pixels, int x_cpitch,
                                const int* __restrict__ idx, int Cp, uint16_t* __restrict__ out, int out_cpitch,
                                int vec_ok) {
@@ -104,7 +105,7 @@ __global__ void k_compact_nhwc(const uint16_t* __restrict__ x, int64_t pixels, i
     uint16_t v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (c0 + e < Cp) ? src[idx[c0 + e]] : (uint16_t)0;
-    if (vec_ok && c0 + 7 < Cp) {
+    if (vec_ok) {  // pitch a multiple of 8: the whole group lies inside the row
         uint4 o;
         o.x = v[0] | ((uint32_t)v[1] << 16);
         o.y = v[2] | ((uint32_t)v[3] << 16);
@@ -114,7 +115,7 @@ __global__ void k_compact_nhwc(const uint16_t* __restrict__ x, int64_t pixels, i
     } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            if (c0 + e < Cp) dst[e] = v[e];
+            if (c0 + e < out_cpitch) dst[e] = v[e];
     }
 }
 
@@ -122,7 +123,9 @@ __global__ void k_compact_nhwc(const uint16_t* __restrict__ x, int64_t pixels, i
 // pixel rows through two LDS buffers with direct global->LDS loads (every source byte is read once, fully
 // coalesced, and the next run is in flight while the current one is gathered); every thread keeps its eight
 // channel indices in registers, assembles 8 output channels of a pixel from LDS with eight 16-bit reads and
-// writes one 16-byte store.  Channels of the last vector past Cp are not written.
+// writes one 16-byte store.  Channels of the last vector past Cp are written as zero: rows without holes keep
+// the memory system from merging partial lines (measured: stores of ragged rows with holes ran at half the
+// rate of whole rows).
 constexpr int kGatherThreads = 256;
 constexpr int kGatherChunk = 32 * 1024;                           // bytes of pixel rows per LDS buffer
 constexpr int kGatherLoads = kGatherChunk / (kGatherThreads * 16);  // 16-byte loads per thread and run (8)
@@ -181,7 +184,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const Gathe
     };
 
     // gather-side state of the current tensor
-    int cur = -1, ppb = 1, pp = 0, v = 0, nlast = 0, row_bytes = 0;
+    int cur = -1, ppb = 1, pp = 0, v = 0, row_bytes = 0;
+    uint32_t m0 = 0, m1 = 0, m2 = 0, m3 = 0;   // which halves of the four output words hold channels < Cp
     bool active = false;
     uint32_t id2[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // byte offset of each source channel inside a pixel row
 
@@ -210,7 +214,9 @@ __global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const Gathe
             active = pp < ppb;
 #pragma unroll
             for (int e = 0; e < 8; ++e) id2[e] = (active && v * 8 + e < J.Cp) ? 2u * (uint32_t)J.idx[v * 8 + e] : 0u;
-            nlast = J.Cp - v * 8;                // valid channels of this thread's vector (>= 8: all)
+            const int nlast = J.Cp - v * 8;      // valid channels of this thread's vector (>= 8: all)
+            auto halves = [&](int k) { return (k < nlast ? 0xFFFFu : 0u) | (k + 1 < nlast ? 0xFFFF0000u : 0u); };
+            m0 = halves(0); m1 = halves(2); m2 = halves(4); m3 = halves(6);
             row_bytes = J.x_cpitch * 2;
         }
         const int64_t p0 = (int64_t)(g - J.chunk0) * J.ppc;
@@ -224,15 +230,10 @@ __global__ __launch_bounds__(kGatherThreads) void k_compact_nhwc_lds(const Gathe
                 for (int k = 0; k < 8; ++k) asm volatile("ds_read_u16 %0, %1" : "=v"(e[k]) : "v"(r + id2[k]));
                 asm volatile("s_waitcnt lgkmcnt(0)"
                              : "+v"(e[0]), "+v"(e[1]), "+v"(e[2]), "+v"(e[3]), "+v"(e[4]), "+v"(e[5]), "+v"(e[6]), "+v"(e[7]));
-                const uint32_t o0 = e[0] | (e[1] << 16), o1 = e[2] | (e[3] << 16);
-                const uint32_t o2 = e[4] | (e[5] << 16), o3 = e[6] | (e[7] << 16);
+                const uint32_t o0 = (e[0] | (e[1] << 16)) & m0, o1 = (e[2] | (e[3] << 16)) & m1;
+                const uint32_t o2 = (e[4] | (e[5] << 16)) & m2, o3 = (e[6] | (e[7] << 16)) & m3;
                 uint16_t* dst = J.out + (p0 + p) * (int64_t)J.out_cpitch + v * 8;
-                if (nlast >= 8) {
-                    *reinterpret_cast<uint4*>(dst) = make_uint4(o0, o1, o2, o3);
-                } else {
-                    const uint32_t w[4] = {o0, o1, o2, o3};
-                    for (int k = 0; k < nlast; ++k) dst[k] = (uint16_t)(w[k >> 1] >> ((k & 1) * 16));
-                }
+                *reinterpret_cast<uint4*>(dst) = make_uint4(o0, o1, o2, o3);
             }
         }
         asm volatile("" ::: "memory");

@@ -256,15 +256,19 @@ def test_compact_vector_bit_exact():
     B.compact_vector(idd, 4, idd, 0, idd)  # empty gather is a no-op
 
 
-@pytest.mark.parametrize("pixels,C,pad", [(4 * 16 * 16, 16, False), (3 * 7 * 7, 203, True), (1000, 64, True),
-                                          (129, 811, True), (50, 5, False), (1, 8, False)])
+@pytest.mark.parametrize("pixels,C,pad", [(4 * 16 * 16, 16, 0), (3 * 7 * 7, 203, 8), (1000, 64, 8),
+                                          (129, 811, 8), (50, 5, 0), (1, 8, 0), (77, 45, 24), (1000, 209, 16),
+                                          (33, 21, 3), (9, 30, 13)])
 def test_compact_nhwc_bit_exact(pixels, C, pad):
+    """pad: 0 = dense rows; 8 = pitches rounded up to 8; 16 / 24 = output pitch with whole spare vectors behind the
+    last one; other values = output pitch Cp + pad (rows neither aligned nor a multiple of 8).  Padding channels up
+    to the next multiple of 8 are written as zero, the rest of the row is left alone."""
     from gpu_util import DEV, pitch8
     rng = np.random.Generator(np.random.PCG64(pixels + C))
     x = rng.integers(0, 65536, size=(pixels, C)).astype(np.uint16)
     idx = np.sort(rng.choice(C, max(1, int(C * 0.6)), replace=False)).astype(np.int32)
-    xp = pitch8(C) if pad else C
-    op = pitch8(idx.size) if pad else idx.size
+    xp = pitch8(C) if pad % 8 == 0 and pad else C
+    op = idx.size if pad == 0 else (pitch8(idx.size) + pad - 8 if pad % 8 == 0 else idx.size + pad)
     xfull = np.full((pixels, xp), 0xDEAD, dtype=np.uint16)
     xfull[:, :C] = x
     xd = torch.from_numpy(xfull.view(np.int16)).to(DEV).view(torch.bfloat16)
@@ -274,7 +278,9 @@ def test_compact_nhwc_bit_exact(pixels, C, pad):
     torch.cuda.synchronize()
     got = out.view(torch.int16).cpu().numpy().view(np.uint16)
     assert np.array_equal(got[:, : idx.size], oracle.compact_nhwc(x, idx))
-    assert np.all(got[:, idx.size:] == 0x1234)
+    zero_to = min(op, (idx.size + 7) // 8 * 8)
+    assert np.all(got[:, idx.size:zero_to] == 0)
+    assert np.all(got[:, zero_to:] == 0x1234)
 
 
 def test_cfg1_reconfiguration_end_to_end():
