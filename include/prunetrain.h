@@ -320,7 +320,9 @@ int32_t pt_apply_zero(float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpit
  *   mean[c] = sum_p x[p][c] / pixels,  var[c] = sum_p (x[p][c] - mean[c])^2 / pixels  (biased),
  *   invstd[c] = 1 / sqrt(var[c] + eps),  y[p][c] = bf16((x[p][c] - mean[c]) * invstd[c] * gamma[c] + beta[c]).
  * x, y: device, rows of x_cpitch / y_cpitch elements, both multiples of 8 and >= C, 16-byte aligned bases; channels
- * >= C of a row are never read into a result nor written.  gamma, beta: device fp32 [C] (inputs); mean, invstd:
+ * >= C of a row are never read into a result.  Of y's padding, the channels from C up to the next multiple of 8 are
+ * written as zero (rows go out as whole 16-byte vectors, and a convolution reading y may be given
+ * PT_CONV_PAD_ZERO when y_cpitch is C rounded up to 8); channels beyond are left untouched.  gamma, beta: device fp32 [C] (inputs); mean, invstd:
  * device fp32 [C] (outputs, kept by the caller for pt_bn_bwd).  ws: device scratch of pt_bn_workspace_bytes().
  * Statistics are combined in fp64 in a fixed order: run-to-run identical.  Three launches on `stream`.
  * Limits: C <= 2048, pixels < 2^31 (else PT_ERR_UNSUPPORTED; so are pitches that are not multiples of 8). */
@@ -332,7 +334,8 @@ int32_t pt_bn_fwd(const uint16_t* x, int64_t pixels, int32_t C, int32_t x_cpitch
 /* Backward of pt_bn_fwd given dy (bf16, same shape, pitch dy_cpitch) and the forward's mean / invstd:
  *   xhat = (x - mean) * invstd,  dbeta[c] = sum_p dy[p][c],  dgamma[c] = sum_p dy[p][c] * xhat[p][c],
  *   dx[p][c] = bf16(gamma[c] * invstd[c] * (dy[p][c] - dbeta[c]/pixels - xhat[p][c] * dgamma[c]/pixels)).
- * dgamma, dbeta: device fp32 [C] outputs.  Same layout rules, limits and workspace as pt_bn_fwd. */
+ * dgamma, dbeta: device fp32 [C] outputs.  Same layout rules (dx's padding like y's), limits and workspace as
+ * pt_bn_fwd. */
 int32_t pt_bn_bwd(const uint16_t* x, const uint16_t* dy, int64_t pixels, int32_t C, int32_t x_cpitch,
                   int32_t dy_cpitch, const float* gamma, const float* mean, const float* invstd, uint16_t* dx,
                   int32_t dx_cpitch, float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream);

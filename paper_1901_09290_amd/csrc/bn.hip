@@ -206,7 +206,11 @@ __global__ __launch_bounds__(kBnThreads) void k_bn_apply(const uint16_t* __restr
             k1[e] = invstd[c] * (p1[c] * invM);
         }
     }
+    // Padding channels of the last vector go out as zero: whole rows are written, never partial ones (a hole in
+    // every row costs the memory system a merge of partial lines and halves the store rate).
     const int nlast = g.C - tx * 8;  // valid channels of this thread's vector (>= 8: all)
+    auto halves = [&](int k) { return (k < nlast ? 0xFFFFu : 0u) | (k + 1 < nlast ? 0xFFFF0000u : 0u); };
+    const uint32_t m0 = halves(0), m1 = halves(2), m2 = halves(4), m3 = halves(6);
     const int64_t stride = (int64_t)gridDim.x * g.ty;
     // last pixels first: the reduction pass before this one ended there, so they are the likeliest to still sit
     // in the chip's caches
@@ -224,17 +228,11 @@ __global__ __launch_bounds__(kBnThreads) void k_bn_apply(const uint16_t* __restr
             for (int e = 0; e < 8; ++e) o[e] = sc[e] * (gv[e] - k0[e] - (xv[e] - mu[e]) * k1[e]);
         }
         uint4 pk;
-        pk.x = cvt_pk_bf16(o[0], o[1]);
-        pk.y = cvt_pk_bf16(o[2], o[3]);
-        pk.z = cvt_pk_bf16(o[4], o[5]);
-        pk.w = cvt_pk_bf16(o[6], o[7]);
-        uint16_t* dst = out + r * opitch + tx * 8;
-        if (nlast >= 8) {
-            *reinterpret_cast<uint4*>(dst) = pk;
-        } else {
-            const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
-            for (int k = 0; k < nlast; ++k) dst[k] = (uint16_t)(w[k >> 1] >> ((k & 1) * 16));
-        }
+        pk.x = cvt_pk_bf16(o[0], o[1]) & m0;
+        pk.y = cvt_pk_bf16(o[2], o[3]) & m1;
+        pk.z = cvt_pk_bf16(o[4], o[5]) & m2;
+        pk.w = cvt_pk_bf16(o[6], o[7]) & m3;
+        *reinterpret_cast<uint4*>(out + r * opitch + tx * 8) = pk;
     }
 }
 
