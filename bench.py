@@ -11,8 +11,8 @@ One *step* = one pass of the whole hot path over one batch of synthetic input:
   (3) training step at pruned width - the same 53 layers at ragged widths (keep fractions U[0.4,0.9]).
 `value` = convolution FLOPs of (1)+(3) divided by the time of the whole step, inputs resident in HBM.
 The launch sequences are captured once into HIP graphs and replayed (the survivor counts the sweep
-reads back are checked on every step).  Prints ONE JSON line on stdout; --detail writes per-layer
-tables under gpurun_out/.
+reads back are checked on every step).  Prints ONE JSON line on stdout; --detail FILE also writes
+per-layer tables to FILE.
 """
 from __future__ import annotations
 
@@ -83,7 +83,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--sparsity", type=float, default=0.3, help="fraction of each edge zeroed in the sweep")
-    ap.add_argument("--detail", action="store_true", help="write per-layer tables under gpurun_out/")
+    ap.add_argument("--detail", metavar="FILE", default=None, help="also write per-layer tables to FILE")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep the weight gradients on the same stream as the input-gradient chain")
@@ -344,8 +344,8 @@ def main():
 
     if args.detail:
         calls = ("fwd", "bwd_data", "bwd_weight")
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_detail.txt"), "w") as f:
+        os.makedirs(os.path.dirname(os.path.abspath(args.detail)), exist_ok=True)
+        with open(args.detail, "w") as f:
             for tag, net in (("full", full), ("pruned", pruned)):
                 f.write(f"== {tag} ==  per call, eager (includes launch latency): us, TFLOP/s, algorithmic GB/s\n")
                 for l in net.layers:
