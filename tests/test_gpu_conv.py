@@ -103,6 +103,26 @@ def test_ragged_channel_counts_with_zero_padding_vouched(case):
     _check_full(spec, 400 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=True)
 
 
+MANY_TILES = [
+    # launches with more tiles than the chip holds workgroups at once (650 - 770 pixel tiles, all whole), in both
+    # pipeline depths of the direct kernel and with one, two, four and nine reduction steps per tile
+    ((5, 128, 130, 64, 64, 1, 1, 0), False),    # one step per tile, three stages; input gradient alike
+    ((5, 128, 130, 64, 128, 1, 1, 0), False),   # one step per tile, two stages; input gradient: two steps
+    ((5, 128, 130, 128, 128, 1, 1, 0), False),  # two steps per tile, two stages, both directions
+    ((7, 128, 100, 24, 64, 1, 1, 0), False),    # partial 64-channel block
+    ((5, 128, 130, 64, 64, 3, 1, 1), False),    # nine steps per tile, image borders
+    ((17, 128, 160, 64, 64, 2, 2, 0), False),   # strided: four input-gradient classes, scattered destination pixels
+    ((6, 256, 256, 3, 64, 7, 2, 3), True),      # image-like input, filter rows folded, zero padding vouched for
+]
+
+
+@pytest.mark.parametrize("case,pad_zero", MANY_TILES, ids=lambda c: "x".join(map(str, c)) if isinstance(c, tuple) else str(c))
+def test_many_whole_tiles(case, pad_zero):
+    from gpu_util import pitch8
+    spec = _spec(*case)
+    _check_full(spec, 600 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=pad_zero)
+
+
 def test_results_are_run_to_run_identical():
     from gpu_util import run_conv_all
     spec = _spec(4, 14, 14, 72, 104, 3, 1, 1)
