@@ -117,6 +117,8 @@ inline hipError_t launch_igemm(IgemmArgs& a, bool vec, hipStream_t st) {
     if (a.TR * a.TSm > 64) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, true>(a, st);
     // 128x128 tiles when they still fill the chip, else 128x64 tiles (more workgroups, deeper pipeline)
     const int64_t tiles128 = ceil_div(a.M, 128) * ceil_div(a.Nout, 128);
+    // very many pixel tiles and a narrow output (the stem): tall tiles, so half as many workgroups pay set-up and fill
+    if (a.Nout <= 64 && tiles128 >= 4096 && !a.stats) return launch_igemm_dl_cfg<256, 64, 4, 2, 2>(a, st);
     if (a.Nout <= 64 || tiles128 < 256) return launch_igemm_dl_cfg<128, 64, 4, 2, 3>(a, st);
     return launch_igemm_dl_cfg<128, 128, 2, 4, 2>(a, st);
 }

@@ -123,6 +123,16 @@ def test_many_whole_tiles(case, pad_zero):
     _check_full(spec, 600 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=pad_zero)
 
 
+@pytest.mark.parametrize("case", [(8, 256, 256, 8, 16, 1, 1, 0), (2, 515, 511, 5, 24, 3, 1, 1), (3, 420, 420, 16, 64, 1, 1, 0)],
+                         ids=lambda c: "x".join(map(str, c)))
+def test_narrow_outputs_over_very_many_pixels(case):
+    """More than half a million output pixels with at most 64 output channels: the forward launch takes 256-pixel tiles
+    (whole and ragged pixel counts, plain / folded / partial-block reductions)."""
+    from gpu_util import pitch8
+    spec = _spec(*case)
+    _check_full(spec, 700 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=True)
+
+
 def test_results_are_run_to_run_identical():
     from gpu_util import run_conv_all
     spec = _spec(4, 14, 14, 72, 104, 3, 1, 1)
