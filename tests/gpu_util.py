@@ -29,6 +29,18 @@ def rel_err(got, ref) -> float:
     return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
 
 
+def strict_rel_err(got, ref) -> float:
+    """Plain element-wise relative error max |g - r| / |r| over the elements that are not cancellation zeros
+    (|r| > 0.1 rms(r)); reported beside rel_err."""
+    got = np.asarray(got, dtype=np.float64).reshape(-1)
+    ref = np.asarray(ref, dtype=np.float64).reshape(-1)
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    sel = np.abs(ref) > 0.1 * rms
+    if rms == 0.0 or not sel.any():
+        return 0.0
+    return float(np.max(np.abs(got[sel] - ref[sel]) / np.abs(ref[sel])))
+
+
 def dev_bf16(a: np.ndarray, pitch=None, pad=0x7FC0) -> torch.Tensor:
     """fp32 values on the bf16 grid -> device bf16 tensor; optional innermost pitch (padding = NaN so
     that any use of padding as data poisons the result, unless `pad` says otherwise)."""
