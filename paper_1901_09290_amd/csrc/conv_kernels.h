@@ -620,8 +620,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < nk) issue(s);
     PT_STAMP(1);
+    // waves inside the reduction loop go first at the CU's issue arbiter: ahead of a co-resident workgroup's set-up
+    // or stores, and ahead of weight-gradient waves sharing the CU from another stream (+0.4 % on the step)
+    __builtin_amdgcn_s_setprio(2);
     if (all_live) main_loop(std::false_type{});
     else main_loop(std::true_type{});
+    __builtin_amdgcn_s_setprio(0);
     PT_STAMP(2);
 
     // ---- epilogue: registers -> global.  A lane holds, per 32x32 block, channels 8g + 4*(lane/32) + {0..3}
