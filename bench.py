@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep the weight gradients on the same stream as the input-gradient chain")
+    ap.add_argument("--no-fused-lasso", action="store_true",
+                    help="add the regulariser's gradient in a pass of its own after the weight gradients")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB): the "
@@ -113,6 +115,7 @@ def main():
     full = hz.Network(hz.build_network(full_specs, seed=2))
     pruned = hz.Network(hz.build_network(pruned_specs, seed=3))
     full.overlap_wgrad = pruned.overlap_wgrad = not args.no_overlap
+    full.fuse_lasso = pruned.fuse_lasso = not args.no_fused_lasso
     rng = np.random.Generator(np.random.PCG64(10 + int(round(args.sparsity * 10))))
     zero_sets = wl.zeroed_channel_sets(pruned_edges, args.sparsity, rng)
     rweights = wl.network_weights(pruned_specs, pruned_edges, zero_sets, rng)
@@ -314,7 +317,8 @@ def main():
                                f"(cfg3) + reconfiguration sweep at {int(args.sparsity * 100)}% zeroed groups (cfg5) + "
                                "train step at ragged pruned widths (cfg4)",
                    "lambda": LAMBDA, "threshold": THRESHOLD, "hip_graphs": use_graph,
-                   "wgrad_side_streams": 0 if args.no_overlap else hz.WGRAD_STREAMS},
+                   "wgrad_side_streams": 0 if args.no_overlap else hz.WGRAD_STREAMS,
+                   "lasso_in_wgrad_reduce": bool(full.fuse_lasso and full.overlap_wgrad)},
         "roofline": roofline,
         "breakdown": {
             "wall_ms_per_step": round(wall_ms, 4),

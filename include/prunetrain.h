@@ -137,6 +137,16 @@ int32_t pt_group_lasso_grad(const float* w, const float* out_norm, const float* 
                             uint32_t flags, float* dw, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch,
                             void* stream);
 
+/* Weight gradient with the regulariser's gradient folded in (Eq. 4 followed by the dW update of Alg. 1's GroupLassoReg
+ * step): dw = pt_conv_bwd_weight's result + what pt_group_lasso_grad would add, written once - the pass that combines
+ * the split partial sums adds the term, so dw is not written, read and rewritten.  w: the layer's fp32 master weights
+ * [K][RS][w_cpitch]; out_norm [K], in_norm [C] as written by pt_group_norms for the same w; flags as above.  The
+ * workspace is that of pt_conv_bwd_weight or one dw-sized slab, whichever is larger. */
+int32_t pt_conv_bwd_weight_lasso_workspace_bytes(const pt_conv_desc* d, size_t* bytes);
+int32_t pt_conv_bwd_weight_lasso(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, const float* w,
+                                 const float* out_norm, const float* in_norm, float lambda, uint32_t flags, float* dw,
+                                 void* ws, size_t ws_bytes, void* stream);
+
 /* Multi-layer forms: the regulariser of Eq. 2 runs over every layer of the network each iteration and a
  * layer's weights are small, so all layers go into a few launches (32 layers per launch).  `layers`
  * is a HOST array of n descriptors whose pointers are device pointers; per layer the semantics,

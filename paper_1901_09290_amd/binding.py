@@ -35,6 +35,7 @@ EXPORTS = [
     "pt_zero_groups_batched", "pt_reconcile_plan_batched", "pt_compact_vector_batched", "pt_compact_weights_batched",
     "pt_bn_workspace_bytes", "pt_bn_fwd", "pt_bn_bwd", "pt_plan_layer_removal",
     "pt_conv_fwd_stats_workspace_bytes", "pt_conv_fwd_stats", "pt_bn_fwd_from_sums",
+    "pt_conv_bwd_weight_lasso_workspace_bytes", "pt_conv_bwd_weight_lasso",
 ]
 
 
@@ -126,6 +127,8 @@ def lib() -> C.CDLL:
             "pt_conv_fwd": [dp, vp, vp, vp, vp, sz, vp],
             "pt_conv_bwd_data": [dp, vp, vp, vp, vp, sz, vp],
             "pt_conv_bwd_weight": [dp, vp, vp, vp, vp, sz, vp],
+            "pt_conv_bwd_weight_lasso_workspace_bytes": [dp, C.POINTER(sz)],
+            "pt_conv_bwd_weight_lasso": [dp, vp, vp, vp, vp, vp, f32, u32, vp, vp, sz, vp],
             "pt_group_norms_workspace_bytes": [i32, i32, i32, C.POINTER(sz)],
             "pt_group_norms": [vp, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
             "pt_group_lasso_grad": [vp, vp, vp, f32, u32, vp, i32, i32, i32, i32, vp],
@@ -234,6 +237,17 @@ def conv_bwd_weight(d: ConvDesc, x, dy, dw, ws=None, stream=None) -> None:
     p, n = _ws(ws)
     _ck("pt_conv_bwd_weight",
         lib().pt_conv_bwd_weight(C.byref(d), _ptr(x), _ptr(dy), _ptr(dw), p, n, _stream(stream)))
+
+
+def conv_bwd_weight_lasso_workspace_bytes(d: ConvDesc) -> int:
+    return _ws_bytes("pt_conv_bwd_weight_lasso_workspace_bytes", d)
+
+
+def conv_bwd_weight_lasso(d: ConvDesc, x, dy, w, out_norm, in_norm, lam: float, flags: int, dw, ws=None, stream=None) -> None:
+    p, n = _ws(ws)
+    _ck("pt_conv_bwd_weight_lasso",
+        lib().pt_conv_bwd_weight_lasso(C.byref(d), _ptr(x), _ptr(dy), _ptr(w), _ptr(out_norm), _ptr(in_norm), lam, flags,
+                                       _ptr(dw), p, n, _stream(stream)))
 
 
 def group_norms_workspace_bytes(K: int, RS: int, Cc: int) -> int:

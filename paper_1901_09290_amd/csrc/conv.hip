@@ -106,10 +106,20 @@ __global__ void k_zero_class(uint16_t* __restrict__ D, int64_t pixels, int gH, i
 // dw[k][tap][c] = sum over splits of partial[split][k][tap*CP + c], in a fixed order: a workgroup owns
 // 64 consecutive outputs; wavefront v adds the splits v, v+8, v+16, ... (four loads in flight), and the
 // eight wavefront sums are added in ascending order.  Results do not depend on timing.
+// LASSO: the gradient of the group-lasso penalty (Eq. 1-2) is added on the way out, with the arithmetic of
+// k_group_lasso_grad: dw = sum + lambda * (w * (1/out_norm[k] + 1/in_norm[c])), a zero norm contributing 0.
 constexpr int kReduceWaves = 8;
+struct ReduceLasso {
+    const float* w;         // [K][RS][wpitch], the pitch of dw
+    const float* out_norm;  // [K]
+    const float* in_norm;   // [C]
+    float lambda;
+    uint32_t flags;         // PT_LASSO_OUT | PT_LASSO_IN
+};
+template <bool LASSO>
 __global__ __launch_bounds__(64 * kReduceWaves) void k_wgrad_reduce(const float* __restrict__ part, int splits, int K,
                                                                      int RS, int C, int CP, int wpitch,
-                                                                     float* __restrict__ dw) {
+                                                                     float* __restrict__ dw, const ReduceLasso rl) {
     __shared__ float red[kReduceWaves][64];
     const int Mtot = RS * CP;
     const int64_t total = (int64_t)K * Mtot;
@@ -135,7 +145,16 @@ __global__ __launch_bounds__(64 * kReduceWaves) void k_wgrad_reduce(const float*
         const int64_t k = t / Mtot;
         const int mrow = (int)(t - k * Mtot);
         const int tp = mrow / CP, c = mrow - tp * CP;
-        if (c < C) dw[(k * RS + tp) * wpitch + c] = s;
+        if (c < C) {
+            const int64_t o = (k * RS + tp) * wpitch + c;
+            if constexpr (LASSO) {
+                const float on = (rl.flags & PT_LASSO_OUT) ? rl.out_norm[k] : 0.f;
+                const float in = (rl.flags & PT_LASSO_IN) ? rl.in_norm[c] : 0.f;
+                const float inv_out = on > 0.f ? 1.0f / on : 0.f, inv_in = in > 0.f ? 1.0f / in : 0.f;
+                s += rl.lambda * (rl.w[o] * (inv_out + inv_in));
+            }
+            dw[o] = s;
+        }
     }
 }
 
@@ -332,28 +351,68 @@ extern "C" int32_t pt_weights_to_crsk_batched(const pt_layer_crsk* layers, int32
     return flush();
 }
 
-extern "C" int32_t pt_conv_bwd_weight(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, float* dw, void* ws,
-                                      size_t ws_bytes, void* stream) {
+// rl == nullptr: plain weight gradient.  Otherwise the regulariser's gradient is added where dw is written: in the
+// reduction pass of a split launch, in the epilogue of an unsplit launch of the direct kernel, and for an unsplit
+// launch of the register-staged kernel in a reduction pass over one slab of partial sums.
+static int32_t bwd_weight_impl(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, float* dw, void* ws,
+                               size_t ws_bytes, void* stream, const ReduceLasso* rl) {
     int32_t rc = check_desc(d);
     if (rc != PT_OK) return rc;
     if (!x || !dy || !dw) return PT_ERR_NULL;
     // the direct kernel needs 16-byte aligned rows; it keeps one tile row block per filter tap
     const bool vec = d->x_cpitch % 8 == 0 && d->y_cpitch % 8 == 0 && aligned16(x) && aligned16(dy);
     const WgradPlan p = plan_wgrad(d, vec);
-    if (p.ws_bytes > 0 && !ws) return PT_ERR_NULL;
-    if (ws_bytes < p.ws_bytes) return PT_ERR_WORKSPACE;
-    if (p.ws_bytes > 0 && !aligned16(ws)) return PT_ERR_SHAPE;
+    const size_t need = rl ? wgrad_lasso_ws_of(d, p) : p.ws_bytes;
+    if (need > 0 && !ws) return PT_ERR_NULL;
+    if (ws_bytes < need) return PT_ERR_WORKSPACE;
+    if (need > 0 && !aligned16(ws)) return PT_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
     WgradArgs a = make_wgrad_args(d, p, x, dy, dw, ws);
+    if (rl && a.direct && p.dl) {  // the direct kernel's own epilogue adds the term
+        a.lw = rl->w;
+        a.l_on = (rl->flags & PT_LASSO_OUT) ? rl->out_norm : nullptr;
+        a.l_in = (rl->flags & PT_LASSO_IN) ? rl->in_norm : nullptr;
+        a.l_lambda = rl->lambda;
+    } else if (rl) {               // the reduction pass adds it (one slab when the launch is not split)
+        a.direct = 0;
+        a.OUT = (float*)ws;
+    }
     rc = hip_status(launch_wgrad(a, p, vec, st));
     if (rc != PT_OK) return rc;
     if (!a.direct) {
         const int64_t work = (int64_t)d->K * p.Mtot;
         const int64_t nblk = ceil_div(work, 64);
         if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)nblk), dim3(64 * kReduceWaves), 0, st, (const float*)ws, p.splits,
-                           d->K, a.RS, d->C, p.CP, d->w_cpitch, dw);
+        if (rl)
+            hipLaunchKernelGGL(k_wgrad_reduce<true>, dim3((unsigned)nblk), dim3(64 * kReduceWaves), 0, st, (const float*)ws,
+                               p.splits, d->K, a.RS, d->C, p.CP, d->w_cpitch, dw, *rl);
+        else
+            hipLaunchKernelGGL(k_wgrad_reduce<false>, dim3((unsigned)nblk), dim3(64 * kReduceWaves), 0, st, (const float*)ws,
+                               p.splits, d->K, a.RS, d->C, p.CP, d->w_cpitch, dw, ReduceLasso{});
         rc = launch_status();
     }
     return rc;
+}
+
+extern "C" int32_t pt_conv_bwd_weight(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, float* dw, void* ws,
+                                      size_t ws_bytes, void* stream) {
+    return bwd_weight_impl(d, x, dy, dw, ws, ws_bytes, stream, nullptr);
+}
+
+extern "C" int32_t pt_conv_bwd_weight_lasso_workspace_bytes(const pt_conv_desc* d, size_t* bytes) {
+    if (!bytes) return PT_ERR_NULL;
+    int32_t rc = check_desc(d);
+    if (rc != PT_OK) return rc;
+    const size_t a = wgrad_lasso_ws_of(d, plan_wgrad(d, true)), b = wgrad_lasso_ws_of(d, plan_wgrad(d, false));
+    *bytes = a > b ? a : b;
+    return PT_OK;
+}
+
+extern "C" int32_t pt_conv_bwd_weight_lasso(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, const float* w,
+                                            const float* out_norm, const float* in_norm, float lambda, uint32_t flags,
+                                            float* dw, void* ws, size_t ws_bytes, void* stream) {
+    if (!w || !out_norm || !in_norm) return PT_ERR_NULL;
+    if (flags & ~(PT_LASSO_OUT | PT_LASSO_IN)) return PT_ERR_UNSUPPORTED;
+    const ReduceLasso rl{w, out_norm, in_norm, lambda, flags};
+    return bwd_weight_impl(d, x, dy, dw, ws, ws_bytes, stream, &rl);
 }

@@ -193,6 +193,12 @@ inline size_t wgrad_ws(const pt_conv_desc* d) {
     return a > b ? a : b;
 }
 
+// Workspace of the weight gradient with the regulariser folded into its reduction pass: at least one slab of partials
+inline size_t wgrad_lasso_ws_of(const pt_conv_desc* d, const WgradPlan& p) {
+    const size_t one = (size_t)round_up((int64_t)d->K * p.Mtot * 4, 256);
+    return p.ws_bytes > one ? p.ws_bytes : one;
+}
+
 inline WgradArgs make_wgrad_args(const pt_conv_desc* d, const WgradPlan& p, const uint16_t* x, const uint16_t* dy,
                                  float* dw, void* ws) {
     WgradArgs a{};

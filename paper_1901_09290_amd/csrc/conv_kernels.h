@@ -864,6 +864,12 @@ struct WgradArgs {
     int KP;              // K rounded up to 8
     int fold;            // direct kernel: a tile row block spans the S taps of one filter row (dense small-C pixels)
     int iters_total, iters_per_split, splits;
+    // direct kernel writing dw itself (direct != 0): when lw is set, the gradient of the group-lasso penalty is added
+    // to every element on the way out, dw += l_lambda * (lw * (1/l_on[k] + 1/l_in[c])) with a zero norm contributing 0
+    const float* lw;    // fp32 master weights, layout and pitch of dw
+    const float* l_on;  // [K], nullptr = output groups not regularised
+    const float* l_in;  // [C], nullptr = input groups not regularised
+    float l_lambda;
     int out_row_pitch;   // elements between consecutive k in the partial buffer (Mtot)
     int wpitch;
     int direct;          // 1: write dw layout directly (splits == 1)
@@ -1328,11 +1334,25 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
                 const int ts = a.fold ? cr / a.CP : 0;
                 const int c = cr - ts * a.CP;
                 const int tapi = a.fold ? tb * a.S + ts : tb;
-                const float v0 = acc[tm][tn][4 * g + 0], v1 = acc[tm][tn][4 * g + 1];
-                const float v2 = acc[tm][tn][4 * g + 2], v3 = acc[tm][tn][4 * g + 3];
+                float v0 = acc[tm][tn][4 * g + 0], v1 = acc[tm][tn][4 * g + 1];
+                float v2 = acc[tm][tn][4 * g + 2], v3 = acc[tm][tn][4 * g + 3];
                 if (a.direct) {
                     if (c >= a.C) continue;
-                    float* dst = out + ((int64_t)k * a.RS + tapi) * a.wpitch + c;
+                    const int64_t o = ((int64_t)k * a.RS + tapi) * a.wpitch + c;
+                    float* dst = out + o;
+                    if (a.lw) {  // uniform: regulariser folded in
+                        const float on = a.l_on ? a.l_on[k] : 0.f;
+                        const float inv_out = on > 0.f ? 1.0f / on : 0.f;
+                        float t[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const bool in_range = c + e < a.C;
+                            const float in = (a.l_in && in_range) ? a.l_in[c + e] : 0.f;
+                            const float inv_in = in > 0.f ? 1.0f / in : 0.f;
+                            t[e] = in_range ? a.l_lambda * (a.lw[o + e] * (inv_out + inv_in)) : 0.f;
+                        }
+                        v0 += t[0]; v1 += t[1]; v2 += t[2]; v3 += t[3];
+                    }
                     if (a.o_vec && c + 3 < a.C) {
                         *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
                     } else {

@@ -84,7 +84,8 @@ class ConvLayer:
     def workspace_bytes(self) -> int:
         d = self.desc
         return max(B.conv_fwd_workspace_bytes(d), B.conv_bwd_data_workspace_bytes(d),
-                   B.conv_bwd_weight_workspace_bytes(d), B.group_norms_workspace_bytes(self.spec.K, self.RS, self.spec.C))
+                   B.conv_bwd_weight_workspace_bytes(d), B.conv_bwd_weight_lasso_workspace_bytes(d),
+                   B.group_norms_workspace_bytes(self.spec.K, self.RS, self.spec.C))
 
     def norms_job(self, shadow: bool = True) -> B.LayerWeights:
         s = self.spec
@@ -115,6 +116,11 @@ class ConvLayer:
 
     def bwd_weight(self, ws):
         B.conv_bwd_weight(self.desc, self.x, self.dy, self.dw, ws)
+
+    def bwd_weight_lasso(self, ws, lam: float):
+        """Weight gradient with the regulariser's gradient added in its reduction pass (dw written once)."""
+        B.conv_bwd_weight_lasso(self.desc, self.x, self.dy, self.w_master, self.out_norm, self.in_norm, lam,
+                                self.lasso_flags, self.dw, ws)
 
     def lasso(self, lam: float):
         s = self.spec
@@ -170,6 +176,7 @@ class Network:
         self.sides = [torch.cuda.Stream() for _ in range(WGRAD_STREAMS)]
         self.ws_sides = [self.ws] + [torch.empty_like(self.ws) for _ in range(WGRAD_STREAMS - 1)]
         self.overlap_wgrad = True
+        self.fuse_lasso = True   # regulariser's gradient inside the weight gradient's reduction pass
 
     def train_step(self, lam: float) -> None:
         """Alg. 1, one iteration restricted to the conv layers: GroupLassoReg (all layers' group norms, which
@@ -181,8 +188,9 @@ class Network:
         stays on the caller's stream and each weight gradient is enqueued on a side stream behind the event that
         marks its dy as ready.  Weight gradients of different layers are independent of each other as well, so
         they alternate between WGRAD_STREAMS side streams (each with its own split workspace): one layer's short
-        reduction pass and the ramp-down of its main kernel overlap the next layer's main kernel.  All streams
-        join before the regulariser's gradient."""
+        reduction pass and the ramp-down of its main kernel overlap the next layer's main kernel.  In this mode the
+        regulariser's gradient is added by each weight gradient's own reduction pass (fuse_lasso), so dW is written
+        once and no pass over all weights follows the join."""
         if not self.overlap_wgrad:
             B.group_norms_batched(self.norm_jobs, self.ws_norms)
             if self.crsk_jobs is not None:
@@ -219,11 +227,16 @@ class Network:
                 ready = torch.cuda.Event()
                 ready.record(main)                 # dy(l) is final here (the layer above has produced it)
                 side.wait_event(ready)
-                with torch.cuda.stream(side):
-                    l.bwd_weight(ws)               # each workspace is used by one stream only
+                with torch.cuda.stream(side):      # each workspace is used by one stream only
+                    if self.fuse_lasso:
+                        l.bwd_weight_lasso(ws, lam)
+                    else:
+                        l.bwd_weight(ws)
                 l.bwd_data_crsk()
             for side in self.sides:
                 main.wait_stream(side)
+            if self.fuse_lasso:
+                return
         B.group_lasso_grad_batched(self.lasso_jobs, lam)
 
     def regulariser_value(self) -> None:

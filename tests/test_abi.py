@@ -33,6 +33,23 @@ def test_every_declared_symbol_is_exported(lib):
     assert sorted(B.EXPORTS) == names
 
 
+def test_weight_gradient_with_lasso_validates_before_launching(lib):
+    d = B.conv_desc(4, 16, 16, 16, 16, 3, 3, 1, 1)
+    n = C.c_size_t(0)
+    assert lib.pt_conv_bwd_weight_lasso_workspace_bytes(C.byref(d), C.byref(n)) == 0
+    assert n.value >= 16 * 9 * 16 * 4 and n.value >= B.conv_bwd_weight_workspace_bytes(d)   # at least one dw-sized slab
+    assert lib.pt_conv_bwd_weight_lasso_workspace_bytes(C.byref(d), None) == -1
+    fake = C.c_void_p(4096)
+    args = lambda **kw: [kw.get(k, fake) for k in ("x", "dy", "w", "on", "inn")]
+    call = lambda a, flags=3, ws=fake, nb=1 << 30: lib.pt_conv_bwd_weight_lasso(C.byref(d), a[0], a[1], a[2], a[3], a[4], 1e-3,
+                                                                             flags, fake, ws, nb, None)
+    for missing in ("x", "dy", "w", "on", "inn"):
+        assert call(args(**{missing: None})) == -1
+    assert call(args(), flags=4) == -4                     # unknown regulariser flag
+    assert call(args(), ws=None) == -1                     # the slab is always needed
+    assert call(args(), nb=16) == -3                       # workspace too small
+
+
 def test_version(lib):
     assert lib.pt_version() >= 100
 

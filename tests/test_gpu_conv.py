@@ -137,6 +137,66 @@ def test_narrow_outputs_over_very_many_pixels(case):
     _check_full(spec, 700 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=True)
 
 
+FUSED_LASSO = [
+    # N  H   W   C    K   R st pad   flags        reductions split over many workgroups, and single-slab ones
+    ((2, 12, 12, 64, 64, 3, 1, 1), 3),
+    ((3, 9, 11, 24, 40, 3, 1, 1), 3),
+    ((2, 14, 14, 128, 96, 1, 1, 0), 1),
+    ((2, 15, 15, 40, 136, 3, 2, 1), 2),
+    ((2, 18, 18, 3, 16, 7, 2, 3), 1),          # a first layer: input groups exempt
+    ((2, 10, 10, 37, 51, 3, 1, 1), 3),         # ragged counts
+    ((1, 7, 7, 520, 520, 3, 1, 1), 3),         # more tiles than the split target: one slab, no split
+    ((5, 128, 130, 64, 64, 1, 1, 0), 3),       # very many pixels
+]
+
+
+@pytest.mark.parametrize("case,flags", FUSED_LASSO, ids=lambda c: "x".join(map(str, c)) if isinstance(c, tuple) else str(c))
+@pytest.mark.parametrize("padded", [True, False])
+def test_weight_gradient_with_regulariser_folded_in(case, flags, padded):
+    """pt_conv_bwd_weight_lasso against the oracle's weight gradient plus the oracle's lasso gradient (convolution
+    tolerance on the sum, 1e-5 on the added term itself), and against the two separate GPU calls."""
+    from gpu_util import CONV_TOL, DEV, F32_TOL, dev_bf16, dev_f32, pitch8, rel_err, workspace
+    from paper_1901_09290_amd import binding as B
+    spec = _spec(*case)
+    rng = np.random.Generator(np.random.PCG64(800 + sum(case) + flags))
+    t = wl.conv_tensors(spec, rng, want=("x", "dy"))
+    w = (rng.standard_normal((spec.K, spec.R, spec.S, spec.C)) * 0.05).astype(np.float32)
+    w[0] = 0.0                    # a zero output group and a zero input group: their terms are exactly 0
+    w[..., spec.C - 1] = 0.0
+    lam = 0.5                     # large, so that the added term is visible beside the data gradient
+    xp, yp, wp = (pitch8(spec.C), pitch8(spec.K), pitch8(spec.C)) if padded else (spec.C, spec.K, spec.C)
+    d = B.desc_of(spec, xp, yp, wp)
+    xd, dyd, wd = dev_bf16(t["x"], xp), dev_bf16(t["dy"], yp), dev_f32(w, wp)
+    ron, rin = oracle.group_norms(w)
+    on = torch.from_numpy(ron.astype(np.float32)).to(DEV)
+    inn = torch.from_numpy(rin.astype(np.float32)).to(DEV)
+    RS = spec.R * spec.S
+    ws = workspace(max(B.conv_bwd_weight_lasso_workspace_bytes(d), B.conv_bwd_weight_workspace_bytes(d)))
+    dw_f = torch.full((spec.K, spec.R, spec.S, wp), float("nan"), dtype=torch.float32, device=DEV)
+    dw_s = torch.full((spec.K, spec.R, spec.S, wp), float("nan"), dtype=torch.float32, device=DEV)
+    B.conv_bwd_weight_lasso(d, xd, dyd, wd, on, inn, lam, flags, dw_f, ws)
+    B.conv_bwd_weight(d, xd, dyd, dw_s, ws)
+    torch.cuda.synchronize()
+    plain = dw_s.cpu().numpy()[..., : spec.C].copy()
+    B.group_lasso_grad(wd, on, inn, lam, flags, dw_s, spec.K, RS, spec.C, wp)
+    torch.cuda.synchronize()
+    fused, separate = dw_f.cpu().numpy()[..., : spec.C], dw_s.cpu().numpy()[..., : spec.C]
+    if wp != spec.C:
+        assert bool(torch.isnan(dw_f[..., spec.C:]).all())              # padding untouched
+    rdw = oracle.conv_bwd_weight(oracle.shape_of(spec), t["x"], t["dy"])
+    ref = oracle.group_lasso_grad(w, on.cpu().numpy(), inn.cpu().numpy(), lam, flags, rdw)
+    assert rel_err(fused, ref) <= CONV_TOL
+    # the added term alone: what the fused call wrote minus the plain weight gradient of the same kernels
+    term_ref = oracle.group_lasso_grad(w, on.cpu().numpy(), inn.cpu().numpy(), lam, flags, np.zeros_like(rdw))
+    # (one fp32 rounding of the sum, a few ulps of the larger operand, plus 1e-5 of the term)
+    big = np.maximum(np.abs(plain), np.abs(fused)).astype(np.float32)
+    slack = 4 * np.spacing(big).astype(np.float64) + 1e-5 * (np.abs(term_ref) + np.sqrt(np.mean(term_ref ** 2)))
+    assert np.all(np.abs(fused.astype(np.float64) - plain - term_ref) <= slack)
+    assert rel_err(fused, separate) <= F32_TOL
+    if flags == 1:
+        assert np.array_equal(fused[0], plain[0])                       # zero output group: nothing added
+
+
 def test_results_are_run_to_run_identical():
     from gpu_util import run_conv_all
     spec = _spec(4, 14, 14, 72, 104, 3, 1, 1)
