@@ -17,7 +17,9 @@
  *             weights     KRSC  w[K][R][S][w_cpitch].
  *    A `*_cpitch` is the physical length, in elements, of the innermost (channel) axis; it is
  *    >= the logical channel count.  Elements between the logical count and the pitch are never
- *    read as data and are never written.  Pitches that are multiples of 8 elements (16 bytes of
+ *    read as data, and are not written except where a call says so (pt_compact_nhwc, pt_bn_fwd /
+ *    pt_bn_bwd, and the convolutions under PT_CONV_PAD_ZERO write zeros from the channel count up to
+ *    the next multiple of 8).  Pitches that are multiples of 8 elements (16 bytes of
  *    bf16) select the vectorised kernels; any other pitch takes a slower element-wise path with
  *    identical results.
  *  - bf16 tensors are passed as uint16_t bit patterns (IEEE bfloat16, round-to-nearest-even on
@@ -26,6 +28,9 @@
  *    Inputs and outputs must not alias.
  *  - Every call returns a pt_status.  Argument errors are detected on the host before anything is
  *    enqueued.  No exception crosses this boundary.
+ *  - State: none besides the last HIP error code and a one-time, idempotent opt-in of some kernels to
+ *    large LDS allocations, made at their first launch on the device current at that moment (one
+ *    device per process is assumed).  Calls may come from any host thread.
  */
 #ifndef PRUNETRAIN_H
 #define PRUNETRAIN_H
