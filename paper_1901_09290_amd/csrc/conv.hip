@@ -368,7 +368,7 @@ static int32_t bwd_weight_impl(const pt_conv_desc* d, const uint16_t* x, const u
     if (need > 0 && !aligned16(ws)) return PT_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
     WgradArgs a = make_wgrad_args(d, p, x, dy, dw, ws);
-    if (rl && a.direct && p.dl) {  // the direct kernel's own epilogue adds the term
+    if (rl && a.direct && p.dl && aligned16(rl->w)) {  // the direct kernel's own epilogue adds the term (vector loads of w)
         a.lw = rl->w;
         a.l_on = (rl->flags & PT_LASSO_OUT) ? rl->out_norm : nullptr;
         a.l_in = (rl->flags & PT_LASSO_IN) ? rl->in_norm : nullptr;

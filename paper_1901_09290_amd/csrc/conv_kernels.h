@@ -1343,14 +1343,23 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
                     if (a.lw) {  // uniform: regulariser folded in
                         const float on = a.l_on ? a.l_on[k] : 0.f;
                         const float inv_out = on > 0.f ? 1.0f / on : 0.f;
+                        float wv[4], in[4];
+                        if (a.o_vec && c + 3 < a.C) {  // whole vectors (w has the alignment and pitch of dw)
+                            const float4 w4 = *reinterpret_cast<const float4*>(a.lw + o);
+                            wv[0] = w4.x; wv[1] = w4.y; wv[2] = w4.z; wv[3] = w4.w;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) in[e] = a.l_in ? a.l_in[c + e] : 0.f;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const bool in_range = c + e < a.C;
+                                wv[e] = in_range ? a.lw[o + e] : 0.f;
+                                in[e] = (a.l_in && in_range) ? a.l_in[c + e] : 0.f;
+                            }
+                        }
                         float t[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const bool in_range = c + e < a.C;
-                            const float in = (a.l_in && in_range) ? a.l_in[c + e] : 0.f;
-                            const float inv_in = in > 0.f ? 1.0f / in : 0.f;
-                            t[e] = in_range ? a.l_lambda * (a.lw[o + e] * (inv_out + inv_in)) : 0.f;
-                        }
+                        for (int e = 0; e < 4; ++e) t[e] = a.l_lambda * (wv[e] * (inv_out + (in[e] > 0.f ? 1.0f / in[e] : 0.f)));
                         v0 += t[0]; v1 += t[1]; v2 += t[2]; v3 += t[3];
                     }
                     if (a.o_vec && c + 3 < a.C) {
