@@ -109,6 +109,8 @@ __global__ void k_zero_class(uint16_t* __restrict__ D, int64_t pixels, int gH, i
 // LASSO: the gradient of the group-lasso penalty (Eq. 1-2) is added on the way out, with the arithmetic of
 // k_group_lasso_grad: dw = sum + lambda * (w * (1/out_norm[k] + 1/in_norm[c])), a zero norm contributing 0.
 constexpr int kReduceWaves = 8;
+constexpr int kReduceWideMaxSplits = 16;
+constexpr int64_t kReduceWideMinOutputs = 64 * 1024;
 struct ReduceLasso {
     const float* w;         // [K][RS][wpitch], the pitch of dw
     const float* out_norm;  // [K]
@@ -155,6 +157,60 @@ __global__ __launch_bounds__(64 * kReduceWaves) void k_wgrad_reduce(const float*
             }
             dw[o] = s;
         }
+    }
+}
+
+// The same sum for launches with few splits and many outputs: one thread per four consecutive outputs of the slab
+// (16-byte loads, the splits added in ascending order with four loads in flight), so a workgroup covers 1024 outputs
+// instead of 64.  CP is a multiple of 8: the four outputs share a filter tap.
+template <bool LASSO>
+__global__ __launch_bounds__(256) void k_wgrad_reduce4(const float* __restrict__ part, int splits, int K, int RS, int C,
+                                                       int CP, int wpitch, int o_vec, float* __restrict__ dw,
+                                                       const ReduceLasso rl) {
+    const int Mtot = RS * CP;
+    const int64_t total = (int64_t)K * Mtot;
+    const int64_t t = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (t >= total) return;
+    const int64_t k = t / Mtot;
+    const int mrow = (int)(t - k * Mtot);
+    const int tp = mrow / CP, c = mrow - tp * CP;
+    if (c >= C) return;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    int i = 0;
+    for (; i + 3 < splits; i += 4) {
+        const float4 a0 = *reinterpret_cast<const float4*>(part + (int64_t)i * total + t);
+        const float4 a1 = *reinterpret_cast<const float4*>(part + (int64_t)(i + 1) * total + t);
+        const float4 a2 = *reinterpret_cast<const float4*>(part + (int64_t)(i + 2) * total + t);
+        const float4 a3 = *reinterpret_cast<const float4*>(part + (int64_t)(i + 3) * total + t);
+        s.x = (((s.x + a0.x) + a1.x) + a2.x) + a3.x;
+        s.y = (((s.y + a0.y) + a1.y) + a2.y) + a3.y;
+        s.z = (((s.z + a0.z) + a1.z) + a2.z) + a3.z;
+        s.w = (((s.w + a0.w) + a1.w) + a2.w) + a3.w;
+    }
+    for (; i < splits; ++i) {
+        const float4 a0 = *reinterpret_cast<const float4*>(part + (int64_t)i * total + t);
+        s.x += a0.x; s.y += a0.y; s.z += a0.z; s.w += a0.w;
+    }
+    const int64_t o = (k * RS + tp) * wpitch + c;
+    float v[4] = {s.x, s.y, s.z, s.w};
+    const bool whole = o_vec && c + 3 < C;
+    if constexpr (LASSO) {
+        const float on = (rl.flags & PT_LASSO_OUT) ? rl.out_norm[k] : 0.f;
+        const float inv_out = on > 0.f ? 1.0f / on : 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (c + e < C) {
+                const float in = (rl.flags & PT_LASSO_IN) ? rl.in_norm[c + e] : 0.f;
+                v[e] += rl.lambda * (rl.w[o + e] * (inv_out + (in > 0.f ? 1.0f / in : 0.f)));
+            }
+        }
+    }
+    if (whole) {
+        *reinterpret_cast<float4*>(dw + o) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (c + e < C) dw[o + e] = v[e];
     }
 }
 
@@ -383,12 +439,25 @@ static int32_t bwd_weight_impl(const pt_conv_desc* d, const uint16_t* x, const u
         const int64_t work = (int64_t)d->K * p.Mtot;
         const int64_t nblk = ceil_div(work, 64);
         if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
-        if (rl)
+        // few splits over many outputs: the four-outputs-per-thread form; many splits over few outputs: one output per
+        // lane with the splits spread over eight wavefronts
+        const bool wide = p.splits <= kReduceWideMaxSplits && work >= kReduceWideMinOutputs && p.Mtot % 4 == 0;
+        const ReduceLasso none{};
+        if (wide) {
+            const unsigned nb4 = (unsigned)ceil_div(work / 4, 256);
+            if (rl)
+                hipLaunchKernelGGL(k_wgrad_reduce4<true>, dim3(nb4), dim3(256), 0, st, (const float*)ws, p.splits, d->K, a.RS,
+                                   d->C, p.CP, d->w_cpitch, a.o_vec, dw, *rl);
+            else
+                hipLaunchKernelGGL(k_wgrad_reduce4<false>, dim3(nb4), dim3(256), 0, st, (const float*)ws, p.splits, d->K, a.RS,
+                                   d->C, p.CP, d->w_cpitch, a.o_vec, dw, none);
+        } else if (rl) {
             hipLaunchKernelGGL(k_wgrad_reduce<true>, dim3((unsigned)nblk), dim3(64 * kReduceWaves), 0, st, (const float*)ws,
                                p.splits, d->K, a.RS, d->C, p.CP, d->w_cpitch, dw, *rl);
-        else
+        } else {
             hipLaunchKernelGGL(k_wgrad_reduce<false>, dim3((unsigned)nblk), dim3(64 * kReduceWaves), 0, st, (const float*)ws,
-                               p.splits, d->K, a.RS, d->C, p.CP, d->w_cpitch, dw, ReduceLasso{});
+                               p.splits, d->K, a.RS, d->C, p.CP, d->w_cpitch, dw, none);
+        }
         rc = launch_status();
     }
     return rc;
