@@ -29,8 +29,8 @@
  *  - Every call returns a pt_status.  Argument errors are detected on the host before anything is
  *    enqueued.  No exception crosses this boundary.
  *  - State: none besides the last HIP error code and a one-time, idempotent opt-in of some kernels to
- *    large LDS allocations, made at their first launch on the device current at that moment (one
- *    device per process is assumed).  Calls may come from any host thread.
+ *    large LDS allocations, made at their first launch on each device and recorded per device with
+ *    atomics.  Calls may come from any host thread.
  */
 #ifndef PRUNETRAIN_H
 #define PRUNETRAIN_H
@@ -119,6 +119,19 @@ int32_t pt_conv_bwd_data_crsk(const pt_conv_desc* d, const uint16_t* dy, const u
 int32_t pt_conv_bwd_weight(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, float* dw, void* ws,
                            size_t ws_bytes, void* stream);
 
+/* Host-only: how pt_conv_bwd_weight[_lasso] would run this descriptor on 16-byte aligned tensors (aligned != 0) or
+ * on unaligned ones: the number of workgroup slices of the pixel reduction (1 = the main kernel writes dw itself),
+ * output tiles per slice, and which pass combines the slices (PT_WGRAD_REDUCE_*).  For tests and tuning: lets a
+ * caller assert that a problem size reaches the code path it is meant to cover. */
+#define PT_WGRAD_REDUCE_NONE 0 /* unsplit: no second pass (with the regulariser: added in the main kernel's epilogue, or
+                                  by a pass over one slab when the main kernel cannot) */
+#define PT_WGRAD_REDUCE_DEEP 1 /* many slices over few outputs: one output per lane, slices spread over wavefronts */
+#define PT_WGRAD_REDUCE_WIDE 2 /* few slices over many outputs: four outputs per thread, slices in ascending order */
+typedef struct pt_wgrad_plan_info {
+    int32_t splits, tiles, reduce_kind, tile_m, tile_n;
+} pt_wgrad_plan_info;
+int32_t pt_conv_bwd_weight_plan(const pt_conv_desc* d, int32_t aligned, pt_wgrad_plan_info* info);
+
 /* ---- group lasso: Eq. 1-2 ------------------------------------------------------------------- */
 
 /* Channel-group L2 norms of one layer's fp32 master weights w[K][RS][w_cpitch], RS = R*S:
@@ -175,6 +188,23 @@ typedef struct pt_layer_lasso {
 } pt_layer_lasso;
 int32_t pt_group_norms_batched_workspace_bytes(const pt_layer_weights* layers, int32_t n, size_t* bytes);
 int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_t n, void* ws, size_t ws_bytes, void* stream);
+
+/* Group norms and zero-group detection in the same two launches (Eq. 2 + threshold zeroing of Sec. 4.1): per
+ * layer, out_norm / in_norm as pt_group_norms writes them and zero_out[k] = (out_norm[k] < thr),
+ * zero_in[c] = (in_norm[c] < thr), the comparison of pt_zero_groups on the fp32 norms (strict; thr <= 0 marks
+ * nothing).  `layers` is a HOST array; all five pointers of a layer are required.  Workspace as for
+ * pt_group_norms_batched. */
+typedef struct pt_layer_detect {
+    const float* w;     /* [K][RS][w_cpitch] fp32 master weights */
+    float* out_norm;    /* [K] */
+    float* in_norm;     /* [C] */
+    uint8_t* zero_out;  /* [K] */
+    uint8_t* zero_in;   /* [C] */
+    int32_t K, RS, C, w_cpitch;
+} pt_layer_detect;
+int32_t pt_group_norms_detect_batched_workspace_bytes(const pt_layer_detect* layers, int32_t n, size_t* bytes);
+int32_t pt_group_norms_detect_batched(const pt_layer_detect* layers, int32_t n, float thr, void* ws, size_t ws_bytes,
+                                      void* stream);
 int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int32_t n, float lambda, void* stream);
 
 /* Optimizer step of Alg. 1 with the regulariser's gradient folded in (one pass over w, dw, mom instead of a
@@ -199,7 +229,7 @@ int32_t pt_sgd_momentum_lasso_batched(const pt_layer_update* layers, int32_t n, 
 
 /* Value of the regulariser over a whole network (GroupLassoReg of Alg. 1, Eq. 1-2):
  *   *penalty_dev = sum over layers of ( a * sum_k out_norm[k] + b * sum_c in_norm[c] ),  a, b = flags bits.
- * No weighting by group size (one global coefficient, Sec. 3.1).  The norms are those pt_group_norms wrote;
+ * No weighting by group size (one global coefficient, Sec. 4.1).  The norms are those pt_group_norms wrote;
  * `layers` is a HOST array whose pointers are device pointers; penalty_dev is a device double, overwritten
  * (0 for n == 0).  fp64 accumulation in a fixed order: run-to-run identical.  One small launch per 96 layers. */
 typedef struct pt_layer_penalty {
@@ -212,7 +242,7 @@ typedef struct pt_layer_penalty {
 int32_t pt_group_lasso_penalty_batched(const pt_layer_penalty* layers, int32_t n, double* penalty_dev, void* stream);
 
 /* Host-only: SetCoeff of Alg. 1.  The coefficient for which the regulariser makes up `ratio` of the total loss at
- * the first iteration (penalty-ratio equation of Sec. 3.1; the paper uses 0.20-0.25):
+ * the first iteration (penalty-ratio equation of Sec. 4.1; the paper uses 0.20-0.25):
  *   ratio = lambda*loss2 / (loss1 + lambda*loss2)   =>   lambda = ratio*loss1 / ((1 - ratio)*loss2),
  * loss1 = classification loss, loss2 = the value above.  PT_ERR_SHAPE unless 0 < ratio < 1, loss2 > 0, loss1 >= 0. */
 int32_t pt_lasso_set_coeff(double loss1, double loss2, double ratio, double* lambda);
@@ -318,7 +348,7 @@ int32_t pt_compact_nhwc_batched(const pt_gather_nhwc* jobs, int32_t n_jobs, void
 int32_t pt_scatter_nhwc(const uint16_t* x, int64_t pixels, int32_t Cp, int32_t x_cpitch, const int32_t* idx, int32_t C,
                         uint16_t* out, int32_t out_cpitch, void* stream);
 
-/* Largest absolute weight per channel group (Sec. 4.1 also states the zeroing rule this way):
+/* Largest absolute weight per channel group (Sec. 4.2 states the zeroing rule this way):
  *   out_max[k] = max |w[k,:,:]|,  in_max[c] = max |w[:,:,c]|.   Exact (a maximum has no rounding); feed the
  * results to pt_zero_groups like norms.  Limit: C <= 2048.  Three small launches. */
 int32_t pt_group_maxabs(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, float* out_max,
@@ -371,7 +401,7 @@ int32_t pt_bn_fwd_from_sums(const uint16_t* x, int64_t pixels, int32_t C, int32_
                             int32_t n_partial, const float* gamma, const float* beta, float eps, uint16_t* y,
                             int32_t y_cpitch, float* mean, float* invstd, void* stream);
 
-/* ---- layer removal: Sec. 3.1 ("Layer Removal by Overlapping Regularization Groups") --------------------------- */
+/* ---- layer removal: Sec. 4.1 ("Layer Removal by Overlapping Regularization Groups") --------------------------- */
 
 /* HOST-only graph logic, no device work.  After a plan, an edge with no survivors (n_keep == 0) carries nothing: the
  * layers writing it and the layers reading it are removed.  Removal propagates: an edge all of whose producers are

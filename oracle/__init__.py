@@ -313,7 +313,7 @@ def bn_bwd(x, dy, gamma, mean, invstd):
 
 
 def plan_layer_removal(n_layers: int, edges):
-    """Layer removal after a plan (Sec. 3.1, "Layer Removal by Overlapping Regularization Groups"), as sets.
+    """Layer removal after a plan (Sec. 4.1, "Layer Removal by Overlapping Regularization Groups"), as sets.
 
     edges: one (producers, consumers, n_keep, fed_outside, read_outside) per channel edge.  An edge with no
     survivors carries nothing, so the layers on either side of it go; an edge whose listed producers are all

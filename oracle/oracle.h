@@ -64,12 +64,12 @@ int oracle_group_lasso_grad(const double* w, const double* out_norm, const doubl
 
 /* One layer's share of the regulariser's value (Eq. 1-2; GroupLassoReg of Alg. 1), ADDED onto *penalty:
  * a * sum_k out_norm[k] + b * sum_c in_norm[c], a = flags bit 0, b = flags bit 1 (no size weighting: one
- * global coefficient, Sec. 3.1). */
+ * global coefficient, Sec. 4.1). */
 int oracle_group_lasso_penalty(const double* out_norm, int32_t K, const double* in_norm, int32_t C, uint32_t flags,
                                double* penalty);
 
 /* SetCoeff of Alg. 1: the coefficient for which the regulariser makes up `ratio` of the total loss
- * (penalty-ratio equation of Sec. 3.1): ratio = lambda*loss2 / (loss1 + lambda*loss2), solved for lambda.
+ * (penalty-ratio equation of Sec. 4.1): ratio = lambda*loss2 / (loss1 + lambda*loss2), solved for lambda.
  * Needs 0 < ratio < 1, loss2 > 0, loss1 >= 0. */
 int oracle_set_coeff(double loss1, double loss2, double ratio, double* lambda);
 

@@ -27,6 +27,7 @@ EXPORTS = [
     "pt_conv_fwd", "pt_conv_bwd_data", "pt_conv_bwd_weight",
     "pt_group_norms_workspace_bytes", "pt_group_norms", "pt_group_lasso_grad",
     "pt_group_norms_batched_workspace_bytes", "pt_group_norms_batched", "pt_group_lasso_grad_batched",
+    "pt_group_norms_detect_batched_workspace_bytes", "pt_group_norms_detect_batched", "pt_conv_bwd_weight_plan",
     "pt_zero_groups", "pt_reconcile_edge", "pt_compact_plan",
     "pt_compact_weights", "pt_compact_vector", "pt_compact_nhwc",
     "pt_weights_to_crsk_batched", "pt_conv_bwd_data_crsk",
@@ -55,6 +56,18 @@ class ConvDesc(C.Structure):
 class LayerWeights(C.Structure):
     _fields_ = [("w", C.c_void_p), ("out_norm", C.c_void_p), ("in_norm", C.c_void_p), ("w_shadow", C.c_void_p),
                 ("K", C.c_int32), ("RS", C.c_int32), ("C", C.c_int32), ("w_cpitch", C.c_int32)]
+
+
+class LayerDetect(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("out_norm", C.c_void_p), ("in_norm", C.c_void_p), ("zero_out", C.c_void_p),
+                ("zero_in", C.c_void_p), ("K", C.c_int32), ("RS", C.c_int32), ("C", C.c_int32), ("w_cpitch", C.c_int32)]
+
+
+class WgradPlanInfo(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("splits", "tiles", "reduce_kind", "tile_m", "tile_n")]
+
+
+WGRAD_REDUCE_NONE, WGRAD_REDUCE_DEEP, WGRAD_REDUCE_WIDE = 0, 1, 2
 
 
 class LayerLasso(C.Structure):
@@ -135,6 +148,9 @@ def lib() -> C.CDLL:
             "pt_group_norms_batched_workspace_bytes": [C.POINTER(LayerWeights), i32, C.POINTER(sz)],
             "pt_group_norms_batched": [C.POINTER(LayerWeights), i32, vp, sz, vp],
             "pt_group_lasso_grad_batched": [C.POINTER(LayerLasso), i32, f32, vp],
+            "pt_group_norms_detect_batched_workspace_bytes": [C.POINTER(LayerDetect), i32, C.POINTER(sz)],
+            "pt_group_norms_detect_batched": [C.POINTER(LayerDetect), i32, f32, vp, sz, vp],
+            "pt_conv_bwd_weight_plan": [dp, i32, C.POINTER(WgradPlanInfo)],
             "pt_zero_groups": [vp, i32, f32, vp, vp],
             "pt_reconcile_edge": [C.POINTER(vp), i32, C.POINTER(vp), i32, i32, vp, vp],
             "pt_compact_plan": [vp, i32, vp, vp, vp],
@@ -291,6 +307,31 @@ def group_norms_batched(layers, ws, stream=None) -> None:
     arr = _array(layers, LayerWeights)
     p, n = _ws(ws)
     _ck("pt_group_norms_batched", lib().pt_group_norms_batched(arr, len(layers), p, n, _stream(stream)))
+
+
+def layer_detect(w, K, RS, Cc, w_cpitch, out_norm, in_norm, zero_out, zero_in) -> LayerDetect:
+    return LayerDetect(_ptr(w), _ptr(out_norm), _ptr(in_norm), _ptr(zero_out), _ptr(zero_in), K, RS, Cc, w_cpitch)
+
+
+def group_norms_detect_batched_workspace_bytes(layers) -> int:
+    arr = _array(layers, LayerDetect)
+    n = C.c_size_t(0)
+    _ck("pt_group_norms_detect_batched_workspace_bytes",
+        lib().pt_group_norms_detect_batched_workspace_bytes(arr, len(layers), C.byref(n)))
+    return n.value
+
+
+def group_norms_detect_batched(layers, thr: float, ws, stream=None) -> None:
+    """layers: list of LayerDetect (or a prepared ctypes array): norms and zero masks of every layer."""
+    arr = _array(layers, LayerDetect)
+    p, n = _ws(ws)
+    _ck("pt_group_norms_detect_batched", lib().pt_group_norms_detect_batched(arr, len(layers), thr, p, n, _stream(stream)))
+
+
+def conv_bwd_weight_plan(d: ConvDesc, aligned: bool = True) -> WgradPlanInfo:
+    info = WgradPlanInfo()
+    _ck("pt_conv_bwd_weight_plan", lib().pt_conv_bwd_weight_plan(C.byref(d), 1 if aligned else 0, C.byref(info)))
+    return info
 
 
 def group_lasso_grad_batched(layers, lam: float, stream=None) -> None:

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "prunetrain.h"
 
 namespace pt {
@@ -21,6 +23,25 @@ inline int32_t launch_status() {
     }
     return PT_OK;
 }
+
+// One-time opt-in of a kernel to `lds` bytes of dynamic LDS (needed above 64 KiB), kept per device: bit d of `done`
+// says the attribute is set on device d.  Safe from any host thread: the attribute call is idempotent, so two
+// threads racing through the first call both succeed.
+struct LdsOptIn {
+    std::atomic<uint64_t> done{0};
+    hipError_t ensure(const void* kernel, size_t lds, size_t always_above = 65536) {
+        if (lds <= always_above) return hipSuccess;
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const uint64_t bit = 1ull << (dev & 63);
+        if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        done.fetch_or(bit, std::memory_order_release);
+        return hipSuccess;
+    }
+};
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }

@@ -407,6 +407,26 @@ extern "C" int32_t pt_weights_to_crsk_batched(const pt_layer_crsk* layers, int32
     return flush();
 }
 
+// Few slices over many outputs take the four-outputs-per-thread reduction, the rest the one-output-per-lane form.
+static bool reduce_is_wide(const pt_conv_desc* d, const WgradPlan& p) {
+    const int64_t work = (int64_t)d->K * p.Mtot;
+    return p.splits <= kReduceWideMaxSplits && work >= kReduceWideMinOutputs && p.Mtot % 4 == 0;
+}
+
+extern "C" int32_t pt_conv_bwd_weight_plan(const pt_conv_desc* d, int32_t aligned, pt_wgrad_plan_info* info) {
+    if (!info) return PT_ERR_NULL;
+    const int32_t rc = check_desc(d);
+    if (rc != PT_OK) return rc;
+    const bool vec = aligned != 0 && d->x_cpitch % 8 == 0 && d->y_cpitch % 8 == 0;
+    const WgradPlan p = plan_wgrad(d, vec);
+    info->splits = p.splits;
+    info->tiles = p.tiles_m * p.tiles_n;
+    info->reduce_kind = p.splits == 1 ? PT_WGRAD_REDUCE_NONE : (reduce_is_wide(d, p) ? PT_WGRAD_REDUCE_WIDE : PT_WGRAD_REDUCE_DEEP);
+    info->tile_m = p.BM;
+    info->tile_n = p.BN;
+    return PT_OK;
+}
+
 // rl == nullptr: plain weight gradient.  Otherwise the regulariser's gradient is added where dw is written: in the
 // reduction pass of a split launch, in the epilogue of an unsplit launch of the direct kernel, and for an unsplit
 // launch of the register-staged kernel in a reduction pass over one slab of partial sums.
@@ -441,7 +461,7 @@ static int32_t bwd_weight_impl(const pt_conv_desc* d, const uint16_t* x, const u
         if (nblk > 0x7fffffff) return PT_ERR_UNSUPPORTED;
         // few splits over many outputs: the four-outputs-per-thread form; many splits over few outputs: one output per
         // lane with the splits spread over eight wavefronts
-        const bool wide = p.splits <= kReduceWideMaxSplits && work >= kReduceWideMinOutputs && p.Mtot % 4 == 0;
+        const bool wide = reduce_is_wide(d, p);
         const ReduceLasso none{};
         if (wide) {
             const unsigned nb4 = (unsigned)ceil_div(work / 4, 256);

@@ -72,19 +72,6 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
-#ifdef PT_KERNEL_TIMING
-// Working-build instrumentation (never defined for the library): per-workgroup phase time stamps.
-__device__ unsigned long long pt_dbg_times[4 * 16384];
-#define PT_STAMP(phase)                                                                                  \
-    do {                                                                                                 \
-        if (threadIdx.x == 0 && blockIdx.x < 16384) pt_dbg_times[blockIdx.x * 4 + (phase)] = wall_clock64(); \
-    } while (0)
-#else
-#define PT_STAMP(phase) \
-    do {                \
-    } while (0)
-#endif
-
 // XCD-aware block remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; give
 // each XCD a contiguous range of logical tiles so tiles that share operands share an L2.
 __device__ __forceinline__ int xcd_remap(int bid, int nb) {
@@ -365,13 +352,8 @@ inline hipError_t launch_igemm_cfg(IgemmArgs& a, hipStream_t st) {
     constexpr int NT = 64 * WGM * WGN;
     constexpr size_t lds = (size_t)STAGES * (BM + BN) * (BK + 8) * 2;
     auto kern = k_igemm<BM, BN, BK, WGM, WGN, STAGES, MINB, VEC>;
-    static bool attr_set = false;  // one-time opt-in to more than 64 KiB of dynamic LDS
-    if (lds > 65536 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;
+    if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     const int tiles_m = (int)ceil_div(a.M, BM);
     a.tiles_n = (int)ceil_div(a.Nout, BN);
     a.nk = (int)ceil_div((int64_t)a.TR * a.TS * a.CredP, BK);
@@ -435,7 +417,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
     static_assert(NW % 2 == 0 && GA % NW == 0 && GB % NW == 0 && LA >= 1 && LB >= 1 && TM >= 1 && TN >= 1, "tile config");
     static_assert(STAGES >= 2 && (STAGES - 2) * LPT < 64, "stages");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_b[];
-    PT_STAMP(0);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -619,14 +600,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < nk) issue(s);
-    PT_STAMP(1);
     // waves inside the reduction loop go first at the CU's issue arbiter: ahead of a co-resident workgroup's set-up
     // or stores, and ahead of weight-gradient waves sharing the CU from another stream (+0.4 % on the step)
     __builtin_amdgcn_s_setprio(2);
     if (all_live) main_loop(std::false_type{});
     else main_loop(std::true_type{});
     __builtin_amdgcn_s_setprio(0);
-    PT_STAMP(2);
 
     // ---- epilogue: registers -> global.  A lane holds, per 32x32 block, channels 8g + 4*(lane/32) + {0..3}
     // (g = 0..3) of pixel lane%32.  Swapping the upper half-wave of the g-even registers with the lower
@@ -801,7 +780,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
             a.stats[((size_t)q * a.tiles_m + tile_m) * a.Nout + n0 + chl] = tot;
         }
     }
-    PT_STAMP(3);
 #endif
 }
 
@@ -828,12 +806,8 @@ inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
                             reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true>),
                             reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, true>),
                             reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, true>)};
-    static bool attr_set[5] = {false, false, false, false, false};  // one-time opt-in to more than 64 KiB of dynamic LDS
-    if (lds > 65536 && !attr_set[variant]) {
-        hipError_t e = hipFuncSetAttribute(kerns[variant], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set[variant] = true;
-    }
+    static LdsOptIn opt_in[5];
+    if (hipError_t e = opt_in[variant].ensure(kerns[variant], lds); e != hipSuccess) return e;
     const dim3 grid((unsigned)(ceil_div(a.M, BM) * a.tiles_n)), block(NT);
     switch (variant) {
         case 0: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false>), grid, block, lds, st, a); break;
@@ -1059,13 +1033,8 @@ inline hipError_t launch_wgrad_cfg(WgradArgs& a, hipStream_t st) {
     constexpr int NT = 64 * WGM * WGN;
     constexpr size_t lds = (size_t)2 * BK * (BM + 32 + BN + 32) * 2;
     auto kern = k_wgrad<BM, BN, BK, WGM, WGN, MINB, VEC>;
-    static bool attr_set = false;
-    if (lds > 65536 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;
+    if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     a.tiles_m = (int)ceil_div(a.Mtot, BM);
     a.tiles_n = (int)ceil_div(a.K, BN);
     hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(NT), lds, st, a);
@@ -1123,7 +1092,6 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kg = wave / NWT, wave_t = wave - kg * NWT;  // wave group, wave inside the group
-    PT_STAMP(0);
     // Workgroup ids are dealt round-robin to the 8 XCDs.  All tiles of one pixel split read the same x and dy
     // slabs, so each XCD gets a contiguous range of the split-major (split, tile) order: a split's tiles run
     // back to back on one XCD and the slabs are fetched into that L2 once.
@@ -1268,7 +1236,6 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < nk) issue(it0 + s, s);
-    PT_STAMP(1);
     for (int kt0 = 0; kt0 < nk; kt0 += STAGES) {
 #pragma unroll
         for (int s = 0; s < STAGES; ++s) {
@@ -1289,7 +1256,6 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
         }
     }
 
-    PT_STAMP(2);
     if constexpr (KSPLIT > 1) {
         // groups 1.. park their accumulators in LDS (the stage buffers are dead: every load was waited for and the
         // barrier below follows every wave's last read), group 0 adds them in group order and stores
@@ -1376,7 +1342,6 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
             }
         }
     }
-    PT_STAMP(3);
 #endif
 }
 
@@ -1387,13 +1352,8 @@ inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
     constexpr size_t lds = ring > red ? ring : red;
     static_assert(lds <= 160 * 1024, "LDS capacity");
     auto kern = k_wgrad_dl<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT>;
-    static bool attr_set = false;
-    if (lds > 65536 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;
+    if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(NT), lds, st, a);
     return hipSuccess;
 }

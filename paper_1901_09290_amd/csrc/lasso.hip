@@ -15,28 +15,36 @@
 // filter and the per-chunk column partials in ascending order.
 #include <vector>
 #include "common.h"
+#include "norms.h"
 
 namespace pt {
 
 constexpr int kThreads = 256;
 constexpr int kMaxC = 2048;  // 64 lanes x (8 float4 column groups | 32 scalar column groups) per thread
-constexpr int kMaxJobs = 32;       // layers per launch (kernel-argument table)
+#ifndef PT_NORM_JOBS
+#define PT_NORM_JOBS 46  // 46 x 88 bytes + 16 = 4064 bytes of kernel arguments
+#endif
+constexpr int kMaxJobs = PT_NORM_JOBS;  // layers per launch (the table rides in the kernel arguments)
 
 struct NormJob {
     const float* w;
-    uint16_t* shadow;
-    float* rowsq;     // [K*RS] sum of squares of each (k, rs) row
-    float* colpart;   // [n_chunks][C] per-chunk column sums of squares
+    uint16_t* shadow;   // nullptr: no bf16 copy
     float* out_norm;
     float* in_norm;
+    uint8_t* zero_out;  // nullptr, or [K]: the finish pass also writes (out_norm < thr)
+    uint8_t* zero_in;   // nullptr, or [C]
+    uint32_t ws_off;    // this job's scratch in the workspace, in floats: [K*RS] row sums, then [n_chunks][C] column partials
     int K, RS, C, cpitch;
-    int first_block, n_chunks, rows_per_chunk, txlog2;
-    int fin_first, pad;  // first workgroup of this job in the finish kernel
+    int first_block, n_chunks, rows_per_chunk;
+    int fin_first;      // first workgroup of this job in the finish kernel
 };
 struct NormJobs {
     NormJob j[kMaxJobs];
+    float* ws;
+    float thr;
     int n;
 };
+static_assert(sizeof(NormJobs) <= 4096 || PT_NORM_JOBS > 46, "kernel-argument table");
 
 struct LassoJob {
     const float* w;
@@ -49,17 +57,22 @@ struct LassoJob {
     uint32_t flags;
     int pad;
 };
+constexpr int kMaxLassoJobs = 32;
 struct LassoJobs {
-    LassoJob j[kMaxJobs];
+    LassoJob j[kMaxLassoJobs];
     int n;
 };
 
+// Last job whose first workgroup is <= block (the table is ascending); uniform, so it runs on the scalar unit.
 template <typename Jobs>
 __device__ __forceinline__ int find_job(const Jobs& jobs, int block) {
-    int idx = 0;
-    for (int i = 1; i < jobs.n; ++i)
-        if (block >= jobs.j[i].first_block) idx = i;
-    return idx;
+    int lo = 0, hi = jobs.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs.j[mid].first_block <= block) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
 }
 
 template <int VEC>
@@ -72,82 +85,206 @@ __device__ __forceinline__ void load_vec(const float* p, float (&v)[VEC]) {
     }
 }
 
-// One workgroup = one chunk of whole rows of one layer.
-template <int VEC>
-__global__ __launch_bounds__(kThreads) void k_group_norms_partial(const NormJobs jobs) {
-    constexpr int kColsPerThread = kMaxC / (64 * VEC);
-    __shared__ float colred[kThreads * VEC];
-    const int ji = find_job(jobs, blockIdx.x);
-    const NormJob& J = jobs.j[ji];
-    const int chunk = blockIdx.x - J.first_block;
-    const int tid = threadIdx.x;
-    const int TX = 1 << J.txlog2, TY = kThreads >> J.txlog2;
-    const int tx = tid & (TX - 1), ty = tid >> J.txlog2;
+// Channel-axis layout of a layer for the vector kernel: Lv float4 columns, CG = 1 << cglog2 column groups per
+// thread (1, 2, 4 or 8), TX = 1 << txlog2 lanes across a row; column of (tx, j) = tx + j * TX.
+struct NormLayout {
+    int cglog2, txlog2;
+};
+__host__ __device__ inline NormLayout norm_layout(int C) {
+    const int Lv = (C + 3) >> 2;
+    NormLayout l;
+    l.cglog2 = 0;
+    while ((64 << l.cglog2) < Lv) ++l.cglog2;           // <= 3 for C <= 2048
+    const int per = (Lv + (1 << l.cglog2) - 1) >> l.cglog2;  // columns per group
+    l.txlog2 = 0;
+    while ((1 << l.txlog2) < per) ++l.txlog2;            // <= 6
+    return l;
+}
+
+// One workgroup = one chunk of whole rows of one layer (vector path: 16-byte aligned rows).  A thread keeps eight
+// 16-byte loads in flight: 8 / CG rows at a time, CG column groups each.  Row sums: per thread over its columns,
+// then a shuffle tree over the TX lanes of the row.  Column sums: in registers over the rows a thread visits, then
+// over the rows of a wavefront by shuffles and over the four wavefronts through LDS, all in a fixed order.
+template <int CG>
+__device__ __forceinline__ void norms_partial_body(const NormJob& J, float* __restrict__ ws, int chunk, int txlog2,
+                                                   float (*colred)[1024]) {
+    constexpr int U = 8 / CG;  // rows in flight per thread
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int TX = 1 << txlog2, TY = kThreads >> txlog2;
+    const int tx = tid & (TX - 1), ty = tid >> txlog2;
     const int64_t rows = (int64_t)J.K * J.RS;
     const int64_t r0 = (int64_t)chunk * J.rows_per_chunk;
     const int64_t r1 = min(rows, r0 + J.rows_per_chunk);
     const int C = J.C, cpitch = J.cpitch;
-    const int Lv = (C + VEC - 1) / VEC;
+    const int Lv = (C + 3) >> 2;
     const float* __restrict__ w = J.w;
     uint16_t* __restrict__ shadow = J.shadow;
+    float* __restrict__ rowsq = ws + J.ws_off;
+    float* __restrict__ colpart = rowsq + rows;
 
-    float acc[kColsPerThread][VEC];
+    float acc[CG][4];
+    bool col_ok[CG];
+    int col_n[CG];  // valid elements of this thread's j-th column vector (0: none)
 #pragma unroll
-    for (int j = 0; j < kColsPerThread; ++j)
+    for (int j = 0; j < CG; ++j) {
+        const int cg = tx + j * TX;
+        col_ok[j] = cg < Lv;
+        col_n[j] = col_ok[j] ? min(4, C - cg * 4) : 0;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[j][e] = 0.f;
+        for (int e = 0; e < 4; ++e) acc[j][e] = 0.f;
+    }
 
+    for (int64_t rb = r0 + ty; rb < r1; rb += (int64_t)TY * U) {
+        float4 v[U][CG];
+        // all loads first (rows past the chunk and columns past the row re-read a valid vector and are masked below)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t r = min(rb + (int64_t)u * TY, r1 - 1);
+#pragma unroll
+            for (int j = 0; j < CG; ++j) {
+                const int cg = col_ok[j] ? tx + j * TX : 0;
+                v[u][j] = *reinterpret_cast<const float4*>(w + (size_t)r * cpitch + (size_t)cg * 4);
+            }
+        }
+        float rs[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t r = rb + (int64_t)u * TY;
+            const bool row_ok = r < r1;
+            rs[u] = 0.f;
+#pragma unroll
+            for (int j = 0; j < CG; ++j) {
+                float e4[4] = {v[u][j].x, v[u][j].y, v[u][j].z, v[u][j].w};
+                const int n = row_ok ? col_n[j] : 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float x = e < n ? e4[e] : 0.f;  // pitch padding is not data
+                    e4[e] = x;
+                    const float q = x * x;
+                    acc[j][e] += q;
+                    rs[u] += q;
+                }
+                if (shadow && n > 0) {
+                    const size_t off = (size_t)r * cpitch + (size_t)(tx + j * TX) * 4;
+                    if (n == 4) {
+                        uint2 o;
+                        o.x = cvt_pk_bf16(e4[0], e4[1]);
+                        o.y = cvt_pk_bf16(e4[2], e4[3]);
+                        *reinterpret_cast<uint2*>(shadow + off) = o;
+                    } else {
+                        for (int e = 0; e < n; ++e) shadow[off + e] = f32_to_bf16(e4[e]);
+                    }
+                }
+            }
+        }
+        for (int off = TX >> 1; off > 0; off >>= 1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) rs[u] += __shfl_xor(rs[u], off);
+        }
+        if (tx == 0) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t r = rb + (int64_t)u * TY;
+                if (r < r1) rowsq[r] = rs[u];
+            }
+        }
+    }
+
+    // column partials: rows of one wavefront by shuffles (lanes tx, tx + TX, ... hold the same columns) ...
+    for (int off = TX; off < 64; off <<= 1) {
+#pragma unroll
+        for (int j = 0; j < CG; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[j][e] += __shfl_xor(acc[j][e], off);
+    }
+    // ... then the four wavefronts through LDS in wavefront order, at most four column groups (1024 floats) per round
+    constexpr int ROUNDS = CG > 4 ? CG / 4 : 1, PER = CG > 4 ? 4 : CG;
+#pragma unroll
+    for (int rnd = 0; rnd < ROUNDS; ++rnd) {
+        if (rnd > 0) __syncthreads();
+        if (lane < TX) {
+#pragma unroll
+            for (int jj = 0; jj < PER; ++jj)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) colred[wave][(jj * TX + lane) * 4 + e] = acc[rnd * PER + jj][e];
+        }
+        __syncthreads();
+        // with fewer than 64 lanes per row every wavefront holds full sums of its own rows; all four are added
+        for (int f = tid; f < PER * TX * 4; f += kThreads) {
+            const int c = rnd * PER * TX * 4 + f;
+            if (c < C) colpart[(size_t)chunk * C + c] = ((colred[0][f] + colred[1][f]) + colred[2][f]) + colred[3][f];
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_group_norms_partial_vec(const NormJobs jobs) {
+    __shared__ float colred[4][1024];
+    const int ji = find_job(jobs, blockIdx.x);
+    const NormJob& J = jobs.j[ji];
+    const int chunk = blockIdx.x - J.first_block;
+    const NormLayout l = norm_layout(J.C);
+    switch (l.cglog2) {  // uniform
+        case 0: norms_partial_body<1>(J, jobs.ws, chunk, l.txlog2, colred); break;
+        case 1: norms_partial_body<2>(J, jobs.ws, chunk, l.txlog2, colred); break;
+        case 2: norms_partial_body<4>(J, jobs.ws, chunk, l.txlog2, colred); break;
+        default: norms_partial_body<8>(J, jobs.ws, chunk, l.txlog2, colred); break;
+    }
+}
+
+// Element-wise path (rows that are not 16-byte aligned): one element per lane and column group, one row at a time.
+__global__ __launch_bounds__(kThreads) void k_group_norms_partial_elem(const NormJobs jobs) {
+    constexpr int kColsPerThread = kMaxC / 64;
+    __shared__ float colred[kThreads];
+    const int ji = find_job(jobs, blockIdx.x);
+    const NormJob& J = jobs.j[ji];
+    const int chunk = blockIdx.x - J.first_block;
+    const int tid = threadIdx.x;
+    int txlog2 = 0;
+    while ((1 << txlog2) < J.C && txlog2 < 6) ++txlog2;
+    const int TX = 1 << txlog2, TY = kThreads >> txlog2;
+    const int tx = tid & (TX - 1), ty = tid >> txlog2;
+    const int64_t rows = (int64_t)J.K * J.RS;
+    const int64_t r0 = (int64_t)chunk * J.rows_per_chunk;
+    const int64_t r1 = min(rows, r0 + J.rows_per_chunk);
+    const int C = J.C, cpitch = J.cpitch;
+    const float* __restrict__ w = J.w;
+    uint16_t* __restrict__ shadow = J.shadow;
+    float* __restrict__ rowsq = jobs.ws + J.ws_off;
+    float* __restrict__ colpart = rowsq + rows;
+
+    float acc[kColsPerThread];
+#pragma unroll
+    for (int j = 0; j < kColsPerThread; ++j) acc[j] = 0.f;
     for (int64_t r = r0 + ty; r < r1; r += TY) {
         const size_t roff = (size_t)r * cpitch;
         float rs = 0.f;
 #pragma unroll
         for (int j = 0; j < kColsPerThread; ++j) {
-            const int cg = tx + j * TX;
-            if (cg < Lv) {
-                float v[VEC];
-                load_vec<VEC>(w + roff + (size_t)cg * VEC, v);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    if (cg * VEC + e >= C) v[e] = 0.f;  // pitch padding is not data
-                    const float q = v[e] * v[e];
-                    acc[j][e] += q;
-                    rs += q;
-                }
-                if (shadow) {
-                    if constexpr (VEC == 4) {
-                        if (cg * 4 + 3 < C) {
-                            uint2 o;
-                            o.x = cvt_pk_bf16(v[0], v[1]);
-                            o.y = cvt_pk_bf16(v[2], v[3]);
-                            *reinterpret_cast<uint2*>(shadow + roff + (size_t)cg * 4) = o;
-                        } else {
-                            for (int e = 0; e < 4; ++e)
-                                if (cg * 4 + e < C) shadow[roff + (size_t)cg * 4 + e] = f32_to_bf16(v[e]);
-                        }
-                    } else {
-                        shadow[roff + cg] = f32_to_bf16(v[0]);
-                    }
-                }
+            const int c = tx + j * TX;
+            if (c < C) {
+                const float v = w[roff + c];
+                const float q = v * v;
+                acc[j] += q;
+                rs += q;
+                if (shadow) shadow[roff + c] = f32_to_bf16(v);
             }
         }
         for (int off = TX >> 1; off > 0; off >>= 1) rs += __shfl_xor(rs, off);
-        if (tx == 0) J.rowsq[r] = rs;
+        if (tx == 0) rowsq[r] = rs;
     }
-
     // column partials: across the TY row groups of the workgroup, in ty order, one column group at a time
 #pragma unroll
     for (int j = 0; j < kColsPerThread; ++j) {
-        if (j * TX >= Lv) break;  // uniform
+        if (j * TX >= C) break;  // uniform
         __syncthreads();
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) colred[(ty * TX + tx) * VEC + e] = acc[j][e];
+        colred[ty * TX + tx] = acc[j];
         __syncthreads();
-        for (int f = tid; f < TX * VEC; f += kThreads) {
-            const int c = j * TX * VEC + f;
+        for (int f = tid; f < TX; f += kThreads) {
+            const int c = j * TX + f;
             if (c < C) {
                 float s = 0.f;
-                for (int y = 0; y < TY; ++y) s += colred[y * TX * VEC + f];
-                J.colpart[(size_t)chunk * C + c] = s;
+                for (int y = 0; y < TY; ++y) s += colred[y * TX + f];
+                colpart[(size_t)chunk * C + c] = s;
             }
         }
     }
@@ -155,27 +292,39 @@ __global__ __launch_bounds__(kThreads) void k_group_norms_partial(const NormJobs
 
 // Sixteen lanes per group (K filters, then C input channels of each job): the lanes stride over the R*S row
 // sums of a filter / the per-chunk partials of a channel, then a fixed shuffle tree adds the 16 lane sums.
-// The order of additions depends only on the shapes, so results are run-to-run identical.
+// The order of additions depends only on the shapes, so results are run-to-run identical.  Jobs with mask
+// pointers also get their zero masks here: zero[g] = (norm[g] < thr), the comparison of pt_zero_groups.
 constexpr int kFinLanes = 16, kFinGroups = kThreads / kFinLanes;
 __global__ __launch_bounds__(kThreads) void k_group_norms_finish(const NormJobs jobs) {
-    int ji = 0;
-    for (int i = 1; i < jobs.n; ++i)
-        if ((int)blockIdx.x >= jobs.j[i].fin_first) ji = i;
-    const NormJob& J = jobs.j[ji];
+    int lo = 0, hi = jobs.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs.j[mid].fin_first <= (int)blockIdx.x) lo = mid;
+        else hi = mid - 1;
+    }
+    const NormJob& J = jobs.j[lo];
+    const float* __restrict__ rowsq = jobs.ws + J.ws_off;
+    const float* __restrict__ colpart = rowsq + (int64_t)J.K * J.RS;
     const int l = threadIdx.x & (kFinLanes - 1);
     const int g = (blockIdx.x - J.fin_first) * kFinGroups + (threadIdx.x / kFinLanes);
     const bool live = g < J.K + J.C;
     float s = 0.f;
     if (live && g < J.K) {
-        for (int t = l; t < J.RS; t += kFinLanes) s += J.rowsq[(size_t)g * J.RS + t];
+        for (int t = l; t < J.RS; t += kFinLanes) s += rowsq[(size_t)g * J.RS + t];
     } else if (live) {
         const int c = g - J.K;
-        for (int b = l; b < J.n_chunks; b += kFinLanes) s += J.colpart[(size_t)b * J.C + c];
+        for (int b = l; b < J.n_chunks; b += kFinLanes) s += colpart[(size_t)b * J.C + c];
     }
     for (int off = kFinLanes / 2; off > 0; off >>= 1) s += __shfl_xor(s, off);
     if (live && l == 0) {
-        if (g < J.K) J.out_norm[g] = sqrtf(s);
-        else J.in_norm[g - J.K] = sqrtf(s);
+        const float nrm = sqrtf(s);
+        if (g < J.K) {
+            J.out_norm[g] = nrm;
+            if (J.zero_out) J.zero_out[g] = nrm < jobs.thr ? 1 : 0;
+        } else {
+            J.in_norm[g - J.K] = nrm;
+            if (J.zero_in) J.zero_in[g - J.K] = nrm < jobs.thr ? 1 : 0;
+        }
     }
 }
 
@@ -261,12 +410,12 @@ struct ChunkPlan {
     int txlog2, rows_per_chunk, n_chunks;
 };
 
+// Gradient / optimizer pass and the element-wise norms pass: TX lanes across a row, about 16 K elements per workgroup.
 static ChunkPlan plan_chunks(int64_t rows, int C, bool vec) {
     const int Lv = vec ? (C + 3) / 4 : C;
     int l = 0;
     while ((1 << l) < Lv && l < 6) ++l;
     const int TY = kThreads >> l;
-    // about 16 K elements per workgroup, a whole number of TY-row passes
     int64_t rpc = ceil_div(16384, C);
     rpc = round_up(rpc, TY);
     ChunkPlan p;
@@ -276,24 +425,102 @@ static ChunkPlan plan_chunks(int64_t rows, int C, bool vec) {
     return p;
 }
 
-static bool norms_vec_ok(const pt_layer_weights& L) {
-    return (L.w_cpitch % 4 == 0) && (((uintptr_t)L.w & 15) == 0) && (!L.w_shadow || ((uintptr_t)L.w_shadow & 7) == 0) &&
-           L.C <= kMaxC;
+// Vector norms pass: a workgroup streams whole batches of TY * U rows (256 threads x eight 16-byte loads, 8 K
+// elements when every lane has a column), kNormBatches of them per chunk.
+constexpr int kNormBatches = 2;
+static ChunkPlan plan_norm_chunks(int64_t rows, int C) {
+    const NormLayout l = norm_layout(C);
+    const int batch_rows = (kThreads >> l.txlog2) * (8 >> l.cglog2);
+    ChunkPlan p;
+    p.txlog2 = l.txlog2;
+    p.rows_per_chunk = batch_rows * kNormBatches;
+    p.n_chunks = (int)ceil_div(rows, p.rows_per_chunk);
+    return p;
 }
 
-static int32_t check_layer(const pt_layer_weights& L) {
-    if (!L.w) return PT_ERR_NULL;
-    if (L.K <= 0 || L.RS <= 0 || L.C <= 0 || L.w_cpitch < L.C) return PT_ERR_SHAPE;
+static bool norms_vec_ok(const NormLayer& L) {
+    return (L.cpitch % 4 == 0) && (((uintptr_t)L.w & 15) == 0) && (!L.shadow || ((uintptr_t)L.shadow & 7) == 0) && L.C <= kMaxC;
+}
+
+int32_t check_norm_layer(const NormLayer& L) {
+    if (!L.w || !L.out_norm || !L.in_norm) return PT_ERR_NULL;
+    if (L.K <= 0 || L.RS <= 0 || L.C <= 0 || L.cpitch < L.C) return PT_ERR_SHAPE;
     if (L.C > kMaxC) return PT_ERR_UNSUPPORTED;  // register tile of the column sums
+    if ((int64_t)L.K * L.RS >= (1ll << 31)) return PT_ERR_UNSUPPORTED;
     return PT_OK;
 }
 
 // Workspace of one layer: row sums + per-chunk column partials, sized for whichever loader is used.
-static size_t layer_ws_bytes(const pt_layer_weights& L) {
-    const int64_t rows = (int64_t)L.K * L.RS;
-    const ChunkPlan a = plan_chunks(rows, L.C, true), b = plan_chunks(rows, L.C, false);
+size_t norm_layer_ws_bytes(int32_t K, int32_t RS, int32_t C) {
+    const int64_t rows = (int64_t)K * RS;
+    const ChunkPlan a = plan_norm_chunks(rows, C), b = plan_chunks(rows, C, false);
     const int n_chunks = a.n_chunks > b.n_chunks ? a.n_chunks : b.n_chunks;
-    return (size_t)round_up((rows + (int64_t)n_chunks * L.C) * 4, 256);
+    return (size_t)round_up((rows + (int64_t)n_chunks * C) * 4, 256);
+}
+
+// Group norms (and optionally zero masks) of n layers: one partial + one finish launch per kMaxJobs layers of a
+// loader kind.  The workspace is split between the layers in array order.
+int32_t launch_norms(const NormLayer* layers, int n, void* ws, size_t ws_bytes, float thr, hipStream_t st) {
+    size_t need = 0;
+    for (int i = 0; i < n; ++i) {
+        const int32_t rc = check_norm_layer(layers[i]);
+        if (rc != PT_OK) return rc;
+        need += norm_layer_ws_bytes(layers[i].K, layers[i].RS, layers[i].C);
+    }
+    if (!ws) return PT_ERR_NULL;
+    if (ws_bytes < need) return PT_ERR_WORKSPACE;
+    if (((uintptr_t)ws & 15) != 0) return PT_ERR_SHAPE;
+    if (need / 4 >= (1ull << 32)) return PT_ERR_UNSUPPORTED;
+    for (int pass = 0; pass < 2; ++pass) {
+        const bool want_vec = pass == 0;
+        NormJobs jobs;
+        jobs.n = 0;
+        jobs.ws = (float*)ws;
+        jobs.thr = thr;
+        int64_t blocks = 0, fin_blocks = 0;
+        auto flush = [&]() -> int32_t {
+            if (jobs.n == 0) return PT_OK;
+            if (want_vec) hipLaunchKernelGGL(k_group_norms_partial_vec, dim3((unsigned)blocks), dim3(kThreads), 0, st, jobs);
+            else hipLaunchKernelGGL(k_group_norms_partial_elem, dim3((unsigned)blocks), dim3(kThreads), 0, st, jobs);
+            int32_t rc = launch_status();
+            if (rc != PT_OK) return rc;
+            hipLaunchKernelGGL(k_group_norms_finish, dim3((unsigned)fin_blocks), dim3(kThreads), 0, st, jobs);
+            jobs.n = 0;
+            blocks = 0;
+            fin_blocks = 0;
+            return launch_status();
+        };
+        size_t off = 0;  // bytes
+        for (int i = 0; i < n; ++i) {
+            const NormLayer& L = layers[i];
+            const size_t bytes = norm_layer_ws_bytes(L.K, L.RS, L.C);
+            if (norms_vec_ok(L) == want_vec) {
+                const int64_t rows = (int64_t)L.K * L.RS;
+                const ChunkPlan cp = want_vec ? plan_norm_chunks(rows, L.C) : plan_chunks(rows, L.C, false);
+                if (blocks + cp.n_chunks > 0x3fffffff) {
+                    const int32_t rc = flush();
+                    if (rc != PT_OK) return rc;
+                }
+                NormJob& J = jobs.j[jobs.n++];
+                J.w = L.w; J.shadow = L.shadow; J.out_norm = L.out_norm; J.in_norm = L.in_norm;
+                J.zero_out = L.zero_out; J.zero_in = L.zero_in;
+                J.ws_off = (uint32_t)(off / 4);
+                J.K = L.K; J.RS = L.RS; J.C = L.C; J.cpitch = L.cpitch;
+                J.first_block = (int)blocks; J.n_chunks = cp.n_chunks; J.rows_per_chunk = cp.rows_per_chunk;
+                J.fin_first = (int)fin_blocks;
+                blocks += cp.n_chunks;
+                fin_blocks += ceil_div((int64_t)L.K + L.C, kFinGroups);
+                if (jobs.n == kMaxJobs) {
+                    const int32_t rc = flush();
+                    if (rc != PT_OK) return rc;
+                }
+            }
+            off += bytes;
+        }
+        const int32_t rc = flush();
+        if (rc != PT_OK) return rc;
+    }
+    return PT_OK;
 }
 
 // Value of the regulariser (GroupLassoReg of Alg. 1): the sum of the enabled group norms of up to
@@ -344,7 +571,7 @@ extern "C" int32_t pt_group_norms_batched_workspace_bytes(const pt_layer_weights
     size_t total = 0;
     for (int i = 0; i < n; ++i) {
         if (layers[i].K <= 0 || layers[i].RS <= 0 || layers[i].C <= 0) return PT_ERR_SHAPE;
-        total += layer_ws_bytes(layers[i]);
+        total += norm_layer_ws_bytes(layers[i].K, layers[i].RS, layers[i].C);
     }
     *bytes = total;
     return PT_OK;
@@ -355,64 +582,38 @@ extern "C" int32_t pt_group_norms_batched(const pt_layer_weights* layers, int32_
     if (n < 0) return PT_ERR_SHAPE;
     if (n == 0) return PT_OK;
     if (!layers || !ws) return PT_ERR_NULL;
-    size_t need = 0;
+    std::vector<NormLayer> v((size_t)n);
     for (int i = 0; i < n; ++i) {
-        int32_t rc = check_layer(layers[i]);
-        if (rc != PT_OK) return rc;
-        if (!layers[i].out_norm || !layers[i].in_norm) return PT_ERR_NULL;
-        need += layer_ws_bytes(layers[i]);
+        const pt_layer_weights& L = layers[i];
+        v[i] = NormLayer{L.w, L.out_norm, L.in_norm, L.w_shadow, nullptr, nullptr, L.K, L.RS, L.C, L.w_cpitch};
     }
-    if (ws_bytes < need) return PT_ERR_WORKSPACE;
-    if (((uintptr_t)ws & 15) != 0) return PT_ERR_SHAPE;
-    hipStream_t st = (hipStream_t)stream;
-    char* wsp = (char*)ws;
-    // layers are grouped by loader kind (vector / element-wise) and sent kMaxJobs at a time
-    for (int pass = 0; pass < 2; ++pass) {
-        const bool want_vec = pass == 0;
-        NormJobs jobs;
-        jobs.n = 0;
-        int blocks = 0, fin_blocks = 0;
-        auto flush = [&]() -> int32_t {
-            if (jobs.n == 0) return PT_OK;
-            if (want_vec)
-                hipLaunchKernelGGL(k_group_norms_partial<4>, dim3(blocks), dim3(kThreads), 0, st, jobs);
-            else
-                hipLaunchKernelGGL(k_group_norms_partial<1>, dim3(blocks), dim3(kThreads), 0, st, jobs);
-            int32_t rc = launch_status();
-            if (rc != PT_OK) return rc;
-            hipLaunchKernelGGL(k_group_norms_finish, dim3((unsigned)fin_blocks), dim3(kThreads), 0, st, jobs);
-            jobs.n = 0;
-            blocks = 0;
-            fin_blocks = 0;
-            return launch_status();
-        };
-        char* p = wsp;
-        for (int i = 0; i < n; ++i) {
-            const pt_layer_weights& L = layers[i];
-            const size_t bytes = layer_ws_bytes(L);
-            const bool vec = norms_vec_ok(L);
-            if (vec == want_vec) {
-                const int64_t rows = (int64_t)L.K * L.RS;
-                const ChunkPlan cp = plan_chunks(rows, L.C, vec);
-                NormJob& J = jobs.j[jobs.n++];
-                J.w = L.w; J.shadow = L.w_shadow; J.out_norm = L.out_norm; J.in_norm = L.in_norm;
-                J.rowsq = (float*)p; J.colpart = (float*)p + rows;
-                J.K = L.K; J.RS = L.RS; J.C = L.C; J.cpitch = L.w_cpitch;
-                J.first_block = blocks; J.n_chunks = cp.n_chunks; J.rows_per_chunk = cp.rows_per_chunk; J.txlog2 = cp.txlog2;
-                J.fin_first = fin_blocks; J.pad = 0;
-                blocks += cp.n_chunks;
-                fin_blocks += (int)ceil_div(L.K + L.C, kFinGroups);
-                if (jobs.n == kMaxJobs) {
-                    int32_t rc = flush();
-                    if (rc != PT_OK) return rc;
-                }
-            }
-            p += bytes;
-        }
-        int32_t rc = flush();
-        if (rc != PT_OK) return rc;
+    return launch_norms(v.data(), n, ws, ws_bytes, 0.f, (hipStream_t)stream);
+}
+
+extern "C" int32_t pt_group_norms_detect_batched_workspace_bytes(const pt_layer_detect* layers, int32_t n, size_t* bytes) {
+    if (!bytes || (n > 0 && !layers)) return PT_ERR_NULL;
+    if (n < 0) return PT_ERR_SHAPE;
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        if (layers[i].K <= 0 || layers[i].RS <= 0 || layers[i].C <= 0) return PT_ERR_SHAPE;
+        total += norm_layer_ws_bytes(layers[i].K, layers[i].RS, layers[i].C);
     }
+    *bytes = total;
     return PT_OK;
+}
+
+extern "C" int32_t pt_group_norms_detect_batched(const pt_layer_detect* layers, int32_t n, float thr, void* ws,
+                                                 size_t ws_bytes, void* stream) {
+    if (n < 0) return PT_ERR_SHAPE;
+    if (n == 0) return PT_OK;
+    if (!layers || !ws) return PT_ERR_NULL;
+    std::vector<NormLayer> v((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        const pt_layer_detect& L = layers[i];
+        if (!L.zero_out || !L.zero_in) return PT_ERR_NULL;
+        v[i] = NormLayer{L.w, L.out_norm, L.in_norm, nullptr, L.zero_out, L.zero_in, L.K, L.RS, L.C, L.w_cpitch};
+    }
+    return launch_norms(v.data(), n, ws, ws_bytes, thr, (hipStream_t)stream);
 }
 
 // Shared launcher of the gradient pass and of the optimizer step (mom == nullptr in every layer <=> gradient pass).
@@ -457,7 +658,7 @@ static int32_t launch_lasso(const LassoLayer* layers, int n, bool update, float 
             J.first_block = blocks; J.n_chunks = cp.n_chunks; J.rows_per_chunk = cp.rows_per_chunk; J.txlog2 = cp.txlog2;
             J.flags = L.flags; J.pad = 0;
             blocks += cp.n_chunks;
-            if (jobs.n == kMaxJobs) {
+            if (jobs.n == kMaxLassoJobs) {
                 int32_t rc = flush();
                 if (rc != PT_OK) return rc;
             }
@@ -509,9 +710,7 @@ extern "C" int32_t pt_sgd_momentum_lasso_batched(const pt_layer_update* layers, 
 extern "C" int32_t pt_group_norms_workspace_bytes(int32_t K, int32_t RS, int32_t C, size_t* bytes) {
     if (!bytes) return PT_ERR_NULL;
     if (K <= 0 || RS <= 0 || C <= 0) return PT_ERR_SHAPE;
-    pt_layer_weights L{};
-    L.K = K; L.RS = RS; L.C = C; L.w_cpitch = C;
-    *bytes = layer_ws_bytes(L);
+    *bytes = norm_layer_ws_bytes(K, RS, C);
     return PT_OK;
 }
 

@@ -568,15 +568,10 @@ static bool gather_streams(const uint16_t* x, int32_t x_cpitch, int32_t Cp, cons
 }
 static int32_t launch_gather_jobs(GatherJobs& t, hipStream_t st) {
     if (t.n == 0) return PT_OK;
-    static bool attr_set = false;  // one-time opt-in to 64 KiB of dynamic LDS
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_compact_nhwc_lds),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kGatherChunk);
-        if (e != hipSuccess) {
-            set_hip_error(e);
-            return PT_ERR_LAUNCH;
-        }
-        attr_set = true;
+    static LdsOptIn opt_in;  // 64 KiB of dynamic LDS
+    if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(k_compact_nhwc_lds), 2 * kGatherChunk, 0); e != hipSuccess) {
+        set_hip_error(e);
+        return PT_ERR_LAUNCH;
     }
     const unsigned grid = (unsigned)(t.total_chunks < 512 ? t.total_chunks : 512);  // two resident workgroups per CU
     hipLaunchKernelGGL(k_compact_nhwc_lds, dim3(grid), dim3(kGatherThreads), 2 * kGatherChunk, st, t);

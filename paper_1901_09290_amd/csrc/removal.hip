@@ -1,4 +1,4 @@
-// Layer removal after a reconfiguration plan (Sec. 3.1, "Layer Removal by Overlapping Regularization Groups"; the
+// Layer removal after a reconfiguration plan (Sec. 4.1, "Layer Removal by Overlapping Regularization Groups"; the
 // removed-layer counts of the result tables): host-only graph logic, no device work.
 //
 // A channel edge with no survivors carries nothing, so every layer writing it and every layer reading it drops out of

@@ -204,12 +204,15 @@ class Network:
             main, side = torch.cuda.current_stream(), self.sides[0]
             side.wait_stream(main)
             B.group_norms_batched(self.norm_jobs_head, self.ws_norms)
+            head_ready = torch.cuda.Event()
+            head_ready.record(main)
             with torch.cuda.stream(side):
                 if self.norm_jobs_tail is not None:
                     B.group_norms_batched(self.norm_jobs_tail, self.ws_norms_tail)
                 tail_ready = torch.cuda.Event()
                 tail_ready.record(side)
                 if self.crsk_jobs is not None:
+                    side.wait_event(head_ready)    # the copies read every layer's bf16 weights, the head layers' too
                     B.weights_to_crsk_batched(self.crsk_jobs)
             for i, l in enumerate(self.layers):
                 if i == self.norm_head:
@@ -356,6 +359,9 @@ class ReconfigModel:
             for i, s in enumerate(self.specs)])
         self.ws = torch.empty(max(256, B.group_norms_batched_workspace_bytes(self.norm_jobs)), dtype=torch.uint8,
                               device=DEV)
+        self.detect_jobs = (B.LayerDetect * len(self.specs))(*[
+            B.layer_detect(self.w[i], s.K, s.R * s.S, s.C, pitch8(s.C), self.on[i], self.inn[i], self.zo[i], self.zi[i])
+            for i, s in enumerate(self.specs)])
         # outputs sized for "nothing pruned"; the sweep writes the compacted tensors at their own pitch
         self.w_out = [torch.zeros_like(t) for t in self.w]
         self.mom_out = [torch.zeros_like(t) for t in self.mom]
@@ -373,8 +379,13 @@ class ReconfigModel:
         self.edge_jobs = (B.EdgePlan * len(self.edges))(*self._edge_structs)
 
     def detect(self, thr: float) -> None:
-        """Group norms and zero masks of every layer, then keep mask + survivor list of every edge: four
-        multi-job calls, all asynchronous."""
+        """Group norms and zero masks of every layer (the masks come out of the norms' finish pass), then keep
+        mask + survivor list of every edge: two multi-job calls, all asynchronous."""
+        B.group_norms_detect_batched(self.detect_jobs, thr, self.ws)
+        B.reconcile_plan_batched(self.edge_jobs)
+
+    def detect_separate(self, thr: float) -> None:
+        """The same detection with the zero masks from a call of their own."""
         B.group_norms_batched(self.norm_jobs, self.ws)
         B.zero_groups_batched(self.mask_jobs, thr)
         B.reconcile_plan_batched(self.edge_jobs)

@@ -138,26 +138,39 @@ def test_narrow_outputs_over_very_many_pixels(case):
 
 
 FUSED_LASSO = [
-    # N  H   W   C    K   R st pad   flags        reductions split over many workgroups, and single-slab ones
-    ((2, 12, 12, 64, 64, 3, 1, 1), 3),
-    ((3, 9, 11, 24, 40, 3, 1, 1), 3),
-    ((2, 14, 14, 128, 96, 1, 1, 0), 1),
-    ((2, 15, 15, 40, 136, 3, 2, 1), 2),
-    ((2, 18, 18, 3, 16, 7, 2, 3), 1),          # a first layer: input groups exempt
-    ((2, 10, 10, 37, 51, 3, 1, 1), 3),         # ragged counts
-    ((1, 7, 7, 520, 520, 3, 1, 1), 3),         # more tiles than the split target: one slab, no split
-    ((5, 128, 130, 64, 64, 1, 1, 0), 3),       # very many pixels
+    # N  H   W   C    K   R st pad   flags  path    reductions split over many workgroups, and single-slab ones
+    ((2, 12, 12, 64, 64, 3, 1, 1), 3, None),
+    ((3, 9, 11, 24, 40, 3, 1, 1), 3, None),
+    ((2, 14, 14, 128, 96, 1, 1, 0), 1, None),
+    ((2, 15, 15, 40, 136, 3, 2, 1), 2, None),
+    ((2, 18, 18, 3, 16, 7, 2, 3), 1, None),          # a first layer: input groups exempt
+    ((2, 10, 10, 37, 51, 3, 1, 1), 3, None),         # ragged counts
+    ((1, 7, 7, 520, 520, 3, 1, 1), 3, "none"),       # more tiles than the split target: one slab, no split
+    ((5, 128, 130, 64, 64, 1, 1, 0), 3, "deep"),     # very many pixels: many slices over few outputs
+    # few slices over many outputs (the late layers of a deep network): the wide reduction adds the regulariser
+    ((8, 14, 14, 256, 256, 3, 1, 1), 3, "wide"),
+    ((8, 14, 14, 203, 171, 3, 1, 1), 3, "wide"),     # the same with ragged counts
+    ((8, 14, 14, 203, 171, 3, 1, 1), 1, "wide"),
+    ((8, 14, 14, 203, 171, 3, 1, 1), 2, "wide"),
+    ((16, 14, 14, 520, 264, 1, 1, 0), 3, "wide"),
 ]
 
 
-@pytest.mark.parametrize("case,flags", FUSED_LASSO, ids=lambda c: "x".join(map(str, c)) if isinstance(c, tuple) else str(c))
+@pytest.mark.parametrize("case,flags,path", FUSED_LASSO,
+                         ids=lambda c: "x".join(map(str, c)) if isinstance(c, tuple) else str(c))
 @pytest.mark.parametrize("padded", [True, False])
-def test_weight_gradient_with_regulariser_folded_in(case, flags, padded):
+def test_weight_gradient_with_regulariser_folded_in(case, flags, path, padded):
     """pt_conv_bwd_weight_lasso against the oracle's weight gradient plus the oracle's lasso gradient (convolution
-    tolerance on the sum, 1e-5 on the added term itself), and against the two separate GPU calls."""
+    tolerance on the sum, 1e-5 on the added term itself), and against the two separate GPU calls.  Where a case is
+    meant for one of the reduction passes, the library's own plan must say that it takes it."""
     from gpu_util import CONV_TOL, DEV, F32_TOL, dev_bf16, dev_f32, pitch8, rel_err, workspace
     from paper_1901_09290_amd import binding as B
     spec = _spec(*case)
+    if path is not None and padded:
+        info = B.conv_bwd_weight_plan(B.desc_of(spec, pitch8(spec.C), pitch8(spec.K), pitch8(spec.C)), True)
+        kinds = {"none": B.WGRAD_REDUCE_NONE, "deep": B.WGRAD_REDUCE_DEEP, "wide": B.WGRAD_REDUCE_WIDE}
+        assert info.reduce_kind == kinds[path], (case, info.splits, info.tiles, info.reduce_kind)
+        assert (info.splits == 1) == (path == "none")
     rng = np.random.Generator(np.random.PCG64(800 + sum(case) + flags))
     t = wl.conv_tensors(spec, rng, want=("x", "dy"))
     w = (rng.standard_normal((spec.K, spec.R, spec.S, spec.C)) * 0.05).astype(np.float32)

@@ -18,7 +18,8 @@ from paper_1901_09290_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-N_SAMPLES = 160
+N_RANDOM = 4000        # random elements per tensor, on top of the corners and of one element per tile block
+LAMBDA_VISIBLE = 1e3   # makes the regulariser's term comparable to the data gradient (|w| ~ 0.05, |dw| ~ 10^2)
 
 
 def _corner_and_random(shape, n, rng):
@@ -31,44 +32,93 @@ def _corner_and_random(shape, n, rng):
     return np.unique(idx)
 
 
+def _block_samples(rows, cols, rng, rb=64, cb=32):
+    """One random element in every rb x cb block of a [rows, cols] matrix, as flat indices: every output tile of
+    every launch (tiles are multiples of 64 rows and 32 columns) is seen, its ragged last ones included."""
+    r0 = np.arange(0, rows, rb, dtype=np.int64)
+    c0 = np.arange(0, cols, cb, dtype=np.int64)
+    R, Cc = np.meshgrid(r0, c0, indexing="ij")
+    r = R + (rng.random(R.shape) * np.minimum(rb, rows - R)).astype(np.int64)
+    c = Cc + (rng.random(Cc.shape) * np.minimum(cb, cols - Cc)).astype(np.int64)
+    return (r * cols + c).reshape(-1)
+
+
+def _samples(shape, rows, cols, rng):
+    return np.unique(np.concatenate([_corner_and_random(shape, N_RANDOM, rng), _block_samples(rows, cols, rng)]))
+
+
 def _sampled_err(got, ref):
     """The conv tolerance metric on a sample: rms is taken over the sampled reference values."""
     from gpu_util import rel_err
     return rel_err(got, ref)
 
 
-def _check_layer_sampled(spec, seed):
-    from gpu_util import CONV_TOL, host_bf16
+def _run_layer_as_the_step_does(spec, t, lam):
+    """One layer through the calls Network.train_step makes for it: norms (+ bf16 weights), forward, the k-innermost
+    filter copy and the workspace-free input gradient, and the weight gradient with the regulariser folded in."""
     from paper_1901_09290_amd import harness as hz
-    rng = np.random.Generator(np.random.PCG64(seed))
-    t = wl.conv_tensors(spec, rng)
     layer = hz.ConvLayer(spec, host=t)
     ws = hz.make_workspace([layer])
-    layer.norms(ws)          # writes the bf16 weights the convolutions read
+    layer.norms(ws)
     layer.fwd(ws)
-    if layer.w_crsk is not None:   # the step converts the filter bank once and runs the workspace-free input gradient
+    if layer.w_crsk is not None:
         B.weights_to_crsk_batched([B.layer_crsk(layer.w_bf16, layer.w_crsk, spec.K, layer.RS, spec.C, layer.wp)])
         layer.bwd_data_crsk()
-    layer.bwd_weight(ws)
+    layer.bwd_weight_lasso(ws, lam)
     torch.cuda.synchronize()
-    s = oracle.shape_of(spec)
-    # the shadow copy is the exact bf16 image of the master weights (already on the bf16 grid)
-    assert np.array_equal(host_bf16(layer.w_bf16, spec.C), t["w"])
-    y = host_bf16(layer.y, spec.K).reshape(-1)
-    iy = _corner_and_random((spec.N, spec.P, spec.Q, spec.K), N_SAMPLES, rng)
-    assert _sampled_err(y[iy], oracle.conv_fwd_at(s, t["x"], t["w"], iy)) <= CONV_TOL, spec
-    if layer.dx is not None:
-        dx = host_bf16(layer.dx, spec.C).reshape(-1)
-        ix = _corner_and_random((spec.N, spec.H, spec.W, spec.C), N_SAMPLES, rng)
-        assert _sampled_err(dx[ix], oracle.conv_bwd_data_at(s, t["dy"], t["w"], ix)) <= CONV_TOL, spec
-    dw = layer.dw.cpu().numpy()[..., : spec.C].reshape(-1)
-    iw = _corner_and_random((spec.K, spec.R, spec.S, spec.C), N_SAMPLES, rng)
-    assert _sampled_err(dw[iw], oracle.conv_bwd_weight_at(s, t["x"], t["dy"], iw)) <= CONV_TOL, spec
+    return layer
+
+
+def _lasso_term(t, spec, layer, lam):
+    ron, rin = oracle.group_norms(t["w"])
+    return oracle.group_lasso_grad(t["w"], ron, rin, lam, layer.lasso_flags, np.zeros((spec.K, spec.R, spec.S, spec.C)))
+
+
+def _check_padding_stays_zero(layer, spec):
     # pitch padding of the outputs stays zero (the harness allocates zero-filled buffers)
     if layer.yp != spec.K:
         assert not bool(layer.y[..., spec.K:].any())
     if layer.wp != spec.C:
         assert not bool(layer.dw[..., spec.C:].any())
+    if layer.dx is not None and layer.xp != spec.C:
+        assert not bool(layer.dx[..., spec.C:].any())
+
+
+def _check_layer_sampled(spec, seed):
+    from gpu_util import CONV_TOL, host_bf16
+    rng = np.random.Generator(np.random.PCG64(seed))
+    t = wl.conv_tensors(spec, rng)
+    layer = _run_layer_as_the_step_does(spec, t, LAMBDA_VISIBLE)
+    s = oracle.shape_of(spec)
+    # the shadow copy is the exact bf16 image of the master weights (already on the bf16 grid)
+    assert np.array_equal(host_bf16(layer.w_bf16, spec.C), t["w"])
+    y = host_bf16(layer.y, spec.K).reshape(-1)
+    iy = _samples((spec.N, spec.P, spec.Q, spec.K), spec.N * spec.P * spec.Q, spec.K, rng)
+    assert _sampled_err(y[iy], oracle.conv_fwd_at(s, t["x"], t["w"], iy)) <= CONV_TOL, spec
+    if layer.dx is not None:
+        dx = host_bf16(layer.dx, spec.C).reshape(-1)
+        ix = _samples((spec.N, spec.H, spec.W, spec.C), spec.N * spec.H * spec.W, spec.C, rng)
+        assert _sampled_err(dx[ix], oracle.conv_bwd_data_at(s, t["dy"], t["w"], ix)) <= CONV_TOL, spec
+    dw = layer.dw.cpu().numpy()[..., : spec.C].reshape(-1)
+    iw = _samples((spec.K, spec.R, spec.S, spec.C), spec.K, spec.R * spec.S * spec.C, rng)
+    ref = oracle.conv_bwd_weight_at(s, t["x"], t["dy"], iw) + _lasso_term(t, spec, layer, LAMBDA_VISIBLE).reshape(-1)[iw]
+    assert _sampled_err(dw[iw], ref) <= CONV_TOL, spec
+    _check_padding_stays_zero(layer, spec)
+
+
+def _check_layer_whole(spec, seed):
+    """Whole tensors of one layer, run as the step runs it, against the oracle."""
+    from gpu_util import CONV_TOL, host_bf16, rel_err
+    rng = np.random.Generator(np.random.PCG64(seed))
+    t = wl.conv_tensors(spec, rng)
+    layer = _run_layer_as_the_step_does(spec, t, LAMBDA_VISIBLE)
+    s = oracle.shape_of(spec)
+    assert rel_err(host_bf16(layer.y, spec.K), oracle.conv_fwd(s, t["x"], t["w"])) <= CONV_TOL, spec
+    if layer.dx is not None:
+        assert rel_err(host_bf16(layer.dx, spec.C), oracle.conv_bwd_data(s, t["dy"], t["w"])) <= CONV_TOL, spec
+    ref = oracle.conv_bwd_weight(s, t["x"], t["dy"]) + _lasso_term(t, spec, layer, LAMBDA_VISIBLE)
+    assert rel_err(layer.dw.cpu().numpy()[..., : spec.C], ref) <= CONV_TOL, spec
+    _check_padding_stays_zero(layer, spec)
 
 
 def _cfg3_shapes():
@@ -91,6 +141,60 @@ def test_cfg3_resnet50_batch64_sampled(i):
 @pytest.mark.parametrize("i", range(len(_cfg4_shapes())))
 def test_cfg4_pruned_ragged_widths_batch64_sampled(i):
     _check_layer_sampled(_cfg4_shapes()[i], seed=3000 + i)
+
+
+def _at_batch(spec, N):
+    import dataclasses
+    return dataclasses.replace(spec, N=N)
+
+
+def test_cfg3_resnet50_shapes_batch2_whole_tensors():
+    """Every distinct full-width layer shape at batch 2: whole y / dx / dw, no sampling."""
+    for i, spec in enumerate(_cfg3_shapes()):
+        _check_layer_whole(_at_batch(spec, 2), seed=2500 + i)
+
+
+def test_cfg4_pruned_shapes_batch2_whole_tensors():
+    for i, spec in enumerate(_cfg4_shapes()):
+        _check_layer_whole(_at_batch(spec, 2), seed=3500 + i)
+
+
+def test_cfg2_resnet32_train_step_on_side_streams_against_oracle():
+    """Network.train_step as the benchmark runs it (norms split over two streams, k-innermost filter copies, weight
+    gradients with the regulariser folded in on four side streams, zero padding vouched for) on the whole ResNet-32
+    stack at batch 128: every layer's norms, y, dx and dw against the oracle.  Then the weights change (one optimizer
+    step) and a second step must see the new weights everywhere, the k-innermost copies of the first layers too."""
+    from gpu_util import CONV_TOL, F32_TOL, host_bf16, rel_err
+    from paper_1901_09290_amd import harness as hz
+    specs, _ = wl.resnet32_layers(N=128)
+    rng = np.random.Generator(np.random.PCG64(1))
+    host = [wl.conv_tensors(s, rng) for s in specs]
+    net = hz.Network([hz.ConvLayer(s, host=t) for s, t in zip(specs, host)])
+    assert net.overlap_wgrad and net.fuse_lasso and net.norm_jobs_tail is not None
+    lam = 50.0
+
+    def check(weights):
+        for l, t, w in zip(net.layers, host, weights):
+            s, o = l.spec, oracle.shape_of(l.spec)
+            wb = wl.to_bf16_grid(w)
+            ron, rin = oracle.group_norms(w)
+            assert rel_err(l.out_norm.cpu().numpy(), ron) <= F32_TOL and rel_err(l.in_norm.cpu().numpy(), rin) <= F32_TOL
+            assert np.array_equal(host_bf16(l.w_bf16, s.C), wb)
+            assert rel_err(host_bf16(l.y, s.K), oracle.conv_fwd(o, t["x"], wb)) <= CONV_TOL, s
+            if l.dx is not None:
+                assert rel_err(host_bf16(l.dx, s.C), oracle.conv_bwd_data(o, t["dy"], wb)) <= CONV_TOL, s
+            ref = oracle.group_lasso_grad(w, ron, rin, lam, l.lasso_flags, oracle.conv_bwd_weight(o, t["x"], t["dy"]))
+            assert rel_err(l.dw.cpu().numpy()[..., : s.C], ref) <= CONV_TOL, s
+
+    net.train_step(lam)
+    torch.cuda.synchronize()
+    check([t["w"] for t in host])
+    net.optimizer_step(0.0, 1e-4, 0.0, 0.0)     # w <- w - lr * dw: every weight moves, off the bf16 grid
+    net.train_step(lam)
+    torch.cuda.synchronize()
+    new_w = [l.w_master.cpu().numpy()[..., : l.spec.C] for l in net.layers]
+    assert not np.array_equal(new_w[1], host[1]["w"])
+    check(new_w)
 
 
 # ---------------------------------------------------------------------------------------------- #

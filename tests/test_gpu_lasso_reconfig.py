@@ -31,7 +31,10 @@ def _norms_gpu(w, pitch=None, shadow=False):
 
 
 NORM_SHAPES = [(16, 3, 3, 16), (64, 1, 1, 64), (256, 1, 1, 64), (64, 7, 7, 3), (128, 3, 3, 128), (37, 3, 3, 51),
-               (203, 1, 1, 811), (512, 1, 1, 2048), (5, 1, 1, 1), (1, 1, 1, 9), (700, 3, 3, 24)]
+               (203, 1, 1, 811), (512, 1, 1, 2048), (5, 1, 1, 1), (1, 1, 1, 9), (700, 3, 3, 24),
+               # one, two, four and eight 16-byte columns per thread, rows that do not fill the last batch of a chunk
+               (207, 1, 1, 655), (45, 3, 3, 209), (300, 1, 1, 1000), (2100, 1, 1, 260), (3, 1, 1, 2048), (20, 1, 1, 516),
+               (4099, 1, 1, 4), (131, 3, 3, 12), (17, 5, 5, 2047)]
 
 
 @pytest.mark.parametrize("shape", NORM_SHAPES)
@@ -98,7 +101,7 @@ def test_batched_norms_and_lasso_match_oracle_per_layer():
     multi-layer calls: more layers than one launch holds, both loader kinds in one call."""
     from gpu_util import DEV, F32_TOL, dev_f32, host_bf16, pitch8, rel_err
     specs, _ = wl.resnet32_layers(N=1)
-    shapes = [(s.K, s.R, s.S, s.C) for s in specs] + [(203, 1, 1, 811), (37, 3, 3, 51), (64, 3, 3, 37)]
+    shapes = [(s.K, s.R, s.S, s.C) for s in specs] * 2 + [(203, 1, 1, 811), (37, 3, 3, 51), (64, 3, 3, 37)]
     rng = np.random.Generator(np.random.PCG64(21))
     lam = 2e-3
     ws_h, jobs_n, jobs_l, devs = [], [], [], []
@@ -118,7 +121,7 @@ def test_batched_norms_and_lasso_match_oracle_per_layer():
         jobs_l.append(B.layer_lasso(wd, on, inn, dwd, K, RS, C, pitch, flags))
         ws_h.append((w, dw0, flags))
         devs.append((wd, dwd, on, inn, sh_t))
-    assert len(shapes) > 32
+    assert len(shapes) > 64
     ws = torch.empty(B.group_norms_batched_workspace_bytes(jobs_n), dtype=torch.uint8, device=DEV)
     B.group_norms_batched(jobs_n, ws)
     B.group_lasso_grad_batched(jobs_l, lam)
@@ -535,3 +538,46 @@ def test_optimizer_step_matches_oracle():
 def workspace_for(s):
     from gpu_util import workspace
     return workspace(B.group_norms_workspace_bytes(s["K"], s["RS"], s["C"]))
+
+
+def test_norms_with_zero_masks_in_one_call():
+    """pt_group_norms_detect_batched: norms bit-identical to pt_group_norms_batched's, masks bit-identical to
+    pt_zero_groups on those norms and to the oracle's (groups are exactly zero or far above the threshold), at
+    several thresholds including the ones that mark nothing."""
+    from gpu_util import DEV, dev_f32, pitch8
+    rng = np.random.Generator(np.random.PCG64(77))
+    shapes = [(64, 3, 3, 64), (203, 1, 1, 811), (37, 3, 3, 51), (655, 1, 1, 207), (16, 7, 7, 3), (64, 3, 3, 37)]
+    host, devs = [], []
+    for i, sh in enumerate(shapes):
+        w = rng.standard_normal(sh, dtype=np.float32) * np.float32(0.05)
+        K, C = sh[0], sh[-1]
+        zo = rng.choice(K, max(1, K // 3), replace=False)
+        zi = rng.choice(C, max(1, C // 4), replace=False)
+        w = wl.zero_groups_in_weights(w, zo, zi)
+        pitch = C if i == len(shapes) - 1 else pitch8(C)          # the last layer is stored unaligned
+        t = dict(w=dev_f32(w, pitch), K=K, RS=sh[1] * sh[2], C=C, pitch=pitch)
+        for name, n, dt in (("on", K, torch.float32), ("inn", C, torch.float32), ("on2", K, torch.float32),
+                            ("inn2", C, torch.float32), ("zo", K, torch.uint8), ("zi", C, torch.uint8),
+                            ("zo2", K, torch.uint8), ("zi2", C, torch.uint8)):
+            t[name] = torch.full((n,), 7, dtype=dt, device=DEV)
+        host.append(w)
+        devs.append(t)
+    jobs_d = [B.layer_detect(t["w"], t["K"], t["RS"], t["C"], t["pitch"], t["on"], t["inn"], t["zo"], t["zi"]) for t in devs]
+    jobs_n = [B.layer_weights(t["w"], t["K"], t["RS"], t["C"], t["pitch"], t["on2"], t["inn2"], None) for t in devs]
+    ws = torch.empty(B.group_norms_detect_batched_workspace_bytes(jobs_d), dtype=torch.uint8, device=DEV)
+    assert ws.numel() == B.group_norms_batched_workspace_bytes(jobs_n)
+    B.group_norms_batched(jobs_n, ws)
+    for thr in (1e-6, 1e-4, 0.0, -1.0, 1e9):
+        B.group_norms_detect_batched(jobs_d, thr, ws)
+        for t in devs:
+            B.zero_groups(t["on2"], t["K"], thr, t["zo2"])
+            B.zero_groups(t["inn2"], t["C"], thr, t["zi2"])
+        torch.cuda.synchronize()
+        for w, t in zip(host, devs):
+            assert torch.equal(t["on"], t["on2"]) and torch.equal(t["inn"], t["inn2"])
+            assert torch.equal(t["zo"], t["zo2"]) and torch.equal(t["zi"], t["zi2"])
+            ron, rin = oracle.group_norms(w)
+            assert np.array_equal(t["zo"].cpu().numpy(), oracle.zero_groups(ron.astype(np.float32), thr))
+            assert np.array_equal(t["zi"].cpu().numpy(), oracle.zero_groups(rin.astype(np.float32), thr))
+            if 0.0 < thr < 1.0:
+                assert int(t["zo"].sum()) == max(1, t["K"] // 3) and int(t["zi"].sum()) == max(1, t["C"] // 4)
