@@ -90,6 +90,8 @@ def main():
     ap.add_argument("--no-fused-lasso", action="store_true",
                     help="add the regulariser's gradient in a pass of its own after the weight gradients")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quick", action="store_true", help="only the timed step and its phases (no per-family timings)")
+    ap.add_argument("--wgrad-streams", type=int, default=None, help="side streams the weight gradients alternate between")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a plain elementwise kernel of known size (reads 1 GiB, writes 1 GiB): the "
                          "reference against which hardware byte counters of a profiler run are scaled")
@@ -105,6 +107,8 @@ def main():
     from paper_1901_09290_amd import workloads as wl
 
     B.lib()  # fail loudly if the HIP library is not built
+    if args.wgrad_streams is not None:
+        hz.WGRAD_STREAMS = args.wgrad_streams
     torch.cuda.set_device(0)
     N = args.batch
 
@@ -209,6 +213,12 @@ def main():
         t_pruned = timed(lambda: pruned.train_step(LAMBDA), reps)
         t_detect = timed(lambda: rmodel.detect(THRESHOLD), reps)
         t_compact = timed(lambda: rmodel.compact(counts0), reps)
+
+    if args.quick:
+        print(json.dumps({"value": round(value, 3), "ms_per_step": round(ms_step, 4), "full_ms": round(t_full, 4),
+                          "pruned_ms": round(t_pruned, 4), "detect_ms": round(t_detect, 4),
+                          "compact_ms": round(t_compact, 4), "wgrad_streams": hz.WGRAD_STREAMS}), flush=True)
+        return
 
     # kernel families: every layer's call of one kind back to back between two events
     fam = {}

@@ -144,6 +144,17 @@ int32_t pt_group_norms_workspace_bytes(int32_t K, int32_t RS, int32_t C, size_t*
 int32_t pt_group_norms(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, float* out_norm,
                        float* in_norm, uint16_t* w_shadow, void* ws, size_t ws_bytes, void* stream);
 
+/* pt_group_norms for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Same arguments minus the workspace, same kernels and
+ * results; the scratch (row sums and per-chunk column partials) is an array of 4 MiB that the library holds on every
+ * device it runs on, for as long as the process lives.  A layer whose pt_group_norms_workspace_bytes exceeds 4 MiB
+ * is rejected with PT_ERR_WORKSPACE before anything is enqueued.  The call allocates and frees nothing, on the
+ * device or through any library.  Nothing in the scratch needs clearing: every element a call reads it has written
+ * itself.  All calls on one device share the one array: calls that overlap on a device (different streams, or
+ * different host threads' streams) race; order them on one stream or with events. */
+int32_t pt_group_norms_static(const float* w, int32_t K, int32_t RS, int32_t C, int32_t w_cpitch, float* out_norm,
+                              float* in_norm, uint16_t* w_shadow, void* stream);
+
 /* Adds the gradient of lambda * (sum_k out_norm[k] + sum_c in_norm[c]) onto dw (accumulates):
  *   dw[k,rs,c] += lambda * w[k,rs,c] * (a / out_norm[k] + b / in_norm[c]),
  * a = flags bit 0 (regularise output groups), b = flags bit 1 (regularise input groups; clear it for

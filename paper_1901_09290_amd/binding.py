@@ -28,6 +28,7 @@ EXPORTS = [
     "pt_group_norms_workspace_bytes", "pt_group_norms", "pt_group_lasso_grad",
     "pt_group_norms_batched_workspace_bytes", "pt_group_norms_batched", "pt_group_lasso_grad_batched",
     "pt_group_norms_detect_batched_workspace_bytes", "pt_group_norms_detect_batched", "pt_conv_bwd_weight_plan",
+    "pt_group_norms_static",
     "pt_zero_groups", "pt_reconcile_edge", "pt_compact_plan",
     "pt_compact_weights", "pt_compact_vector", "pt_compact_nhwc",
     "pt_weights_to_crsk_batched", "pt_conv_bwd_data_crsk",
@@ -145,6 +146,7 @@ def lib() -> C.CDLL:
             "pt_group_norms_workspace_bytes": [i32, i32, i32, C.POINTER(sz)],
             "pt_group_norms": [vp, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
             "pt_group_lasso_grad": [vp, vp, vp, f32, u32, vp, i32, i32, i32, i32, vp],
+            "pt_group_norms_static": [vp, i32, i32, i32, i32, vp, vp, vp, vp],
             "pt_group_norms_batched_workspace_bytes": [C.POINTER(LayerWeights), i32, C.POINTER(sz)],
             "pt_group_norms_batched": [C.POINTER(LayerWeights), i32, vp, sz, vp],
             "pt_group_lasso_grad_batched": [C.POINTER(LayerLasso), i32, f32, vp],
@@ -281,6 +283,12 @@ def group_norms(w, K, RS, Cc, w_cpitch, out_norm, in_norm, w_shadow=None, ws=Non
 def group_lasso_grad(w, out_norm, in_norm, lam: float, flags: int, dw, K, RS, Cc, w_cpitch, stream=None) -> None:
     _ck("pt_group_lasso_grad", lib().pt_group_lasso_grad(_ptr(w), _ptr(out_norm), _ptr(in_norm), lam, flags, _ptr(dw),
                                                          K, RS, Cc, w_cpitch, _stream(stream)))
+
+
+def group_norms_static(w, K: int, RS: int, Cc: int, w_cpitch: int, out_norm, in_norm, w_shadow=None, stream=None) -> None:
+    """pt_group_norms without a workspace argument: the library's own per-device scratch is used."""
+    _ck("pt_group_norms_static", lib().pt_group_norms_static(_ptr(w), K, RS, Cc, w_cpitch, _ptr(out_norm), _ptr(in_norm),
+                                                            _ptr(w_shadow), _stream(stream)))
 
 
 def layer_weights(w, K, RS, Cc, w_cpitch, out_norm, in_norm, w_shadow=None) -> LayerWeights:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 SO = os.path.join(HERE, "libprunetrain.so")
-SOURCES = ["api.hip", "conv.hip", "lasso.hip", "reconfig.hip", "bn.hip", "removal.hip"]
+SOURCES = ["api.hip", "conv.hip", "lasso.hip", "norms_static.hip", "reconfig.hip", "bn.hip", "removal.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

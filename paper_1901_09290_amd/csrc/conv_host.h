@@ -142,7 +142,13 @@ constexpr int kWgDlBKP = 64;                          // direct kernel: pixels p
 // several streams, so one launch need not fill the chip, and every split costs a tile of fp32 partial sums written
 // and read again.  Measured on the ResNet-50 step with four side streams: 512/256 -> 245, 256/96 -> 264 TFLOP/s
 // (run one after the other on a single stream the same launches are ~25 % slower than with 512/256).
-constexpr int kWgTargetBlocks = 256, kWgTargetBlocksBig = 96;
+#ifndef PT_WG_TARGET_SMALL
+#define PT_WG_TARGET_SMALL 256
+#endif
+#ifndef PT_WG_TARGET_BIG
+#define PT_WG_TARGET_BIG 96
+#endif
+constexpr int kWgTargetBlocks = PT_WG_TARGET_SMALL, kWgTargetBlocksBig = PT_WG_TARGET_BIG;
 
 // 64-wide tiles when 128-wide ones would waste more than ~20 % of their rows
 inline int pick_tile(int n) {

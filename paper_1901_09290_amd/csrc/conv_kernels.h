@@ -838,6 +838,7 @@ struct WgradArgs {
     int KP;              // K rounded up to 8
     int fold;            // direct kernel: a tile row block spans the S taps of one filter row (dense small-C pixels)
     int iters_total, iters_per_split, splits;
+    int dn, dp, dq;      // direct kernel: one reduction step of BKP pixels = dn images + dp output rows + dq output columns
     // direct kernel writing dw itself (direct != 0): when lw is set, the gradient of the group-lasso penalty is added
     // to every element on the way out, dw += l_lambda * (lw * (1/l_on[k] + 1/l_in[c])) with a zero norm contributing 0
     const float* lw;    // fp32 master weights, layout and pitch of dw
@@ -1070,8 +1071,8 @@ __device__ __forceinline__ bf16x8 join_halves(s16x4 lo, s16x4 hi) {
 // KSPLIT wave groups share one tile: group g multiplies the g-th part of every stage's pixel sub-steps, and the
 // groups' accumulators are added through LDS before the store.  More waves per SIMD to hide LDS and barrier
 // latency, with the same LDS footprint, loads and partial-sum traffic as one group.
-template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1>
-__global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const WgradArgs a) {
+template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1, int MINB = 1>
+__global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(const WgradArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int NWT = WGM * WGN;       // waves of one group: the wave grid over the tile
     constexpr int NW = NWT * KSPLIT;     // all waves: they share the loads
@@ -1122,31 +1123,62 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
     const int yk = min(n0 + ylc * 8, a.KP - 8);
     const uint16_t* zero_page = reinterpret_cast<const uint16_t*>(g_zero16);
 
-    auto issue = [&](int it, int stage) {
+    // Gather state of this lane's loads, advanced by BKP pixels per reduction step without divisions or multiplies
+    // (integer multiplies run at a quarter of the vector rate and were the loop's bound).  A step moves every
+    // slot from output pixel (n, p, q) to (n + dn, p + dp, q + dq) with at most one carry out of q and one out of
+    // p (dq < Q, dp < P); the slot keeps the input coordinates (ih, iw) of its tap and the element offset of that
+    // input pixel, which change by constants that depend only on the two carries.
+    const int Qs = (int)a.Q.d * a.stride_w, Ps = (int)a.P.d * a.stride_h;
+    const int iw_wrap = Qs - a.pad_w + fs, ih_wrap = Ps - a.pad_h + fr;  // first coordinate past the last output column / row
+    const int dq_s = a.dq * a.stride_w, dp_s = a.dp * a.stride_h;
+    const int rowp = a.W * a.xpitch;  // elements per input row
+    const int D0 = dq_s * a.xpitch + dp_s * rowp + a.dn * a.H * rowp;  // no carry
+    const int D1 = a.stride_h * rowp - Qs * a.xpitch;                  // carry out of q: next output row
+    const int D2 = (a.H - Ps) * rowp;                                  // carry out of p: next image
+    const int xrel0 = wave * RPLX + xr, yrel0 = wave * RPLY + yr;      // this lane's pixel inside a step (slot 0)
+    int x_ih[LX], x_iw[LX];
+    uint32_t x_off[LX], y_off[LY];
+#pragma unroll
+    for (int j = 0; j < LX; ++j) {
+        const int pix = it0 * BKP + xrel0 + NW * j * RPLX;
+        const uint32_t row = fdiv((uint32_t)pix, a.Q);
+        const int q = pix - (int)row * (int)a.Q.d;
+        const uint32_t n = fdiv(row, a.P);
+        const int p = (int)row - (int)n * (int)a.P.d;
+        x_ih[j] = p * a.stride_h - a.pad_h + fr;
+        x_iw[j] = q * a.stride_w - a.pad_w + fs;
+        x_off[j] = (uint32_t)(((int)n * a.H + x_ih[j]) * a.W + (x_iw[j] - fs + fs_addr)) * (uint32_t)a.xpitch + (uint32_t)xc;
+    }
+#pragma unroll
+    for (int j = 0; j < LY; ++j)
+        y_off[j] = (uint32_t)(it0 * BKP + yrel0 + NW * j * RPLY) * (uint32_t)a.ypitch + (uint32_t)yk;
+    int p_left = a.pixels - it0 * BKP;  // pixels from the next step's first one to the end (uniform)
+    const uint32_t y_step = (uint32_t)(BKP * a.ypitch);
+
+    // issues the loads of the next reduction step (steps are issued in order) into `stage`
+    auto issue = [&](int stage) {
         uint8_t* sbase = smem_b + stage * STAGE_BYTES;
-        const int pbase = it * BKP;
 #pragma unroll
         for (int j = 0; j < LX; ++j) {
-            const int pix = pbase + (wave + NW * j) * RPLX + xr;
-            const uint32_t row = fdiv((uint32_t)pix, a.Q);
-            const int q = pix - (int)row * (int)a.Q.d;
-            const uint32_t n = fdiv(row, a.P);
-            const int p = (int)row - (int)n * (int)a.P.d;
-            const int ih = p * a.stride_h - a.pad_h + fr, iw = q * a.stride_w - a.pad_w + fs;
-            const bool ok = pix < a.pixels && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-            const uint32_t off =
-                (uint32_t)(((int)n * a.H + ih) * a.W + (iw - fs + fs_addr)) * (uint32_t)a.xpitch + (uint32_t)xc;
-            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.X + off, zero_page),
+            const bool ok = xrel0 < p_left - NW * j * RPLX && (unsigned)x_ih[j] < (unsigned)a.H && (unsigned)x_iw[j] < (unsigned)a.W;
+            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.X + x_off[j], zero_page),
                                              (lds_void_ptr)(sbase + (wave + NW * j) * 1024), 16, 0, 0);
+            const int iw = x_iw[j] + dq_s;
+            const bool c1 = iw >= iw_wrap;
+            x_iw[j] = iw - (c1 ? Qs : 0);
+            const int ih = x_ih[j] + (c1 ? dp_s + a.stride_h : dp_s);
+            const bool c2 = ih >= ih_wrap;
+            x_ih[j] = ih - (c2 ? Ps : 0);
+            x_off[j] += (uint32_t)((c1 ? D0 + D1 : D0) + (c2 ? D2 : 0));
         }
 #pragma unroll
         for (int j = 0; j < LY; ++j) {
-            const int pix = pbase + (wave + NW * j) * RPLY + yr;
-            const bool ok = pix < a.pixels;
-            const uint32_t off = (uint32_t)pix * (uint32_t)a.ypitch + (uint32_t)yk;
-            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.DY + off, zero_page),
+            const bool ok = yrel0 < p_left - NW * j * RPLY;
+            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.DY + y_off[j], zero_page),
                                              (lds_void_ptr)(sbase + XBYTES + (wave + NW * j) * 1024), 16, 0, 0);
+            y_off[j] += y_step;
         }
+        p_left -= BKP;
     };
 
     // ---- MFMA state ---------------------------------------------------------------------------
@@ -1185,7 +1217,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
             ay[tn][h] = lds_base + (uint32_t)((r0 + r) * RBY + ((u ^ swz(r, RBY)) << 5) + tr_b);
         }
     }
-    static_assert(NRD < 16, "fragment reads per sub-step must fit the lgkmcnt field");
+    static_assert(NKS == 1 || NRD < 16, "fragment reads per sub-step must fit the lgkmcnt field");
     // One stage: the reads of sub-step ks+1 are in flight while the MFMAs of sub-step ks run.
     auto compute = [&](int stage) {
         const uint32_t sb = (uint32_t)(stage * STAGE_BYTES);
@@ -1235,7 +1267,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
     const bool late = STAGES >= 3 && NW >= 8 && (wave & 4) != 0;
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
-        if (s < nk) issue(it0 + s, s);
+        if (s < nk) issue(s);
     for (int kt0 = 0; kt0 < nk; kt0 += STAGES) {
 #pragma unroll
         for (int s = 0; s < STAGES; ++s) {
@@ -1249,40 +1281,42 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
                 // phases overlap on the SIMD instead of running in lockstep.  The target buffer is the one
                 // consumed in the previous step either way.
                 const bool more = kt + STAGES - 1 < nk;
-                if (more && !late) issue(it0 + kt + STAGES - 1, (s + STAGES - 1) % STAGES);
+                if (more && !late) issue((s + STAGES - 1) % STAGES);
                 compute(s);
-                if (more && late) issue(it0 + kt + STAGES - 1, (s + STAGES - 1) % STAGES);
+                if (more && late) issue((s + STAGES - 1) % STAGES);
             }
         }
     }
 
     if constexpr (KSPLIT > 1) {
-        // groups 1.. park their accumulators in LDS (the stage buffers are dead: every load was waited for and the
-        // barrier below follows every wave's last read), group 0 adds them in group order and stores
+        // groups 1.. park their accumulators in LDS one group at a time (the stage buffers are dead: every load was
+        // waited for and the barrier below follows every wave's last read); group 0 adds them in group order and stores
         float* red = reinterpret_cast<float*>(smem_b);
         constexpr int PER_WAVE = TM * TN * 16 * 64;
-        __syncthreads();
-        if (kg > 0) {
-            float* dst = red + ((kg - 1) * NWT + wave_t) * PER_WAVE + lane;
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) dst[((tm * TN + tn) * 16 + v) * 64] = acc[tm][tn][v];
-        }
-        __syncthreads();
-        if (kg > 0) return;
 #pragma unroll
         for (int g = 1; g < KSPLIT; ++g) {
-            const float* src = red + ((g - 1) * NWT + wave_t) * PER_WAVE + lane;
+            __syncthreads();
+            if (kg == g) {
+                float* dst = red + wave_t * PER_WAVE + lane;
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
+                for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
+                    for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[tm][tn][v] += src[((tm * TN + tn) * 16 + v) * 64];
+                        for (int v = 0; v < 16; ++v) dst[((tm * TN + tn) * 16 + v) * 64] = acc[tm][tn][v];
+            }
+            __syncthreads();
+            if (kg == 0) {
+                const float* src = red + wave_t * PER_WAVE + lane;
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[tm][tn][v] += src[((tm * TN + tn) * 16 + v) * 64];
+            }
         }
+        if (kg > 0) return;
     }
     // ---- epilogue: lane holds k (column) = lane%32 and rows 8g + 4*(lane/32) + {0..3} = 4 consecutive c
     float* out = a.OUT + (a.direct ? 0 : (int64_t)split * a.K * a.out_row_pitch);
@@ -1345,13 +1379,17 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, 1) void k_wgrad_dl(const W
 #endif
 }
 
-template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1>
+template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1, int MINB = 1>
 inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
     constexpr int NT = 64 * WGM * WGN * KSPLIT;
-    constexpr size_t ring = (size_t)STAGES * BKP * (BM + BN) * 2, red = (size_t)(KSPLIT - 1) * BM * BN * 4;
+    constexpr size_t ring = (size_t)STAGES * BKP * (BM + BN) * 2, red = KSPLIT > 1 ? (size_t)BM * BN * 4 : 0;
     constexpr size_t lds = ring > red ? ring : red;
     static_assert(lds <= 160 * 1024, "LDS capacity");
-    auto kern = k_wgrad_dl<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT>;
+    auto kern = k_wgrad_dl<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT, MINB>;
+    const int P = (int)a.P.d, Q = (int)a.Q.d;
+    a.dq = BKP % Q;
+    a.dp = (BKP / Q) % P;
+    a.dn = BKP / (P * Q);
     static LdsOptIn opt_in;
     if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(NT), lds, st, a);

@@ -22,7 +22,7 @@ namespace pt {
 constexpr int kThreads = 256;
 constexpr int kMaxC = 2048;  // 64 lanes x (8 float4 column groups | 32 scalar column groups) per thread
 #ifndef PT_NORM_JOBS
-#define PT_NORM_JOBS 46  // 46 x 88 bytes + 16 = 4064 bytes of kernel arguments
+#define PT_NORM_JOBS 64  // 64 x 88 bytes + 16 = 5.5 KiB of kernel arguments
 #endif
 constexpr int kMaxJobs = PT_NORM_JOBS;  // layers per launch (the table rides in the kernel arguments)
 
@@ -44,7 +44,7 @@ struct NormJobs {
     float thr;
     int n;
 };
-static_assert(sizeof(NormJobs) <= 4096 || PT_NORM_JOBS > 46, "kernel-argument table");
+static_assert(sizeof(NormJobs) <= 8192, "kernel-argument table");
 
 struct LassoJob {
     const float* w;
