@@ -25,7 +25,8 @@ inline int32_t check_desc(const pt_conv_desc* d) {
     const int64_t big = d->H > d->W ? d->H : d->W;  // divisors of the in-kernel pixel decompositions
     if (in_pix * big >= (1ll << 32) || out_pix * big >= (1ll << 32)) return PT_ERR_UNSUPPORTED;
     // 32-bit element offsets into every tensor
-    if (in_pix * d->x_cpitch >= (1ll << 31) || out_pix * d->y_cpitch >= (1ll << 31)) return PT_ERR_UNSUPPORTED;
+    // (a margin below 2^31 elements: the buffer addressing of the direct kernels shifts offsets by up to a padded border)
+    if (in_pix * d->x_cpitch >= (1ll << 31) - (1ll << 27) || out_pix * d->y_cpitch >= (1ll << 31) - (1ll << 27)) return PT_ERR_UNSUPPORTED;
     if ((int64_t)d->K * d->R * d->S * d->w_cpitch >= (1ll << 31)) return PT_ERR_UNSUPPORTED;
     if ((int64_t)d->C * d->R * d->S * round_up(d->K, 8) >= (1ll << 31)) return PT_ERR_UNSUPPORTED;
     if ((int64_t)d->R * d->S * round_up(d->C, 8) >= (1ll << 30)) return PT_ERR_UNSUPPORTED;
@@ -132,11 +133,16 @@ inline size_t bwd_data_ws(const pt_conv_desc* d) {
 // (tap, channel) axis, fixed 128x128 tiles).
 struct WgradPlan {
     int dl, fold, BM, BN;
+    int bkp;  // direct kernel: output pixels per reduction step
     int splits, iters_total, iters_per_split, tiles_m, tiles_n, tiles_per_tap, CP, KP, Mtot;
     size_t ws_bytes;
 };
 constexpr int kWgBM = 128, kWgBN = 128, kWgBK = 32;  // register-staged kernel
 constexpr int kWgDlBKP = 64;                          // direct kernel: pixels per reduction step
+#ifndef PT_WG_BKP_BIG
+#define PT_WG_BKP_BIG 64
+#endif
+constexpr int kWgDlBKPBig = PT_WG_BKP_BIG;            // the same for 128 x 128 tiles
 // Workgroups per launch the split count aims at (128x128 tiles: kWgTargetBlocksBig).  Well below the 512 resident
 // slots on purpose: weight gradients of different layers are independent and are meant to run side by side on
 // several streams, so one launch need not fill the chip, and every split costs a tile of fp32 partial sums written
@@ -171,8 +177,10 @@ inline WgradPlan plan_wgrad(const pt_conv_desc* d, bool dl) {
         p.tiles_per_tap = (int)ceil_div(run, p.BM);
         p.tiles_m = (p.fold ? d->R : d->R * d->S) * p.tiles_per_tap;
         p.tiles_n = (int)ceil_div(d->K, p.BN);
-        p.iters_total = (int)ceil_div(pixels, kWgDlBKP);
+        p.bkp = (p.BM == 128 && p.BN == 128) ? kWgDlBKPBig : kWgDlBKP;
+        p.iters_total = (int)ceil_div(pixels, p.bkp);
     } else {
+        p.bkp = kWgBK;
         p.BM = kWgBM;
         p.BN = kWgBN;
         p.tiles_per_tap = 0;
@@ -216,6 +224,8 @@ inline WgradArgs make_wgrad_args(const pt_conv_desc* d, const WgradPlan& p, cons
     a.S = d->S; a.RS = d->R * d->S; a.C = d->C; a.CP = p.CP; a.KP = p.KP; a.Mtot = p.Mtot; a.K = d->K;
     a.tiles_n = p.tiles_n; a.tiles_m = p.tiles_m; a.tiles_per_tap = p.tiles_per_tap; a.fold = p.fold;
     a.iters_total = p.iters_total; a.iters_per_split = p.iters_per_split; a.splits = p.splits;
+    a.affine = d->stride_h == 1 && d->stride_w == 1 && d->P == d->H && d->Q == d->W;
+    a.x_all_valid = a.affine && d->R == 1 && d->S == 1 && d->pad_h == 0 && d->pad_w == 0;
     a.wpitch = d->w_cpitch;
     a.direct = p.splits == 1;
     a.OUT = a.direct ? dw : (float*)ws;
@@ -230,7 +240,10 @@ inline hipError_t launch_wgrad(WgradArgs& a, const WgradPlan& p, bool vec, hipSt
         return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2>(a, st);
     }
     // wave grids and pipeline depths from measurements on ResNet-50 shapes
-    if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKP, 2, 2, 3, 2>(a, st);
+    if (p.BM == 128 && p.BN == 128) {
+        if constexpr (kWgDlBKPBig == 128) return launch_wgrad_dl_cfg<128, 128, 128, 2, 2, 2, 2>(a, st);
+        else return launch_wgrad_dl_cfg<128, 128, kWgDlBKP, 2, 2, 3, 2>(a, st);
+    }
     if (p.BM == 64 && p.BN == 128) return launch_wgrad_dl_cfg<64, 128, kWgDlBKP, 2, 2, 3, 2>(a, st);
     if (p.BM == 128 && p.BN == 64) return launch_wgrad_dl_cfg<128, 64, kWgDlBKP, 2, 2, 3, 2>(a, st);
     return launch_wgrad_dl_cfg<64, 64, kWgDlBKP, 2, 2, 4, 2>(a, st);

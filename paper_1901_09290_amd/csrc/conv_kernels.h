@@ -130,6 +130,10 @@ struct IgemmArgs {
     // q = 0 sums, q = 1 sums of squares - the layout the normalisation's finish pass reads.
     float* stats;
     int tiles_m;
+    // Direct kernel, buffer addressing of the gathered operand: a row's offset plus a_guard is non-negative for
+    // every row, a reduction step's offset minus a_smin is non-negative for every step (both in elements; the
+    // buffer's base address absorbs the two shifts).  a_all_valid: no tap of any row ever leaves the source image.
+    int a_guard, a_smin, a_all_valid;
 };
 
 // Fills tail_kv / tail_nvalid (see IgemmArgs) for the direct kernel's 64-channel blocks.
@@ -404,7 +408,8 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 // TAIL = some run of channels ends inside an 8-chunk whose remaining elements are undefined.
 // STATS = also reduce the stored outputs to per-channel sums and sums of squares (see IgemmArgs::stats).
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED, bool TAIL = RAGGED, bool STATS = false>
+// AV = the caller has established that every tap of every row lies inside the source image (no validity tests).
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED, bool TAIL = RAGGED, bool STATS = false, bool AV = false>
 __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int NW = WGM * WGN, BK = 64;
@@ -456,34 +461,48 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
         const int nrow = min(n0 + (wave + NW * j) * 8 + lrow, a.Nout - 1);
         b_off[j] = (uint32_t)nrow * b_rowlen + (uint32_t)kvoff;
     }
-    const uint16_t* zero_page = reinterpret_cast<const uint16_t*>(g_zero16);
+    // Both operands are fetched with buffer loads: the per-lane part of an address (row, 8-element chunk) is a
+    // constant byte offset (voffset), the part that changes from step to step (filter tap, channel block) is the same
+    // for every lane and travels in a scalar register (soffset), and a lane that must read zeros (tap outside the
+    // image, chunk past the channel count) passes an out-of-range voffset, for which the load writes zeros to LDS.
+    // The reduction loop is bound by the number of instructions a wave issues, so a step costs no vector arithmetic
+    // beyond those validity tests.  The base address of the gathered operand is shifted so that both parts are
+    // non-negative (it may point outside the tensor: only valid taps are ever fetched).
+    constexpr uint32_t kBufRecords = 0xffffff00u, kBufOut = 0xffffffffu, kBufFlags = 0x00020000u;
+    const __amdgpu_buffer_rsrc_t a_srd = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(a.A) + ((int64_t)a.a_smin - a.a_guard), 0, kBufRecords, kBufFlags);
+    const __amdgpu_buffer_rsrc_t b_srd = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.B), 0, kBufRecords, kBufFlags);
+    uint32_t a_v[LA], b_v[LB];
+#pragma unroll
+    for (int j = 0; j < LA; ++j) a_v[j] = (a_off[j] + (uint32_t)a.a_guard) * 2u;
+#pragma unroll
+    for (int j = 0; j < LB; ++j) b_v[j] = b_off[j] * 2u;
 
     int i_tr = 0, i_ts = 0, i_cb = 0;  // next step to issue (uniform)
     int c_cb = 0;                      // channel base of the next step to compute (uniform)
 
     auto issue = [&](int stage) {
         uint8_t* sbase = smem_b + stage * STAGE_BYTES;
-        // Element offsets are formed in 32-bit wrapping arithmetic (row constant + step delta): for a tap inside
-        // the image the sum is the true non-negative offset even when either part alone is "negative".
-        const uint32_t sa = (uint32_t)((i_tr * a.tr_step * a.srcW + i_ts * a.ts_step) * a.apitch + i_cb);
-        const uint32_t sb = (uint32_t)((a.b_tap0 + i_tr * a.b_tr_stride + i_ts * a.b_ts_stride) * a.bpitch + i_cb);
+        const uint32_t sa = (uint32_t)(((i_tr * a.tr_step * a.srcW + i_ts * a.ts_step) * a.apitch + i_cb - a.a_smin) * 2);
+        const uint32_t sb = (uint32_t)(((a.b_tap0 + i_tr * a.b_tr_stride + i_ts * a.b_ts_stride) * a.bpitch + i_cb) * 2);
         const bool chunk_ok = !RAGGED || (i_cb + kvoff < a.Cred);
-        // which tap this lane's chunk belongs to: the step's tap, or in folded mode the tap inside the run
-        const int tapbit = i_tr * a.TSm + (a.fold ? (int)fdiv((uint32_t)(i_cb + kvoff), a.Cfold) : i_ts);
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
-            const bool ok = chunk_ok && ((a_mask[j] >> tapbit) & 1u);
-            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.A + (uint32_t)(a_off[j] + sa), zero_page),
-                                             (lds_void_ptr)(sbase + (wave + NW * j) * 1024), 16, 0, 0);
+            uint32_t v = a_v[j];
+            if constexpr (!AV) {
+                // which tap this lane's chunk belongs to: the step's tap, or in folded mode the tap inside the run
+                const int tapbit = i_tr * a.TSm + (a.fold ? (int)fdiv((uint32_t)(i_cb + kvoff), a.Cfold) : i_ts);
+                v = (chunk_ok && ((a_mask[j] >> tapbit) & 1u)) ? v : kBufOut;
+            } else if constexpr (RAGGED) {
+                v = chunk_ok ? v : kBufOut;
+            }
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_srd, (lds_void_ptr)(sbase + (wave + NW * j) * 1024), 16, v, sa, 0, 0);
         }
 #pragma unroll
         for (int j = 0; j < LB; ++j) {
-            if constexpr (RAGGED)
-                __builtin_amdgcn_global_load_lds(pick_ptr(chunk_ok, a.B + (uint32_t)(b_off[j] + sb), zero_page),
-                                                 (lds_void_ptr)(sbase + BM * 128 + (wave + NW * j) * 1024), 16, 0, 0);
-            else
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(uintptr_t)(a.B + (uint32_t)(b_off[j] + sb)),
-                                                 (lds_void_ptr)(sbase + BM * 128 + (wave + NW * j) * 1024), 16, 0, 0);
+            uint32_t v = b_v[j];
+            if constexpr (RAGGED) v = chunk_ok ? v : kBufOut;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_srd, (lds_void_ptr)(sbase + BM * 128 + (wave + NW * j) * 1024), 16, v, sb, 0, 0);
         }
         i_cb += BK;
         if (i_cb >= a.CredP) {
@@ -801,21 +820,37 @@ inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
         variant += 3;
         a.tiles_m = (int)ceil_div(a.M, BM);
     }
-    const void* kerns[5] = {reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false>),
-                            reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false>),
-                            reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true>),
-                            reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, true>),
-                            reinterpret_cast<const void*>(k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, true>)};
-    static LdsOptIn opt_in[5];
-    if (hipError_t e = opt_in[variant].ensure(kerns[variant], lds); e != hipSuccess) return e;
+    // buffer addressing of the gathered operand (see the kernel): shifts that make both address parts non-negative
+    a.a_guard = ((a.h_add < 0 ? -a.h_add : 0) * a.srcW + (a.w_add < 0 ? -a.w_add : 0)) * a.apitch;
+    const int last_r = (a.TR - 1) * a.tr_step, last_s = (a.TS - 1) * a.ts_step;
+    a.a_smin = ((last_r < 0 ? last_r : 0) * a.srcW + (last_s < 0 ? last_s : 0)) * a.apitch;
+    const int64_t img = (int64_t)ceil_div(a.M, (int64_t)a.gH.d * a.gW.d);  // images of the source tensor
+    if ((img * a.srcH * a.srcW * a.apitch + a.a_guard) * 2 >= 0xffffff00ll) return hipErrorInvalidValue;
+    if ((int64_t)a.Nout * a.b_taps * a.bpitch * 2 >= 0xffffff00ll) return hipErrorInvalidValue;
+    // every tap of every row inside the source image?  coordinates are monotone in the grid index and in the tap
+    auto inside = [](int lo, int hi, int n) { return lo >= 0 && hi >= 0 && lo < n && hi < n; };
+    const int h_first = a.h_add, h_last = ((int)a.gH.d - 1) * a.h_mul + a.h_add;
+    const int w_first = a.w_add, w_last = ((int)a.gW.d - 1) * a.w_mul + a.w_add;
+    const int rr = (a.TR - 1) * a.tr_step, ss = (a.TSm - 1) * a.ts_step;
+    a.a_all_valid = inside(h_first, h_last, a.srcH) && inside(h_first + rr, h_last + rr, a.srcH) &&
+                    inside(w_first, w_last, a.srcW) && inside(w_first + ss, w_last + ss, a.srcW);
+    const bool av = a.a_all_valid && variant != 2;
+    typedef void (*kern_t)(const IgemmArgs);
+    const kern_t kerns[2][5] = {{k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, false, false>,
+                                 k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, false, false>,
+                                 k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true, false, false>,
+                                 k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, true, false>,
+                                 k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, true, false>},
+                                {k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, false, true>,
+                                 k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, false, true>,
+                                 nullptr,
+                                 k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, true, true>,
+                                 k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, true, true>}};
+    const kern_t kern = kerns[av ? 1 : 0][variant];
+    static LdsOptIn opt_in[2][5];
+    if (hipError_t e = opt_in[av ? 1 : 0][variant].ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     const dim3 grid((unsigned)(ceil_div(a.M, BM) * a.tiles_n)), block(NT);
-    switch (variant) {
-        case 0: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false>), grid, block, lds, st, a); break;
-        case 1: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false>), grid, block, lds, st, a); break;
-        case 2: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true>), grid, block, lds, st, a); break;
-        case 3: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, true>), grid, block, lds, st, a); break;
-        default: hipLaunchKernelGGL((k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, true>), grid, block, lds, st, a); break;
-    }
+    hipLaunchKernelGGL(kern, grid, block, lds, st, a);
     return hipSuccess;
 }
 
@@ -839,6 +874,8 @@ struct WgradArgs {
     int fold;            // direct kernel: a tile row block spans the S taps of one filter row (dense small-C pixels)
     int iters_total, iters_per_split, splits;
     int dn, dp, dq;      // direct kernel: one reduction step of BKP pixels = dn images + dp output rows + dq output columns
+    int affine;          // direct kernel: stride 1 and output grid == input grid: x sits at (pixel + tap shift) * xpitch
+    int x_all_valid;     // affine and no tap ever leaves the image (1 x 1 filter without padding)
     // direct kernel writing dw itself (direct != 0): when lw is set, the gradient of the group-lasso penalty is added
     // to every element on the way out, dw += l_lambda * (lw * (1/l_on[k] + 1/l_in[c])) with a zero norm contributing 0
     const float* lw;    // fp32 master weights, layout and pitch of dw
@@ -1071,7 +1108,10 @@ __device__ __forceinline__ bf16x8 join_halves(s16x4 lo, s16x4 hi) {
 // KSPLIT wave groups share one tile: group g multiplies the g-th part of every stage's pixel sub-steps, and the
 // groups' accumulators are added through LDS before the store.  More waves per SIMD to hide LDS and barrier
 // latency, with the same LDS footprint, loads and partial-sum traffic as one group.
-template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1, int MINB = 1>
+// XMODE: how x is addressed.  0 = any geometry (per-lane global addresses, advanced incrementally); 1 = stride 1 with
+// an output grid equal to the input grid ('same'-padded filters): buffer loads whose moving part is a scalar; 2 = the
+// same where no tap ever leaves the image (1 x 1 filters): no per-lane work at all in a reduction step.
+template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1, int MINB = 1, int XMODE = 0>
 __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(const WgradArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     constexpr int NWT = WGM * WGN;       // waves of one group: the wave grid over the tile
@@ -1137,7 +1177,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(cons
     const int D2 = (a.H - Ps) * rowp;                                  // carry out of p: next image
     const int xrel0 = wave * RPLX + xr, yrel0 = wave * RPLY + yr;      // this lane's pixel inside a step (slot 0)
     int x_ih[LX], x_iw[LX];
-    uint32_t x_off[LX], y_off[LY];
+    uint32_t x_off[LX];
 #pragma unroll
     for (int j = 0; j < LX; ++j) {
         const int pix = it0 * BKP + xrel0 + NW * j * RPLX;
@@ -1149,34 +1189,85 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(cons
         x_iw[j] = q * a.stride_w - a.pad_w + fs;
         x_off[j] = (uint32_t)(((int)n * a.H + x_ih[j]) * a.W + (x_iw[j] - fs + fs_addr)) * (uint32_t)a.xpitch + (uint32_t)xc;
     }
+    // pixels from the next step's first one to the end of this workgroup's slice (uniform): loads past it fetch zeros,
+    // so steps may be issued unconditionally
+    int p_left = min(a.pixels, it1 * BKP) - it0 * BKP;
+
+    // dy, and x in layers whose output grid equals the input grid at stride 1 (1x1 and 'same'-padded filters), sit at
+    // an address that is affine in the output pixel index: a reduction step moves every load by one uniform amount.
+    // Those loads are buffer loads: the per-lane part of the address is a constant (voffset), the moving part a
+    // scalar register (soffset), and a lane that must read zeros (tap outside the image, pixel past the end) passes
+    // an out-of-range voffset, for which the load writes zeros to LDS.  The loop is bound by the number of
+    // instructions a wave issues per step, so nothing is computed per lane and step beyond the validity of
+    // 'same'-padded taps.  The filter tap's shift is folded into the buffer's base address (it may point ahead of the
+    // tensor: only valid taps are ever fetched).
+    constexpr uint32_t kBufRecords = 0x40000000u, kBufOut = 0x80000000u, kBufFlags = 0x00020000u;
+    const int tapshift = XMODE ? ((fr - a.pad_h) * a.W + (fs_addr - a.pad_w)) * a.xpitch : 0;  // uniform
+    const __amdgpu_buffer_rsrc_t x_srd =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.X) + tapshift, 0, kBufRecords, kBufFlags);
+    const __amdgpu_buffer_rsrc_t y_srd = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.DY), 0, kBufRecords, kBufFlags);
+    const uint32_t x_v = (uint32_t)(xr * a.xpitch + xc) * 2u, y_v = (uint32_t)(yr * a.ypitch + yk) * 2u;  // bytes
+    uint32_t x_s[LX], y_s[LY];  // scalar byte offsets of the slots' pixel rows
 #pragma unroll
-    for (int j = 0; j < LY; ++j)
-        y_off[j] = (uint32_t)(it0 * BKP + yrel0 + NW * j * RPLY) * (uint32_t)a.ypitch + (uint32_t)yk;
-    int p_left = a.pixels - it0 * BKP;  // pixels from the next step's first one to the end (uniform)
-    const uint32_t y_step = (uint32_t)(BKP * a.ypitch);
+    for (int j = 0; j < LX; ++j) x_s[j] = (uint32_t)(it0 * BKP + (wave + NW * j) * RPLX) * (uint32_t)a.xpitch * 2u;
+#pragma unroll
+    for (int j = 0; j < LY; ++j) y_s[j] = (uint32_t)(it0 * BKP + (wave + NW * j) * RPLY) * (uint32_t)a.ypitch * 2u;
+    const uint32_t x_step = (uint32_t)(BKP * a.xpitch) * 2u, y_step = (uint32_t)(BKP * a.ypitch) * 2u;
 
     // issues the loads of the next reduction step (steps are issued in order) into `stage`
     auto issue = [&](int stage) {
         uint8_t* sbase = smem_b + stage * STAGE_BYTES;
+        const bool whole = p_left >= BKP;  // uniform: every pixel of the step lies inside the slice
+        if constexpr (XMODE == 0) {
 #pragma unroll
-        for (int j = 0; j < LX; ++j) {
-            const bool ok = xrel0 < p_left - NW * j * RPLX && (unsigned)x_ih[j] < (unsigned)a.H && (unsigned)x_iw[j] < (unsigned)a.W;
-            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.X + x_off[j], zero_page),
-                                             (lds_void_ptr)(sbase + (wave + NW * j) * 1024), 16, 0, 0);
-            const int iw = x_iw[j] + dq_s;
-            const bool c1 = iw >= iw_wrap;
-            x_iw[j] = iw - (c1 ? Qs : 0);
-            const int ih = x_ih[j] + (c1 ? dp_s + a.stride_h : dp_s);
-            const bool c2 = ih >= ih_wrap;
-            x_ih[j] = ih - (c2 ? Ps : 0);
-            x_off[j] += (uint32_t)((c1 ? D0 + D1 : D0) + (c2 ? D2 : 0));
+            for (int j = 0; j < LX; ++j) {
+                const bool ok = xrel0 < p_left - NW * j * RPLX && (unsigned)x_ih[j] < (unsigned)a.H && (unsigned)x_iw[j] < (unsigned)a.W;
+                __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.X + x_off[j], zero_page),
+                                                 (lds_void_ptr)(sbase + (wave + NW * j) * 1024), 16, 0, 0);
+                const int iw = x_iw[j] + dq_s;
+                const bool c1 = iw >= iw_wrap;
+                x_iw[j] = iw - (c1 ? Qs : 0);
+                const int ih = x_ih[j] + (c1 ? dp_s + a.stride_h : dp_s);
+                const bool c2 = ih >= ih_wrap;
+                x_ih[j] = ih - (c2 ? Ps : 0);
+                x_off[j] += (uint32_t)((c1 ? D0 + D1 : D0) + (c2 ? D2 : 0));
+            }
+        } else {
+            uint32_t v[LX];
+#pragma unroll
+            for (int j = 0; j < LX; ++j) {
+                v[j] = x_v;
+                if constexpr (XMODE == 1) {
+                    const bool ok = (unsigned)x_ih[j] < (unsigned)a.H && (unsigned)x_iw[j] < (unsigned)a.W;
+                    v[j] = ok ? x_v : kBufOut;
+                    const int iw = x_iw[j] + dq_s;
+                    const bool c1 = iw >= iw_wrap;
+                    x_iw[j] = iw - (c1 ? Qs : 0);
+                    const int ih = x_ih[j] + (c1 ? dp_s + 1 : dp_s);
+                    x_ih[j] = ih - (ih >= ih_wrap ? Ps : 0);
+                }
+            }
+            if (!whole) {
+#pragma unroll
+                for (int j = 0; j < LX; ++j) v[j] = xrel0 < p_left - NW * j * RPLX ? v[j] : kBufOut;
+            }
+#pragma unroll
+            for (int j = 0; j < LX; ++j) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(x_srd, (lds_void_ptr)(sbase + (wave + NW * j) * 1024), 16, v[j], x_s[j], 0, 0);
+                x_s[j] += x_step;
+            }
+        }
+        uint32_t vy[LY];
+#pragma unroll
+        for (int j = 0; j < LY; ++j) vy[j] = y_v;
+        if (!whole) {
+#pragma unroll
+            for (int j = 0; j < LY; ++j) vy[j] = yrel0 < p_left - NW * j * RPLY ? y_v : kBufOut;
         }
 #pragma unroll
         for (int j = 0; j < LY; ++j) {
-            const bool ok = yrel0 < p_left - NW * j * RPLY;
-            __builtin_amdgcn_global_load_lds(pick_ptr(ok, a.DY + y_off[j], zero_page),
-                                             (lds_void_ptr)(sbase + XBYTES + (wave + NW * j) * 1024), 16, 0, 0);
-            y_off[j] += y_step;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(y_srd, (lds_void_ptr)(sbase + XBYTES + (wave + NW * j) * 1024), 16, vy[j], y_s[j], 0, 0);
+            y_s[j] += y_step;
         }
         p_left -= BKP;
     };
@@ -1259,34 +1350,35 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(cons
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vx[tm], vy[tn], acc[tm][tn], 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vy[tn], vx[tm], acc[tm][tn], 0, 0, 0);
+            // keep this sub-step's MFMAs ahead of the next sub-step's wait: otherwise the scheduler sinks them below
+            // it and nothing overlaps the fragment reads
+            __builtin_amdgcn_sched_barrier(0);
         });
     };
 
     const int nk = it1 - it0;
     const bool late = STAGES >= 3 && NW >= 8 && (wave & 4) != 0;
+    // Loads run STAGES - 1 steps ahead and are issued at every step, also past the slice's end (they then fetch
+    // zeros into a stage nobody reads): the number of loads in flight is the same at every wait.
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < nk) issue(s);
+    for (int s = 0; s < STAGES - 1; ++s) issue(s);
     for (int kt0 = 0; kt0 < nk; kt0 += STAGES) {
 #pragma unroll
         for (int s = 0; s < STAGES; ++s) {
-            const int kt = kt0 + s;
-            if (kt < nk) {
-                if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * LPT>();
-                else wait_vmcnt<0>();
+            if (kt0 + s < nk) {
+                wait_vmcnt<(STAGES - 2) * LPT>();
                 barrier_nofence();
                 // Waves w and w+4 share a SIMD.  With three or more stages one of them issues the next stage's
-                // loads (address arithmetic on the vector ALU) before its MFMAs and the other after, so the two
-                // phases overlap on the SIMD instead of running in lockstep.  The target buffer is the one
-                // consumed in the previous step either way.
-                const bool more = kt + STAGES - 1 < nk;
-                if (more && !late) issue((s + STAGES - 1) % STAGES);
+                // loads before its MFMAs and the other after, so the two phases overlap on the SIMD instead of
+                // running in lockstep.  The target buffer is the one consumed in the previous step either way.
+                if (!late) issue((s + STAGES - 1) % STAGES);
                 compute(s);
-                if (more && late) issue((s + STAGES - 1) % STAGES);
+                if (late) issue((s + STAGES - 1) % STAGES);
             }
         }
     }
+    wait_vmcnt<0>();  // the loads issued past the end have landed before LDS is reused or the wave ends
 
     if constexpr (KSPLIT > 1) {
         // groups 1.. park their accumulators in LDS one group at a time (the stage buffers are dead: every load was
@@ -1318,60 +1410,44 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(cons
         }
         if (kg > 0) return;
     }
-    // ---- epilogue: lane holds k (column) = lane%32 and rows 8g + 4*(lane/32) + {0..3} = 4 consecutive c
+    // ---- epilogue: the MFMA's row operand is dy, so a lane holds input channel (column) lane%32 of the 32x32 block
+    // and output channels (rows) 8g + 4*(lane/32) + {0..3}: a store instruction writes, for one output channel per
+    // half-wave, 32 consecutive input channels = 128 contiguous bytes of dw (or of the partial slab).
     float* out = a.OUT + (a.direct ? 0 : (int64_t)split * a.K * a.out_row_pitch);
+    const int hi4 = (lane >> 5) * 4;
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        const int k = n0 + wn * WTN + tn * 32 + (lane & 31);
-        if (k >= a.K) continue;
+    for (int tm = 0; tm < TM; ++tm) {
+        const int cr = cb + wm * WTM + tm * 32 + (lane & 31);  // row inside the run
+        if (cr >= run) continue;
+        const int ts = a.fold ? cr / a.CP : 0;
+        const int c = cr - ts * a.CP;
+        const int tapi = a.fold ? tb * a.S + ts : tb;
+        if (a.direct && c >= a.C) continue;
+        float inv_in = 0.f;
+        if (a.direct && a.lw && a.l_in) {
+            const float in = a.l_in[c];
+            inv_in = in > 0.f ? 1.0f / in : 0.f;
+        }
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
+        for (int tn = 0; tn < TN; ++tn) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int cr = cb + wm * WTM + tm * 32 + 8 * g + (lane >> 5) * 4;  // row inside the run
-                if (cr >= run) continue;
-                // CP is a multiple of 8 and cr of 4: the four rows share one tap
-                const int ts = a.fold ? cr / a.CP : 0;
-                const int c = cr - ts * a.CP;
-                const int tapi = a.fold ? tb * a.S + ts : tb;
-                float v0 = acc[tm][tn][4 * g + 0], v1 = acc[tm][tn][4 * g + 1];
-                float v2 = acc[tm][tn][4 * g + 2], v3 = acc[tm][tn][4 * g + 3];
-                if (a.direct) {
-                    if (c >= a.C) continue;
-                    const int64_t o = ((int64_t)k * a.RS + tapi) * a.wpitch + c;
-                    float* dst = out + o;
-                    if (a.lw) {  // uniform: regulariser folded in
-                        const float on = a.l_on ? a.l_on[k] : 0.f;
-                        const float inv_out = on > 0.f ? 1.0f / on : 0.f;
-                        float wv[4], in[4];
-                        if (a.o_vec && c + 3 < a.C) {  // whole vectors (w has the alignment and pitch of dw)
-                            const float4 w4 = *reinterpret_cast<const float4*>(a.lw + o);
-                            wv[0] = w4.x; wv[1] = w4.y; wv[2] = w4.z; wv[3] = w4.w;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) in[e] = a.l_in ? a.l_in[c + e] : 0.f;
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const bool in_range = c + e < a.C;
-                                wv[e] = in_range ? a.lw[o + e] : 0.f;
-                                in[e] = (a.l_in && in_range) ? a.l_in[c + e] : 0.f;
-                            }
+                for (int i = 0; i < 4; ++i) {
+                    const int k = n0 + wn * WTN + tn * 32 + 8 * g + hi4 + i;
+                    if (k >= a.K) continue;
+                    float v = acc[tm][tn][4 * g + i];
+                    if (a.direct) {
+                        const int64_t o = ((int64_t)k * a.RS + tapi) * a.wpitch + c;
+                        if (a.lw) {  // uniform: regulariser folded in
+                            const float on = a.l_on ? a.l_on[k] : 0.f;
+                            const float inv_out = on > 0.f ? 1.0f / on : 0.f;
+                            v += a.l_lambda * (a.lw[o] * (inv_out + inv_in));
                         }
-                        float t[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) t[e] = a.l_lambda * (wv[e] * (inv_out + (in[e] > 0.f ? 1.0f / in[e] : 0.f)));
-                        v0 += t[0]; v1 += t[1]; v2 += t[2]; v3 += t[3];
-                    }
-                    if (a.o_vec && c + 3 < a.C) {
-                        *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
+                        out[o] = v;
                     } else {
-                        dst[0] = v0;
-                        if (c + 1 < a.C) dst[1] = v1;
-                        if (c + 2 < a.C) dst[2] = v2;
-                        if (c + 3 < a.C) dst[3] = v3;
+                        out[(int64_t)k * a.out_row_pitch + tapi * a.CP + c] = v;
                     }
-                } else {
-                    *reinterpret_cast<float4*>(out + (int64_t)k * a.out_row_pitch + tapi * a.CP + c) = make_float4(v0, v1, v2, v3);
                 }
             }
         }
@@ -1379,13 +1455,13 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(cons
 #endif
 }
 
-template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1, int MINB = 1>
-inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
+template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT, int MINB, int XMODE>
+inline hipError_t launch_wgrad_dl_mode(WgradArgs& a, hipStream_t st) {
     constexpr int NT = 64 * WGM * WGN * KSPLIT;
     constexpr size_t ring = (size_t)STAGES * BKP * (BM + BN) * 2, red = KSPLIT > 1 ? (size_t)BM * BN * 4 : 0;
     constexpr size_t lds = ring > red ? ring : red;
     static_assert(lds <= 160 * 1024, "LDS capacity");
-    auto kern = k_wgrad_dl<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT, MINB>;
+    auto kern = k_wgrad_dl<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT, MINB, XMODE>;
     const int P = (int)a.P.d, Q = (int)a.Q.d;
     a.dq = BKP % Q;
     a.dp = (BKP / Q) % P;
@@ -1394,6 +1470,13 @@ inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
     if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(NT), lds, st, a);
     return hipSuccess;
+}
+
+template <int BM, int BN, int BKP, int WGM, int WGN, int STAGES, int KSPLIT = 1, int MINB = 1>
+inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
+    if (a.x_all_valid) return launch_wgrad_dl_mode<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT, MINB, 2>(a, st);
+    if (a.affine) return launch_wgrad_dl_mode<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT, MINB, 1>(a, st);
+    return launch_wgrad_dl_mode<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT, MINB, 0>(a, st);
 }
 
 }  // namespace pt
