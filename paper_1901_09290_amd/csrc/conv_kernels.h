@@ -1428,6 +1428,31 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(cons
             const float in = a.l_in[c];
             inv_in = in > 0.f ? 1.0f / in : 0.f;
         }
+        if (a.direct && a.lw) {  // uniform: regulariser folded in
+            // every weight and norm this lane needs is fetched before the first store: the stores may alias the loads
+            // as far as the compiler knows, and interleaved they would each wait out a full memory round trip
+            float wv[TN][16], io[TN][16];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int k = n0 + wn * WTN + tn * 32 + 8 * (e >> 2) + hi4 + (e & 3);
+                    const int kc = k < a.K ? k : a.K - 1;
+                    wv[tn][e] = a.lw[((int64_t)kc * a.RS + tapi) * a.wpitch + c];
+                    io[tn][e] = a.l_on ? a.l_on[kc] : 0.f;
+                }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int k = n0 + wn * WTN + tn * 32 + 8 * (e >> 2) + hi4 + (e & 3);
+                    if (k >= a.K) continue;
+                    const float inv_out = io[tn][e] > 0.f ? 1.0f / io[tn][e] : 0.f;
+                    out[((int64_t)k * a.RS + tapi) * a.wpitch + c] =
+                        acc[tm][tn][e] + a.l_lambda * (wv[tn][e] * (inv_out + inv_in));
+                }
+            continue;
+        }
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
 #pragma unroll
@@ -1436,18 +1461,11 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(cons
                 for (int i = 0; i < 4; ++i) {
                     const int k = n0 + wn * WTN + tn * 32 + 8 * g + hi4 + i;
                     if (k >= a.K) continue;
-                    float v = acc[tm][tn][4 * g + i];
-                    if (a.direct) {
-                        const int64_t o = ((int64_t)k * a.RS + tapi) * a.wpitch + c;
-                        if (a.lw) {  // uniform: regulariser folded in
-                            const float on = a.l_on ? a.l_on[k] : 0.f;
-                            const float inv_out = on > 0.f ? 1.0f / on : 0.f;
-                            v += a.l_lambda * (a.lw[o] * (inv_out + inv_in));
-                        }
-                        out[o] = v;
-                    } else {
+                    const float v = acc[tm][tn][4 * g + i];
+                    if (a.direct)
+                        out[((int64_t)k * a.RS + tapi) * a.wpitch + c] = v;
+                    else
                         out[(int64_t)k * a.out_row_pitch + tapi * a.CP + c] = v;
-                    }
                 }
             }
         }

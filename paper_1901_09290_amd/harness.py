@@ -401,7 +401,11 @@ class ReconfigModel:
                              self.keep[e])
             B.compact_plan(self.keep[e], edge.n, self.idx[e], self.counts[e:e + 1])
 
-    def compact(self, cnt: Optional[np.ndarray] = None, per_call: bool = False) -> None:
+    def compact_activations(self, cnt: np.ndarray) -> None:
+        """Only the saved activations' gather of compact(): one multi-job call."""
+        self.compact(cnt, only_activations=True)
+
+    def compact(self, cnt: Optional[np.ndarray] = None, per_call: bool = False, only_activations: bool = False) -> None:
         """Gathers every tensor with the planned index lists.  The survivor counts size the outputs: they
         are read back here (one synchronising copy) unless the caller already holds them.  Weights, momentum
         the per-channel vectors and the saved activations of all layers go through the multi-job calls."""
@@ -432,7 +436,11 @@ class ReconfigModel:
                     B.compact_nhwc(self.act[i], s.N * s.H * s.W, s.C, wp, ic, Cp, self.act_out[i], op)
                 else:
                     ajobs.append(B.gather_nhwc(self.act[i], s.N * s.H * s.W, s.C, wp, ic, Cp, self.act_out[i], op))
-        if not per_call:
+        if only_activations:
+            assert not per_call
+            if ajobs:
+                B.compact_nhwc_batched(ajobs)
+        elif not per_call:
             B.compact_weights_batched(wjobs)
             B.compact_vector_batched(vjobs)
             if ajobs:
