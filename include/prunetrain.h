@@ -177,7 +177,8 @@ int32_t pt_conv_bwd_weight_lasso(const pt_conv_desc* d, const uint16_t* x, const
                                  void* ws, size_t ws_bytes, void* stream);
 
 /* Multi-layer forms: the regulariser of Eq. 2 runs over every layer of the network each iteration and a
- * layer's weights are small, so all layers go into a few launches (32 layers per launch).  `layers`
+ * layer's weights are small, so all layers go into a few launches (64 layers per launch pair for the norms, 32 per launch for the
+ * gradient and the optimizer step).  `layers`
  * is a HOST array of n descriptors whose pointers are device pointers; per layer the semantics,
  * limits and determinism are those of the single-layer calls above.  The workspace is split between
  * the layers in array order. */

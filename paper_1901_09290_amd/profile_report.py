@@ -153,10 +153,12 @@ def cmd_layers(a) -> None:
     o.append("One call = all kernels the entry point launches (conv_bwd_data: one launch per stride-parity class; conv_bwd_weight_lasso:")
     o.append("main kernel + reduction pass when the pixel axis is split).  us = sum of the kernels' durations in the trace (launch gaps")
     o.append("excluded); calls run one at a time in network order, so inputs are not cache-resident from a previous repetition.")
-    o.append("GF = 2*N*P*Q*K*C*R*S; MB = algorithmic bytes (x + y + w in bf16 once; bwd_weight: x + dy once, dw fp32 once).")
-    o.append("roof_us = max(MB / %.0f GB/s, GF / %.0f TFLOP/s); bound = which of the two; frac = roof_us / us." % (hbm / 1e9, mfma / 1e12))
+    o.append("GF = 2*N*P*Q*K*C*R*S per call; algorithmic bytes = x + y + w in bf16 once (bwd_weight: x + dy once, dw fp32 once; MB_fwd is")
+    o.append("the forward call's); TF/s and GB/s are GF and algorithmic bytes over us.")
+    o.append("roof = max(bytes / %.0f GB/s, GF / %.0f TFLOP/s); bound = which of the two; frac = roof / us." % (hbm / 1e9, mfma / 1e12))
     if traffic:
-        o.append("traf = HBM bytes moved by the call's kernels (FETCH_SIZE and WRITE_SIZE scaled by the copy probe) / algorithmic bytes.")
+        o.append("traf = bytes the call's kernels move between the L2s and the fabric (FETCH_SIZE and WRITE_SIZE scaled by the copy probe; reads")
+        o.append("that the Infinity Cache serves are counted too, e.g. weights that each of the eight L2s fetches for itself) / algorithmic bytes.")
     o.append("Networks: full = published widths; pruned = ragged widths (keep fraction U[0.4,0.9] per channel edge, never a multiple of 16);")
     o.append("pruned_up64 = the pruned widths rounded up to the next multiple of 64 (the padded twin of every pruned layer).")
     o.append("")
@@ -168,49 +170,62 @@ def cmd_layers(a) -> None:
     for i, r in enumerate(rec):
         r["traf"] = traffic[i] / r["bytes"] if traffic else None
     idx = {(r["net"], r["kind"], r["layer"]): r for r in rec}
-    for net in man["nets"]:
-        for kind in ("fwd", "bwd_data", "bwd_weight", "bwd_weight_lasso"):
-            rows = [r for r in rec if r["net"] == net and r["kind"] == kind]
-            if not rows:
-                continue
-            o.append("== %s / %s ==" % (net, kind))
-            hdr = "%-18s %-38s %2s %8s %7s %8s %7s %7s %8s %5s %6s" % ("layer", "N,H,W,C,K,R,S,stride,pad", "nk", "GF", "MB", "us", "TF/s", "GB/s", "roof_us", "bound", "frac")
-            if traffic:
-                hdr += " %5s" % "traf"
-            if net == "pruned":
-                hdr += " %9s %9s" % ("up64_us", "us/up64")
-            o.append(hdr)
-            for r in rows:
-                line = "%-18s %-38s %2d %8.2f %7.2f %8.1f %7.0f %7.0f %8.1f %5s %6.3f" % (
-                    r["layer"], ",".join(str(v) for v in r["shape"]), r["n_k"], r["flops"] / 1e9, r["bytes"] / 1e6, r["us"],
-                    r["flops"] / r["us"] / 1e6, r["bytes"] / r["us"] / 1e3, r["roof"], r["bound"], r["roof"] / r["us"])
+    kinds = ("fwd", "bwd_data", "bwd_weight_lasso")
+    short_kind = {"fwd": "fwd", "bwd_data": "bwd_data", "bwd_weight_lasso": "bwd_weight (regulariser folded in)"}
+    for net in ("full", "pruned"):
+        layers = [r["layer"] for r in rec if r["net"] == net and r["kind"] == "fwd"]
+        if not layers:
+            continue
+        twin = net == "pruned"
+        o.append("== %s widths: one row per layer, then per call: %s ==" % (net, "us TF/s GB/s frac bound(h=hbm,m=mfma)" + (" traf" if traffic else "")
+                                                                       + (" t/t64 (time / time of the padded twin)" if twin else "")))
+        o.append("%-15s %-26s %7s %7s | %s" % ("layer", "H,W,C,K,R,stride", "GF", "MB_fwd", " | ".join("%-*s" % (31 + (5 if traffic else 0) + (5 if twin else 0), short_kind[k][:36]) for k in kinds)))
+        for name in layers:
+            f = idx[(net, "fwd", name)]
+            sh = f["shape"]
+            cells = []
+            for k in kinds:
+                r = idx.get((net, k, name))
+                width = 31 + (5 if traffic else 0) + (5 if twin else 0)
+                if r is None:
+                    cells.append("%-*s" % (width, "-"))
+                    continue
+                c = "%6.1f %4.0f %5.0f %5.3f %s" % (r["us"], r["flops"] / r["us"] / 1e6, r["bytes"] / r["us"] / 1e3, r["roof"] / r["us"], r["bound"][0])
                 if traffic:
-                    line += " %5.2f" % r["traf"]
-                if net == "pruned":
-                    tw = idx.get(("pruned_up64", kind, r["layer"]))
-                    if tw:
-                        line += " %9.1f %9.2f" % (tw["us"], r["us"] / tw["us"])
-                o.append(line)
+                    c += " %4.2f" % r["traf"]
+                if twin:
+                    tw = idx.get(("pruned_up64", k, name))
+                    c += " %4.2f" % (r["us"] / tw["us"]) if tw else "    -"
+                cells.append("%-*s" % (width, c))
+            o.append("%-15s %-26s %7.2f %7.2f | %s" % (name, "%d,%d,%d,%d,%d,%d" % (sh[1], sh[2], sh[3], sh[4], sh[5], sh[7]), f["flops"] / 1e9,
+                                                    f["bytes"] / 1e6, " | ".join(cells)))
+        for k in kinds:
+            rows = [r for r in rec if r["net"] == net and r["kind"] == k]
             us, roof = sum(r["us"] for r in rows), sum(r["roof"] for r in rows)
             fl, by = sum(r["flops"] for r in rows), sum(r["bytes"] for r in rows)
-            o.append("%-18s %-38s %2s %8.1f %7.1f %8.1f %7.0f %7.0f %8.1f %5s %6.3f" % (
-                "total", "", "", fl / 1e9, by / 1e6, us, fl / us / 1e6, by / us / 1e3, roof, "", roof / us))
-            o.append("")
+            o.append("total %-34s %4d calls %8.1f GF %8.1f MB %8.1f us %5.0f TF/s %5.0f GB/s; sum of the layers' roofs %7.1f us -> fraction %.3f%s" % (
+                short_kind[k], len(rows), fl / 1e9, by / 1e6, us, fl / us / 1e6, by / us / 1e3, roof, roof / us,
+                ("; measured / algorithmic traffic %.2f" % (sum(traffic[i] for i, r in enumerate(rec) if r["net"] == net and r["kind"] == k) / by)) if traffic else ""))
+        rows = [r for r in rec if r["net"] == net and r["kind"] == "bwd_weight"]
+        if rows:
+            o.append("      (the weight gradient without the regulariser, same layers: %.1f us)" % sum(r["us"] for r in rows))
+        o.append("")
     # ragged widths against their padded twins
     o.append("== ragged widths against their padded twins (pruned vs pruned_up64, same layer, same call) ==")
-    o.append("time ratio = pruned us / twin us; FLOP ratio = pruned GF / twin GF; a ragged layer keeps the twin's efficiency per FLOP when the two match")
-    for kind in ("fwd", "bwd_data", "bwd_weight", "bwd_weight_lasso"):
+    o.append("A ragged layer has fewer FLOPs and fewer bytes than its twin; it should never take longer.  time ratio = pruned us / twin us,")
+    o.append("next to the FLOP and algorithmic-byte ratios of the two networks; then the layers that take more than 1.15x their twin's time.")
+    for kind in kinds:
         pr_ = [r for r in rec if r["net"] == "pruned" and r["kind"] == kind]
         tw_ = [idx[("pruned_up64", kind, r["layer"])] for r in pr_]
         if not pr_:
             continue
         tp, tt = sum(r["us"] for r in pr_), sum(r["us"] for r in tw_)
         fp, ft = sum(r["flops"] for r in pr_), sum(r["flops"] for r in tw_)
-        worst = sorted(((r["us"] / t["us"]) / (r["flops"] / t["flops"]), r["layer"]) for r, t in zip(pr_, tw_))
-        slower = [(x, n) for x, n in worst if x > 1.15]
-        o.append("%-17s time ratio %.3f, FLOP ratio %.3f -> time per FLOP %.3f of the twin's; layers more than 15%% slower per FLOP than their twin: %d of %d%s" % (
-            kind, tp / tt, fp / ft, (tp / tt) / (fp / ft), len(slower), len(pr_),
-            (" (worst: " + ", ".join("%s x%.2f" % (n, x) for x, n in slower[-4:][::-1]) + ")") if slower else ""))
+        bp, bt = sum(r["bytes"] for r in pr_), sum(r["bytes"] for r in tw_)
+        slower = sorted(((r["us"] / t["us"], r["layer"]) for r, t in zip(pr_, tw_) if r["us"] > 1.15 * t["us"]), reverse=True)
+        o.append("%-17s time ratio %.3f (FLOP ratio %.3f, byte ratio %.3f); slower than 1.15x the twin: %d of %d layers%s" % (
+            kind, tp / tt, fp / ft, bp / bt, len(slower), len(pr_),
+            (" (" + ", ".join("%s x%.2f" % (n, x) for x, n in slower[:6]) + ")") if slower else ""))
     _write(a.out, o)
 
 
@@ -228,6 +243,7 @@ def cmd_traffic(a) -> None:
     o.append("  python3 -m paper_1901_09290_amd.profile_report traffic --manifest <out>/f/manifest.json --fetch <out>/f/..._counter_collection.csv --write <out>/w/..._counter_collection.csv --out <this file>")
     o.append("Scale factors from the copy probe (a plain elementwise kernel that reads 1 GiB and writes 1 GiB):")
     o.append("  FETCH_SIZE: %.1f bytes per unit;  WRITE_SIZE: %.1f bytes per unit" % (ff, wf))
+    o.append("The counters see what the L2s exchange with the fabric: reads served by the Infinity Cache (256 MB) are counted like HBM reads.")
     o.append("Only the calls of the two networks the benchmark's step runs (full and pruned widths) are counted below.")
     o.append("")
     agg = collections.defaultdict(lambda: [0, 0.0, 0.0])

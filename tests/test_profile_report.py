@@ -20,7 +20,7 @@ def _manifest(tmp_path):
     for net in ("full", "pruned", "pruned_up64"):
         calls += [
             {"net": net, "kind": "fwd", "layer": "a", "shape": [64, 56, 56, 64, 64, 1, 1, 1, 0], "flops": 2 * 10**9, "bytes": 8 * 10**7},
-            {"net": net, "kind": "bwd_data", "layer": "b", "shape": [64, 56, 56, 64, 64, 3, 3, 2, 1], "flops": 25 * 10**9, "bytes": 4 * 10**7},
+            {"net": net, "kind": "bwd_data", "layer": "a", "shape": [64, 56, 56, 64, 64, 1, 1, 1, 0], "flops": 25 * 10**9, "bytes": 4 * 10**7},
             {"net": net, "kind": "bwd_weight_lasso", "layer": "a", "shape": [64, 56, 56, 64, 64, 1, 1, 1, 0], "flops": 2 * 10**9, "bytes": 8 * 10**7},
         ]
     man = {"batch": 64, "marker": "k_zero_groups", "nets": ["full", "pruned", "pruned_up64"], "calls": calls,
@@ -87,13 +87,15 @@ def test_layer_table_figures(tmp_path):
     pr.main(["layers", "--manifest", mp, "--trace", t, "--out", out])
     text = open(out).read()
     assert "kernel sources: 0123456789abcdef" in text
-    row = [l for l in text.splitlines() if l.startswith("a ") and ",1,1,1,0" in l][0].split()
-    # fwd of layer a: 2 GF and 80 MB in 20 us -> 100 TFLOP/s, 4000 GB/s; roof = 80 MB / 8 TB/s = 10 us (hbm), frac 0.5
-    assert row[2] == "1" and float(row[5]) == 20.0 and float(row[6]) == 100 and float(row[7]) == 4000
-    assert float(row[8]) == 10.0 and row[9] == "hbm" and float(row[10]) == 0.5
-    b = [l for l in text.splitlines() if l.startswith("b ")][0].split()
-    # bwd_data of layer b: 25 GF in 4 x 5 us; roof = 25 GF / 2.5 PFLOP/s = 10 us (mfma)
-    assert b[2] == "4" and float(b[5]) == 20.0 and b[9] == "mfma" and float(b[10]) == 0.5
+    row = [l for l in text.splitlines() if l.startswith("a ")][0]
+    fwd, bwd, wgrad = [c.split() for c in row.split("|")[1:]]
+    # fwd: 2 GF and 80 MB in 20 us -> 100 TFLOP/s, 4000 GB/s; roof = 80 MB / 8 TB/s = 10 us (hbm), frac 0.5
+    assert [float(v) for v in fwd[:4]] == [20.0, 100.0, 4000.0, 0.5] and fwd[4] == "h"
+    # bwd_data: 25 GF in 4 x 5 us; roof = 25 GF / 2.5 PFLOP/s = 10 us (mfma)
+    assert float(bwd[0]) == 20.0 and float(bwd[3]) == 0.5 and bwd[4] == "m"
+    # weight gradient: main kernel 30 us + reduction 4 us
+    assert float(wgrad[0]) == 34.0
+    assert "total fwd" in text and "2 calls" not in text
 
 
 def test_traffic_is_scaled_by_the_copy_probe_and_read_back(tmp_path):
