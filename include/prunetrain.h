@@ -225,7 +225,7 @@ int32_t pt_group_lasso_grad_batched(const pt_layer_lasso* layers, int32_t n, flo
  *   g = dw + weight_decay*w + lambda*w*(a/out_norm[k] + b/in_norm[c])     (a zero norm contributes 0)
  *   mom = momentum*mom + g ;   w = w - lr*mom.
  * dw is the loss gradient WITHOUT the regulariser (what pt_conv_bwd_weight wrote) and is not modified; the norms
- * are those of the weights before the step.  `layers`: HOST array, device pointers inside; 32 layers per launch. */
+ * are those of the weights before the step.  `layers`: HOST array, device pointers inside; any n (32 layers per launch). */
 typedef struct pt_layer_update {
     float* w;              /* [K][RS][w_cpitch] */
     const float* dw;       /* same shape */

@@ -368,16 +368,17 @@ inline hipError_t launch_igemm_cfg(IgemmArgs& a, hipStream_t st) {
 // ------------------------------------------------------------------------------------------- //
 // forward / input-gradient implicit GEMM with direct global->LDS loads (vector path)
 // ------------------------------------------------------------------------------------------- //
-// Same problem mapping as k_igemm, different data movement: 16-byte global loads land in LDS without
-// passing through registers (global_load_lds_dwordx4), so several reduction steps can be in flight
+// Same problem mapping as k_igemm, different data movement: 16-byte loads land in LDS without
+// passing through registers (buffer_load_dwordx4 ... lds), so several reduction steps can be in flight
 // per workgroup at no register cost.  A wave-level load fills 1 KiB of LDS contiguously (lane l ->
 // bytes [16l, 16l+16)), i.e. 8 tile rows of BK = 64 elements; rows are unpadded and the eight 16-byte
 // chunks of a row are XOR-swizzled with ((row >> 1) & 7) so that the MFMA operand reads (16 consecutive
 // rows, same logical chunk) fall into 16 different bank groups.  The swizzle is applied on the global
 // side: the lane that owns physical chunk p of a row fetches logical chunk p ^ swz(row).
-// Taps outside the image and chunks past the channel count fetch from a 16-byte zero page.  RAGGED = the channel
-// count is not a multiple of 64 (the last block of a run is partly zero page); TAIL = in addition some 8-chunk
-// ends in undefined padding elements, which are cleared in registers before the MFMAs (see the kernel).
+// Taps outside the image and chunks past the channel count are fetched as zeros (an out-of-range buffer offset, see
+// the kernel).  RAGGED = the channel count is not a multiple of 64 (the last block of a run is partly zeros); TAIL = in
+// addition some 8-chunk ends in undefined padding elements, which are cleared in LDS before the stage is published.
+// The 16-byte zero page below serves the weight-gradient kernel's general gather, which still uses per-lane addresses.
 __device__ __attribute__((aligned(16))) uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
@@ -540,7 +541,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
         const uint8_t* sA = smem_b + stage * STAGE_BYTES;
         const uint8_t* sB = sA + BM * 128;
         // One stage = BK/16 sub-steps of (fragment reads, MFMAs); all sub-steps always run (chunks past the channel
-        // count were fetched from the zero page) and the body has no branches: a branch per sub-step costs the
+        // count were fetched as zeros) and the body has no branches: a branch per sub-step costs the
         // compiler's schedule far more than the work it would skip.
         bf16x8 fw[2][TN], fp[2][TM];
         auto read_frags = [&](int ks, int b) {
@@ -1085,10 +1086,10 @@ inline hipError_t launch_wgrad_cfg(WgradArgs& a, hipStream_t st) {
 // Output tile: BM input channels of ONE filter tap x BN output channels; reduction over output pixels
 // in steps of BKP.  Both tiles are pixel-major in LDS exactly as they sit in memory (a pixel row of
 // the x tile is BM channels = 2*BM bytes), filled by 16-byte global->LDS loads and read back with the
-// transpose read.  32-byte units of a row are XOR-swizzled with the pixel row so that the four pixel
-// rows a 16-lane group touches in one transpose read fall into different banks.  Pixels whose tap
-// falls outside the image, and pixels past the end, fetch from the zero page (both operands, so no
-// garbage ever meets a zero).  Channel chunks past the channel count re-read the last valid chunk:
+// transpose read.  The 32-byte units of a row are permuted with the pixel row (see unit_phys in the kernel) so that
+// the eight units the first and the second half-wave touch in one transpose read fall into different banks.  Pixels
+// whose tap falls outside the image, and pixels past the end, are fetched as zeros (an out-of-range buffer offset, or
+// the zero page in the general gather; both operands, so no garbage ever meets a zero).  Channel chunks past the channel count re-read the last valid chunk:
 // they only feed accumulator rows/columns that are never stored.
 // Transposing LDS read issued as inline assembly.  The compiler cannot see which LDS bytes the intrinsic
 // form touches and therefore waits for every outstanding global->LDS load before it, which serialises the
@@ -1150,16 +1151,32 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(cons
     const int it0 = split * a.iters_per_split;
     const int it1 = min(a.iters_total, it0 + a.iters_per_split);
 
-    // swizzle of the 32-byte units of a pixel row (see above); constant per lane over its loads
-    auto swz = [](int row, int rb) { return rb == 256 ? (row & 7) : ((row >> 1) & 3); };
+    // Placement of the 32-byte units (16 channels) of a pixel row, constant per lane over its loads.  A transposing
+    // read takes, per 16-lane group, one unit from each of four consecutive pixel rows, and the LDS serves two such
+    // groups per cycle (64 banks of 4 bytes): lanes 0-31 read units u and u + 1 (u even) of the same four rows, lanes
+    // 32-63 the same of rows + 8.  So the low bit of the logical unit becomes the high bit of the physical one (u and
+    // u + 1 land in different halves of a 256-byte bank line) and the remaining bits are XOR-ed with the row so that
+    // the four rows of a group differ: 2.5 instead of 4.1 cycles per read against XOR-ing all bits with the row.
+    // 128-byte rows: consecutive rows already alternate between the halves of a bank line.
+    auto unit_phys = [](int u, int row, int rb) {
+        return rb == 256 ? (((u >> 1) | ((u & 1) << 2)) ^ (row & 3)) : ((((u & 1) << 1) | (u >> 1)) ^ ((row >> 1) & 1));
+    };
+    auto unit_logical = [](int p, int row, int rb) {  // inverse of unit_phys in u
+        if (rb == 256) {
+            const int q = p ^ (row & 3);
+            return ((q & 3) << 1) | (q >> 2);
+        }
+        const int q = p ^ ((row >> 1) & 1);
+        return ((q & 1) << 1) | (q >> 1);
+    };
     // x tile: this lane's row inside a wave-level load, and the logical 8-channel chunk it fetches
     const int xr = lane / CPRX, xpc = lane % CPRX;
-    const int xlc = ((((xpc >> 1) ^ swz(wave * RPLX + xr, RBX)) << 1) | (xpc & 1));
+    const int xlc = (unit_logical(xpc >> 1, wave * RPLX + xr, RBX) << 1) | (xpc & 1);
     const int xc = min(cb + xlc * 8, run - 8);     // clamp: chunks past the run are never stored
     const int fs = a.fold ? xc / a.CP : tb - fr * a.S;   // filter column of this lane's chunk
     const int fs_addr = a.fold ? 0 : fs;           // folded: the column offset is part of xc
     const int yr = lane / CPRY, ypc = lane % CPRY;
-    const int ylc = ((((ypc >> 1) ^ swz(wave * RPLY + yr, RBY)) << 1) | (ypc & 1));
+    const int ylc = (unit_logical(ypc >> 1, wave * RPLY + yr, RBY) << 1) | (ypc & 1);
     const int yk = min(n0 + ylc * 8, a.KP - 8);
     const uint16_t* zero_page = reinterpret_cast<const uint16_t*>(g_zero16);
 
@@ -1300,12 +1317,12 @@ __global__ __launch_bounds__(64 * WGM * WGN * KSPLIT, MINB) void k_wgrad_dl(cons
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int u = (wm * WTM + tm * 32) / 16 + tr_u;
-            ax[tm][h] = lds_base + (uint32_t)((r0 + r) * RBX + ((u ^ swz(r, RBX)) << 5) + tr_b);
+            ax[tm][h] = lds_base + (uint32_t)((r0 + r) * RBX + (unit_phys(u, r, RBX) << 5) + tr_b);
         }
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const int u = (wn * WTN + tn * 32) / 16 + tr_u;
-            ay[tn][h] = lds_base + (uint32_t)((r0 + r) * RBY + ((u ^ swz(r, RBY)) << 5) + tr_b);
+            ay[tn][h] = lds_base + (uint32_t)((r0 + r) * RBY + (unit_phys(u, r, RBY) << 5) + tr_b);
         }
     }
     static_assert(NKS == 1 || NRD < 16, "fragment reads per sub-step must fit the lgkmcnt field");
