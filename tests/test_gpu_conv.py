@@ -117,6 +117,11 @@ MANY_TILES = [
     ((5, 128, 130, 64, 64, 3, 1, 1), False),    # nine steps per tile, image borders
     ((17, 128, 160, 64, 64, 2, 2, 0), False),   # strided: four input-gradient classes, scattered destination pixels
     ((6, 256, 256, 3, 64, 7, 2, 3), True),      # image-like input, filter rows folded, zero padding vouched for
+    # 1 x 1 layers with several resident rounds of tiles: ragged channel counts on either side, an odd pixel count (the
+    # last tile is partial and the last pixel has no partner in the paired stores)
+    ((17, 55, 55, 40, 209, 1, 1, 0), True),     # forward: 402 x 2 tiles of 128 x 128, one partial reduction step
+    ((24, 55, 55, 209, 33, 1, 1, 0), True),     # forward: 568 narrow tiles, four steps; input gradient: 568 x 2 tiles
+    ((9, 128, 128, 72, 136, 1, 1, 0), False),   # channel counts multiples of 8 but not of 64, padding not vouched for
 ]
 
 
