@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256) void k_zero_groups_multi(const MaskJobs jobs, 
 
 // One workgroup per edge: keep mask from the members' zero masks, then the ascending survivor list by a
 // chunked exclusive scan (wavefront ballots), all inside the workgroup.
-constexpr int kMaxPlanEdges = 32, kMaxPlanMembers = 300;
+constexpr int kMaxPlanEdges = 64, kMaxPlanMembers = 320;  // 5 KB of kernel arguments: a ResNet-50 (37 edges) is one launch
 struct PlanEdge {
     uint8_t* keep;
     int* idx;
@@ -319,7 +319,7 @@ __global__ __launch_bounds__(1024) void k_reconcile_plan_multi(const PlanJobs jo
     if (tid == 0) *e.n_keep = base_s;
 }
 
-constexpr int kMaxVecJobs = 80;
+constexpr int kMaxVecJobs = 224;  // 9 KB of kernel arguments: four vectors for each of 53 layers in one launch
 struct VecJob {
     const void* v;
     const int* idx;
@@ -344,7 +344,7 @@ __global__ __launch_bounds__(256) void k_compact_vector_multi(const VecJobs jobs
     }
 }
 
-constexpr int kMaxWJobs = 56;
+constexpr int kMaxWJobs = 112;  // 7 KB of kernel arguments: weights and momentum of 53 layers in one launch
 struct WJob {
     const float* w;
     const int* idxK;

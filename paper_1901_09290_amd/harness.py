@@ -368,6 +368,7 @@ class ReconfigModel:
         self.bn_out = [[torch.zeros_like(v) for v in vs] for vs in self.bn]
         self.act_out = [torch.zeros_like(t) for t in self.act]
         self.new_counts: Optional[np.ndarray] = None
+        self.side = torch.cuda.Stream()   # compaction of the small tensors beside the activation gather
         # whole-network job tables of the multi-job calls (built once; they hold device pointers only)
         mask_jobs = []
         for i, s in enumerate(self.specs):
@@ -441,10 +442,16 @@ class ReconfigModel:
             if ajobs:
                 B.compact_nhwc_batched(ajobs)
         elif not per_call:
-            B.compact_weights_batched(wjobs)
-            B.compact_vector_batched(vjobs)
+            # the weight-shaped tensors and the per-channel vectors are a few launch-bound kernels over 64 MB; they run
+            # on a side stream beside the activation gather, which keeps the memory system busy for 0.3 ms by itself
+            main = torch.cuda.current_stream()
+            self.side.wait_stream(main)
+            with torch.cuda.stream(self.side):
+                B.compact_weights_batched(wjobs)
+                B.compact_vector_batched(vjobs)
             if ajobs:
                 B.compact_nhwc_batched(ajobs)
+            main.wait_stream(self.side)
 
     def sweep(self, thr: float) -> None:
         self.detect(thr)

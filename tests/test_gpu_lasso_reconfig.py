@@ -380,6 +380,46 @@ def test_multi_job_reconfiguration_equals_single_calls_and_oracle():
                 assert np.array_equal(o.cpu().numpy()[:Kp], oracle.compact_vector(v.cpu().numpy(), ik))
 
 
+def test_more_jobs_than_one_launch_holds():
+    """A chain of 130 tiny layers: more edges, weight-shaped tensors, per-channel vectors and activations than the job
+    tables of one launch hold (64 / 112 / 224 / 64), so every multi-job call splits; results equal the single calls."""
+    from paper_1901_09290_amd import harness as hz
+    rng = np.random.Generator(np.random.PCG64(91))
+    n_layers = 130
+    widths = [int(rng.integers(9, 41)) for _ in range(n_layers)]
+    specs, edges = [], []
+    c_in = 3
+    for i, k in enumerate(widths):
+        specs.append(wl.ConvSpec(f"c{i}", 1, 5, 5, c_in, k, 1, 1, 1, 0, None if i == 0 else i - 1,
+                                 i if i + 1 < n_layers else None, first=(i == 0)))
+        if i + 1 < n_layers:
+            edges.append(wl.Edge(f"e{i}", k, [i], [i + 1]))
+        c_in = k
+    zero_sets = wl.zeroed_channel_sets(edges, 0.3, rng)
+    weights = wl.network_weights(specs, edges, zero_sets, rng)
+    a = hz.ReconfigModel(specs, edges, weights, seed=5)
+    b = hz.ReconfigModel(specs, edges, weights, seed=5)
+    a.detect(1e-6)
+    a.compact()
+    b.detect_per_call(1e-6)
+    b.compact(per_call=True)
+    torch.cuda.synchronize()
+    assert a.new_counts.tolist() == [e.n - z.size for e, z in zip(edges, zero_sets)]
+    assert np.array_equal(a.new_counts, b.new_counts)
+    for ta, tb in zip(a.keep + a.idx + a.zo + a.zi + a.w_out + a.mom_out + a.act_out + [v for vs in a.bn_out for v in vs],
+                      b.keep + b.idx + b.zo + b.zi + b.w_out + b.mom_out + b.act_out + [v for vs in b.bn_out for v in vs]):
+        assert torch.equal(ta, tb)
+    for i in (0, 63, 64, 111, 112, 129):      # layers on either side of the table boundaries, against the oracle
+        s = specs[i]
+        ik = oracle.compact_plan(a.keep[s.out_edge].cpu().numpy()) if s.out_edge is not None else None
+        ic = oracle.compact_plan(a.keep[s.in_edge].cpu().numpy()) if s.in_edge is not None else None
+        Kp = s.K if ik is None else ik.size
+        Cp = s.C if ic is None else ic.size
+        op = hz.pitch8(Cp)
+        got = a.w_out[i].reshape(-1)[: Kp * op].reshape(Kp, 1, 1, op).cpu().numpy()[..., :Cp]
+        assert np.array_equal(got, oracle.compact_weights(weights[i], ik, ic).astype(np.float32))
+
+
 def test_regulariser_value_matches_oracle_and_is_deterministic():
     """GroupLassoReg over a whole network (ResNet-32 shapes + a 100-layer stack that needs two launches):
     device fp64 sum of the device's fp32 norms vs the oracle's fp64 sum of fp64 norms, 1e-5 relative; exact
