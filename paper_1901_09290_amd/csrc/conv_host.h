@@ -139,10 +139,12 @@ struct WgradPlan {
 };
 constexpr int kWgBM = 128, kWgBN = 128, kWgBK = 32;  // register-staged kernel
 constexpr int kWgDlBKP = 64;                          // direct kernel: pixels per reduction step
-#ifndef PT_WG_BKP_BIG
-#define PT_WG_BKP_BIG 64
-#endif
-constexpr int kWgDlBKPBig = PT_WG_BKP_BIG;            // the same for 128 x 128 tiles
+// The same for 128 x 128 tiles: 32 pixels, five stages deep = 80 KB of LDS.  A step of 64 pixels at three stages
+// (96 KB) is 4 % faster when the kernel runs alone, but a workgroup of that size shares a CU's 160 KB with no
+// workgroup of the input-gradient kernel's three-stage form (72 KB) and only just with its two-stage form (64 KB);
+// weight gradients are meant to run beside the input-gradient chain, and there the smaller footprint wins: full-width
+// train step -2.2 %, pruned +0.6 % (A/B on one box, three runs each; 64 KB in four stages: -1.9 % / +0.9 %).
+constexpr int kWgDlBKPBig = 32;
 // Workgroups per launch the split count aims at (128x128 tiles: kWgTargetBlocksBig).  Well below the 512 resident
 // slots on purpose: weight gradients of different layers are independent and are meant to run side by side on
 // several streams, so one launch need not fill the chip, and every split costs a tile of fp32 partial sums written
@@ -240,10 +242,7 @@ inline hipError_t launch_wgrad(WgradArgs& a, const WgradPlan& p, bool vec, hipSt
         return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2>(a, st);
     }
     // wave grids and pipeline depths from measurements on ResNet-50 shapes
-    if (p.BM == 128 && p.BN == 128) {
-        if constexpr (kWgDlBKPBig == 128) return launch_wgrad_dl_cfg<128, 128, 128, 2, 2, 2, 2>(a, st);
-        else return launch_wgrad_dl_cfg<128, 128, kWgDlBKP, 2, 2, 3, 2>(a, st);
-    }
+    if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKPBig, 2, 2, 5, 2>(a, st);
     if (p.BM == 64 && p.BN == 128) return launch_wgrad_dl_cfg<64, 128, kWgDlBKP, 2, 2, 3, 2>(a, st);
     if (p.BM == 128 && p.BN == 64) return launch_wgrad_dl_cfg<128, 64, kWgDlBKP, 2, 2, 3, 2>(a, st);
     return launch_wgrad_dl_cfg<64, 64, kWgDlBKP, 2, 2, 4, 2>(a, st);
