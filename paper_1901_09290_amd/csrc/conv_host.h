@@ -96,6 +96,10 @@ inline IgemmArgs make_bwd_data_args(const pt_conv_desc* d, const BwdClass& c, in
     a.fold = 0; a.TSm = c.TS; a.Creal = d->K; a.Cfold = make_fastdiv((uint32_t)kpitch);
     a.d_vec = (d->x_cpitch % 4 == 0) && (((uintptr_t)dx & 7) == 0);
     a.d_vec16 = (d->x_cpitch % 8 == 0) && aligned16(dx);
+#ifndef PT_BWD_EDGE_PRIO
+#define PT_BWD_EDGE_PRIO 2
+#endif
+    a.edge_prio = PT_BWD_EDGE_PRIO;
     return a;
 }
 

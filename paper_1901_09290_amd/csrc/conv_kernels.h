@@ -134,6 +134,10 @@ struct IgemmArgs {
     // every row, a reduction step's offset minus a_smin is non-negative for every step (both in elements; the
     // buffer's base address absorbs the two shifts).  a_all_valid: no tap of any row ever leaves the source image.
     int a_guard, a_smin, a_all_valid;
+    // Direct kernel: wave priority outside the reduction loop (inside it is 2).  0 for a launch that runs alone; the
+    // input gradient, which is meant to run beside weight gradients of other layers, keeps its set-up and its stores
+    // ahead of them too.
+    int edge_prio;
 };
 
 // Fills tail_kv / tail_nvalid (see IgemmArgs) for the direct kernel's 64-channel blocks.
@@ -413,6 +417,8 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED, bool TAIL = RAGGED, bool STATS = false, bool AV = false>
 __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
+    if (a.edge_prio == 2) __builtin_amdgcn_s_setprio(2);
+    else if (a.edge_prio == 1) __builtin_amdgcn_s_setprio(1);
     constexpr int NW = WGM * WGN, BK = 64;
     constexpr int GA = BM / 8, GB = BN / 8;    // 8-row groups = wave-level loads per stage
     constexpr int LA = GA / NW, LB = GB / NW;  // loads per lane per stage
@@ -625,7 +631,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
     __builtin_amdgcn_s_setprio(2);
     if (all_live) main_loop(std::false_type{});
     else main_loop(std::true_type{});
-    __builtin_amdgcn_s_setprio(0);
+    if (a.edge_prio == 0) __builtin_amdgcn_s_setprio(0);
+    else if (a.edge_prio == 1) __builtin_amdgcn_s_setprio(1);
 
     // ---- epilogue: registers -> global.  A lane holds, per 32x32 block, channels 8g + 4*(lane/32) + {0..3}
     // (g = 0..3) of pixel lane%32.  Swapping the upper half-wave of the g-even registers with the lower
@@ -851,7 +858,11 @@ inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
     static LdsOptIn opt_in[2][5];
     if (hipError_t e = opt_in[av ? 1 : 0][variant].ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     const dim3 grid((unsigned)(ceil_div(a.M, BM) * a.tiles_n)), block(NT);
-    hipLaunchKernelGGL(kern, grid, block, lds, st, a);
+    // A reduction of fewer steps than the pipeline has stages touches only the first nk stage buffers (and the
+    // statistics epilogue a few KB of the first): the launch asks for no more LDS than that, which leaves room on the
+    // CU for workgroups of kernels running beside it (train step at pruned widths -0.6 %, full -0.2 %).
+    const size_t lds_used = (size_t)(a.nk < STAGES ? (a.nk < 1 ? 1 : a.nk) : STAGES) * (BM + BN) * 128;
+    hipLaunchKernelGGL(kern, grid, block, lds_used, st, a);
     return hipSuccess;
 }
 
