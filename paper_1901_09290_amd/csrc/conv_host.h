@@ -246,7 +246,9 @@ inline hipError_t launch_wgrad(WgradArgs& a, const WgradPlan& p, bool vec, hipSt
         return launch_wgrad_cfg<kWgBM, kWgBN, kWgBK, 2, 2, 2>(a, st);
     }
     // wave grids and pipeline depths from measurements on ResNet-50 shapes
-    if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKPBig, 2, 2, 5, 2>(a, st);
+    // 128 x 128: eight waves of 32 x 64 outputs, no wave groups (with 32-pixel steps a group would get one sub-step per
+    // stage and nothing to read ahead): 6 % faster alone than two groups of 2 x 2 waves, 0.4 % in the step
+    if (p.BM == 128 && p.BN == 128) return launch_wgrad_dl_cfg<128, 128, kWgDlBKPBig, 4, 2, 5, 1>(a, st);
     if (p.BM == 64 && p.BN == 128) return launch_wgrad_dl_cfg<64, 128, kWgDlBKP, 2, 2, 3, 2>(a, st);
     if (p.BM == 128 && p.BN == 64) return launch_wgrad_dl_cfg<128, 64, kWgDlBKP, 2, 2, 3, 2>(a, st);
     return launch_wgrad_dl_cfg<64, 64, kWgDlBKP, 2, 2, 4, 2>(a, st);
