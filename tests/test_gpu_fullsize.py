@@ -159,8 +159,10 @@ def test_cfg4_pruned_shapes_batch2_whole_tensors():
         _check_layer_whole(_at_batch(spec, 2), seed=3500 + i)
 
 
-def test_cfg2_resnet32_train_step_on_side_streams_against_oracle():
-    """Network.train_step as the benchmark runs it (norms split over two streams, k-innermost filter copies, weight
+@pytest.mark.parametrize("norms_head", [11, None], ids=["norms_split_over_two_streams", "norms_before_forward"])
+def test_cfg2_resnet32_train_step_on_side_streams_against_oracle(norms_head, monkeypatch):
+    """Network.train_step as the benchmark runs it (norms split over two streams or all ahead of the forward pass,
+    k-innermost filter copies, weight
     gradients with the regulariser folded in on four side streams, zero padding vouched for) on the whole ResNet-32
     stack at batch 128: every layer's norms, y, dx and dw against the oracle.  Then the weights change (one optimizer
     step) and a second step must see the new weights everywhere, the k-innermost copies of the first layers too."""
@@ -169,8 +171,10 @@ def test_cfg2_resnet32_train_step_on_side_streams_against_oracle():
     specs, _ = wl.resnet32_layers(N=128)
     rng = np.random.Generator(np.random.PCG64(1))
     host = [wl.conv_tensors(s, rng) for s in specs]
+    if norms_head is not None:
+        monkeypatch.setattr(hz, "NORMS_HEAD_LAYERS", norms_head)
     net = hz.Network([hz.ConvLayer(s, host=t) for s, t in zip(specs, host)])
-    assert net.overlap_wgrad and net.fuse_lasso and net.norm_jobs_tail is not None
+    assert net.overlap_wgrad and net.fuse_lasso and (net.norm_jobs_tail is not None) == (norms_head is not None)
     lam = 50.0
 
     def check(weights):
