@@ -257,10 +257,13 @@ def main():
         g1 = graphed(lambda: (full.train_step(LAMBDA), rmodel.detect(THRESHOLD)))
         g2 = graphed(lambda: (rmodel.compact(counts0), pruned.train_step(LAMBDA)))
 
+        counts_host = torch.empty(rmodel.counts.numel(), dtype=rmodel.counts.dtype, pin_memory=True)
+
         def step():
             g1()
-            cnt = rmodel.counts.cpu().numpy()          # the sweep's one synchronising read-back
-            if not np.array_equal(cnt, counts0):
+            counts_host.copy_(rmodel.counts, non_blocking=True)   # the sweep's one synchronising read-back
+            torch.cuda.current_stream().synchronize()
+            if not np.array_equal(counts_host.numpy(), counts0):
                 raise RuntimeError("survivor counts changed between steps")
             g2()
     else:

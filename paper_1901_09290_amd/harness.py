@@ -448,12 +448,14 @@ class ReconfigModel:
             # the weight-shaped tensors and the per-channel vectors are a few launch-bound kernels over 64 MB; they run
             # on a side stream beside the activation gather, which keeps the memory system busy for 0.3 ms by itself
             main = torch.cuda.current_stream()
-            self.side.wait_stream(main)
+            before = torch.cuda.Event()
+            before.record(main)                    # everything the compaction depends on
+            if ajobs:
+                B.compact_nhwc_batched(ajobs)      # the long kernel first: it is the caller's stream that must not wait
+            self.side.wait_event(before)
             with torch.cuda.stream(self.side):
                 B.compact_weights_batched(wjobs)
                 B.compact_vector_batched(vjobs)
-            if ajobs:
-                B.compact_nhwc_batched(ajobs)
             main.wait_stream(self.side)
 
     def sweep(self, thr: float) -> None:
