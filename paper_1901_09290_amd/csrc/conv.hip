@@ -259,6 +259,13 @@ extern "C" int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const u
     int32_t rc = check_desc(d);
     if (rc != PT_OK) return rc;
     if (!x || !w || !y) return PT_ERR_NULL;
+    // image-like first layer (at most 4 channels at a pitch of 8, zero padding vouched for): its own kernel
+    if (d->C <= 4 && d->x_cpitch == 8 && d->w_cpitch == 8 && (d->flags & PT_CONV_PAD_ZERO) && d->y_cpitch % 8 == 0 &&
+        aligned16(x) && aligned16(w) && aligned16(y) && d->stride_h == d->stride_w && d->stride_h <= 2 && d->R <= kStemMaxR &&
+        d->S <= 8 && (int64_t)d->H * d->W * 16 <= 0x7fffffff) {
+        StemArgs s{x, w, y, d->N, d->H, d->W, d->P, d->Q, d->K, d->R, d->S, d->pad_h, d->pad_w, d->y_cpitch, 0, 0, 0, 0};
+        return hip_status(launch_stem_fwd(s, d->stride_h, kStemSlots, (hipStream_t)stream));
+    }
     IgemmArgs a = make_fwd_args(d, x, w, y);
     const bool vec = d->x_cpitch % 8 == 0 && d->w_cpitch % 8 == 0 && aligned16(x) && aligned16(w);
     return hip_status(launch_igemm(a, vec, (hipStream_t)stream));

@@ -12,6 +12,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // Raw 8 x bf16 load from base + off (elements).  VEC: one 16-byte load (off*2 is 16-byte aligned and all
 // 16 bytes are readable).  Otherwise eight 2-byte loads, where element e >= nvalid re-reads element 0 so
@@ -863,6 +864,237 @@ inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
     // CU for workgroups of kernels running beside it (train step at pruned widths -0.6 %, full -0.2 %).
     const size_t lds_used = (size_t)(a.nk < STAGES ? (a.nk < 1 ? 1 : a.nk) : STAGES) * (BM + BN) * 128;
     hipLaunchKernelGGL(kern, grid, block, lds_used, st, a);
+    return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------------- //
+// forward convolution of a network's first layer: image-like input, at most 4 channels at a pitch of 8
+// ------------------------------------------------------------------------------------------- //
+// The implicit-GEMM kernel treats such a layer as a GEMM over folded filter rows of S * 8 elements: 5 of every 8
+// multiplied elements are padding, and every output pixel pulls R runs of S pixels from L2 into LDS again.  Here a
+// workgroup walks over a run of tiles of 4 x 64 output pixels (x 64 output channels).  It keeps ALL its weights in
+// registers for the whole run (a filter row is 8 taps x 4 channels = two 16-element MFMA steps; taps past S and
+// channels past C are zero).  Per tile it loads the input patch under the tile ONCE, 8 bytes (4 channels) per pixel,
+// into LDS in image order: the two taps a lane multiplies in one step are neighbouring pixels, 16 contiguous bytes, and
+// consecutive output pixels read consecutive (stride 1) or every other (stride 2) such pair.  The patch of the next
+// tile is fetched into registers before the current tile is multiplied and written to the other of two LDS buffers
+// after it, so that its memory latency hides behind the MFMAs.  R * 2 MFMAs per 32 x 32 block: against the folded
+// form half the matrix work and an eighth of the operand traffic.  Both operands' padding channels must be zero (the
+// caller's PT_CONV_PAD_ZERO), the output takes 16-byte stores.
+struct StemArgs {
+    const uint16_t* X;   // [N][H][W][8]
+    const uint16_t* Wt;  // [K][R][S][8]
+    uint16_t* Y;         // [N][P][Q][ypitch]
+    int N, H, W, P, Q, K, R, S, pad_h, pad_w, ypitch;
+    int tiles_q, tiles_p;  // tiles per image along Q and P
+    int tiles, run;        // N * tiles_p * tiles_q, and how many consecutive tiles one workgroup takes
+};
+constexpr int kStemTH = 4, kStemTW = 64, kStemMaxR = 8;
+constexpr int kStemSlots = 512;  // 256 CUs x 2 resident workgroups
+
+// RT: rows of the filter the multiply loop runs over (R itself, or 8 for any R <= 8: rows past R multiply zeros);
+// NJ: 16-element steps per filter row (1 for S <= 4, else 2).
+template <int STRIDE, int RT, int NJ>
+__global__ __launch_bounds__(512, 4) void k_stem_fwd(const StemArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int PH = (kStemTH - 1) * STRIDE + RT;              // patch rows
+    constexpr int PW = (kStemTW - 1) * STRIDE + 4 * NJ;          // patch columns: 4 taps per step
+    constexpr int PWR = (PW + 1) & ~1;                           // row pitch in pixels: rows start on 16 bytes
+    constexpr int PSZ = PH * PWR;
+    __shared__ __attribute__((aligned(16))) uint2 patch[2][PSZ]; // [buffer][row][column], 4 channels each
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tiles_n = (a.K + 63) / 64;
+    const int nt = blockIdx.x % tiles_n, chunk = blockIdx.x / tiles_n;
+    const int n0 = nt * 64;
+    const int first = chunk * a.run, last = first + a.run < a.tiles ? first + a.run : a.tiles;
+    if (first >= last) return;  // whole workgroup
+    const int ph_used = (kStemTH - 1) * STRIDE + a.R;            // rows of the patch this filter reaches (<= PH)
+
+    // ---- weights -> registers: fragment (r, j) of this lane = taps 4j + 2h, 4j + 2h + 1 of filter row r, 4 channels each
+    const int wm = wave & 3, wn = wave >> 2;      // tile row of this wave, half of the 64 output channels
+    const int l32 = lane & 31, h = lane >> 5;
+    const int n = n0 + wn * 32 + l32;             // output channel of this lane's weight rows
+    const bool n_ok = n < a.K;
+    bf16x8 wf[RT][NJ];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            uint2 lo = make_uint2(0u, 0u), hi = make_uint2(0u, 0u);
+            const int s0 = 4 * j + 2 * h;
+            if (n_ok && r < a.R) {
+                const uint16_t* wr = a.Wt + ((int64_t)(n * a.R + r) * a.S) * 8;
+                if (s0 < a.S) lo = *reinterpret_cast<const uint2*>(wr + s0 * 8);
+                if (s0 + 1 < a.S) hi = *reinterpret_cast<const uint2*>(wr + (s0 + 1) * 8);
+            }
+            wf[r][j] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+        }
+
+    // ---- this thread's pixels of a patch: LDS slots tid + 512 * it, the same in every tile --------------------------
+    // (their rows and columns are worked out again at every use, from a copy of the thread index that the compiler
+    // cannot see through: kept across the tile loop they cost registers, which spill)
+    constexpr int NLD = (PSZ + 511) / 512;
+    uint2 pv[NLD];
+    // All loads of a patch are issued back to back, as buffer loads on a descriptor of the tile's image: a pixel
+    // outside the image, or in a row the filter does not reach, passes an offset past the descriptor's range and reads
+    // zeros (no branch, no cleared register, so nothing the loads would have to wait for).
+    constexpr uint32_t kBufOut = 0xffffffffu, kBufFlags = 0x00020000u;
+    const uint32_t img_bytes = (uint32_t)(a.H * a.W) * 16u;
+    auto fetch = [&](int tq, int tp, int img) {
+        const int ih0 = tp * kStemTH * STRIDE - a.pad_h, iw0 = tq * kStemTW * STRIDE - a.pad_w;
+        const __amdgpu_buffer_rsrc_t x_srd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(a.X) + (int64_t)img * a.H * a.W * 8, 0, img_bytes, kBufFlags);
+        int t0 = tid;
+        asm volatile("" : "+v"(t0));
+#pragma unroll
+        for (int it = 0; it < NLD; ++it) {
+            const int i = t0 + it * 512;
+            const int prow = i / PWR, pcol = i - prow * PWR;
+            const int ih = ih0 + prow, iw = iw0 + pcol;
+            const bool ok = prow < ph_used && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;  // (rows >= PH: too)
+            const auto got = __builtin_amdgcn_raw_buffer_load_b64(x_srd, ok ? (uint32_t)(ih * a.W + iw) * 16u : kBufOut, 0, 0);
+            pv[it] = make_uint2(got[0], got[1]);
+        }
+    };
+    auto park = [&](int buf) {
+        int t0 = tid;
+        asm volatile("" : "+v"(t0));
+#pragma unroll
+        for (int it = 0; it < NLD; ++it)
+            if ((it + 1) * 512 <= PSZ || t0 + it * 512 < PSZ) patch[buf][t0 + it * 512] = pv[it];
+    };
+    // tiles are numbered (image, tile row, tile column), column fastest: the next one by counting up
+    auto advance = [&](int& tq, int& tp, int& img) {
+        if (++tq == a.tiles_q) {
+            tq = 0;
+            if (++tp == a.tiles_p) {
+                tp = 0;
+                ++img;
+            }
+        }
+    };
+    int ntq = first % a.tiles_q, ntp = (first / a.tiles_q) % a.tiles_p, nimg = first / (a.tiles_q * a.tiles_p);
+
+    fetch(ntq, ntp, nimg);
+    park(0);
+    __syncthreads();
+    const bool wave_n_live = n0 + wn * 32 < a.K;  // uniform
+    // LDS element this lane's fragments start from: pixel l32 of the wave's tile row, tap 2h
+    const int frag0 = wm * STRIDE * PWR + l32 * STRIDE + 2 * h;
+    int buf = 0;
+    for (int tile = first; tile < last; ++tile, buf ^= 1) {
+        const bool more = tile + 1 < last;  // uniform
+        const int tq = ntq, tp = ntp, img = nimg;
+        advance(ntq, ntp, nimg);
+        if (more) fetch(ntq, ntp, nimg);
+        const int p = tp * kStemTH + wm, q0 = tq * kStemTW;
+        const bool live = wave_n_live && p < a.P;  // uniform
+        f32x16 acc[2];
+        if (live) {
+            // ---- multiply: this wave's 64 output pixels (tile row wm) x 32 output channels -------------------------
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[tm][v] = 0.f;
+            const uint2* pb = patch[buf] + frag0;
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int tm = 0; tm < 2; ++tm) {
+                        // taps 4j + 2h, 4j + 2h + 1 of filter row r under output pixel tm * 32 + l32: two neighbouring pixels
+                        const uint2* src = pb + r * PWR + tm * 32 * STRIDE + 4 * j;
+                        uint4 x4;
+                        if constexpr (STRIDE == 2) {
+                            x4 = *reinterpret_cast<const uint4*>(src);  // an even column: 16-byte aligned
+                        } else {
+                            const uint2 lo = src[0], hi = src[1];
+                            x4 = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                        }
+                        acc[tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[r][j], __builtin_bit_cast(bf16x8, x4), acc[tm], 0, 0, 0);
+                    }
+        }
+        // The next patch goes to the other buffer (last read before the barrier that ended the previous tile) BEFORE this
+        // tile's stores are issued: the wait for its loads then does not also wait for the stores behind them.
+        if (more) park(buf ^ 1);
+        if (live) {
+            // ---- store: the lane-pair exchange of k_igemm_dl (64 contiguous bytes of 16 pixels per store instruction) ----
+            // (a uniform base per tile and wave plus one 32-bit offset per lane; lane-derived values of this part are
+            // worked out afresh per tile, not kept in registers across the multiply)
+            const __amdgpu_buffer_rsrc_t y_srd = __builtin_amdgcn_make_buffer_rsrc(
+                a.Y + ((int64_t)(img * a.P + p) * a.Q + q0) * a.ypitch + n0 + wn * 32, 0, 0xffffff00u, kBufFlags);
+            int le = lane;
+            asm volatile("" : "+v"(le));
+            const int l32e = le & 31;
+            const bool odd = (le & 1) != 0;
+            const int chl = (odd ? 16 : 0) + 8 * (le >> 5);             // channel of this lane's chunk within the wave's 32
+            const int ch = n0 + wn * 32 + chl;
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm) {
+                const int q = q0 + tm * 32 + l32e;
+                const uint32_t off0 = (uint32_t)((tm * 32 + (l32e & ~1)) * a.ypitch + chl) * 2u;  // pixel (q & ~1); (q | 1) is next
+                const bool ok0 = (q & ~1) < a.Q, ok1 = (q | 1) < a.Q;
+                const f32x16& c = acc[tm];
+                uint32_t v[2][4];
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp) {
+                    const uint32_t x0 = cvt_pk_bf16(c[8 * gp + 0], c[8 * gp + 1]), y0 = cvt_pk_bf16(c[8 * gp + 2], c[8 * gp + 3]);
+                    const uint32_t x1 = cvt_pk_bf16(c[8 * gp + 4], c[8 * gp + 5]), y1 = cvt_pk_bf16(c[8 * gp + 6], c[8 * gp + 7]);
+                    const auto ps = __builtin_amdgcn_permlane32_swap(x0, x1, false, false);
+                    const auto qs = __builtin_amdgcn_permlane32_swap(y0, y1, false, false);
+                    v[gp][0] = ps[0]; v[gp][1] = qs[0]; v[gp][2] = ps[1]; v[gp][3] = qs[1];
+                }
+                uint32_t s0[4], s1[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t give = odd ? v[0][e] : v[1][e];
+                    const uint32_t got = (uint32_t)__shfl_xor((int)give, 1, 64);
+                    s0[e] = odd ? got : v[0][e];
+                    s1[e] = odd ? v[1][e] : got;
+                }
+                uint4 o0 = make_uint4(s0[0], s0[1], s0[2], s0[3]), o1 = make_uint4(s1[0], s1[1], s1[2], s1[3]);
+                if (ch < a.K && ch + 7 >= a.K) {  // last chunk: zeros in its padding
+                    const Mask8 k = make_mask8(a.K - ch);
+                    o0 = mask8(o0, true, k);
+                    o1 = mask8(o1, true, k);
+                }
+                // (a pixel past the row's end, a chunk past the channel count: an offset out of range, the store is dropped)
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o0), y_srd, ok0 && ch < a.K ? off0 : kBufOut, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o1), y_srd,
+                                                       ok1 && ch < a.K ? off0 + (uint32_t)a.ypitch * 2u : kBufOut, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+#endif
+}
+
+// One run of tiles per workgroup slot of the chip (2 workgroups per CU): the weights are fetched once per run.
+inline hipError_t launch_stem_fwd(StemArgs& a, int stride, int slots, hipStream_t st) {
+    a.tiles_q = (a.Q + kStemTW - 1) / kStemTW;
+    a.tiles_p = (a.P + kStemTH - 1) / kStemTH;
+    const int64_t tiles = (int64_t)a.N * a.tiles_p * a.tiles_q;
+    if (tiles <= 0) return hipSuccess;
+    if (tiles > 0x3fffffff) return hipErrorInvalidValue;
+    a.tiles = (int)tiles;
+    a.run = (int)((tiles + slots - 1) / slots);
+    const int64_t grid = ((tiles + a.run - 1) / a.run) * ((a.K + 63) / 64);
+    if (grid > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 g((unsigned)grid), b(512);
+    const int nj = a.S <= 4 ? 1 : 2;
+#define PT_STEM_CASE(ST, RT, NJ) hipLaunchKernelGGL((k_stem_fwd<ST, RT, NJ>), g, b, 0, st, a)
+    if (stride == 1) {
+        if (a.R == 3 && nj == 1) PT_STEM_CASE(1, 3, 1);
+        else if (a.R == 7 && nj == 2) PT_STEM_CASE(1, 7, 2);
+        else PT_STEM_CASE(1, 8, 2);
+    } else {
+        if (a.R == 3 && nj == 1) PT_STEM_CASE(2, 3, 1);
+        else if (a.R == 7 && nj == 2) PT_STEM_CASE(2, 7, 2);
+        else PT_STEM_CASE(2, 8, 2);
+    }
+#undef PT_STEM_CASE
     return hipSuccess;
 }
 

@@ -132,6 +132,28 @@ def test_many_whole_tiles(case, pad_zero):
     _check_full(spec, 600 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=pad_zero)
 
 
+FIRST_LAYER = [
+    # image-like inputs (at most 4 channels at a pitch of 8, zero padding vouched for): the first-layer forward kernel
+    (2, 33, 35, 1, 20, 3, 1, 1),      # one channel, 3 x 3 at stride 1 (one step per filter row)
+    (3, 40, 70, 2, 70, 5, 1, 2),      # two channels, 5 x 5, two output-channel tiles with a ragged second one
+    (2, 41, 150, 4, 64, 7, 1, 3),     # four channels, 7 x 7 at stride 1, rows of three tiles (the last partial)
+    (2, 37, 37, 3, 40, 3, 2, 1),      # 3 x 3 at stride 2
+    (2, 50, 50, 3, 100, 5, 2, 2),     # 5 x 5 at stride 2 (filter rows past the fifth multiply zeros)
+    (2, 24, 24, 4, 24, 8, 2, 3),      # the largest filter the kernel takes
+    (2, 10, 10, 4, 16, 1, 1, 0),      # a single tap
+    (3, 21, 21, 3, 12, 2, 2, 0),      # 2 x 2 at stride 2, no padding
+    (41, 200, 120, 3, 45, 7, 2, 3),   # 1025 tiles: runs of three tiles per workgroup, the last run of two
+    (11, 200, 200, 3, 64, 7, 2, 3),   # 550 tiles: runs of two, alternating between the columns of a tile row
+]
+
+
+@pytest.mark.parametrize("case", FIRST_LAYER, ids=lambda c: "x".join(map(str, c)))
+def test_image_like_first_layer(case):
+    from gpu_util import pitch8
+    spec = _spec(*case)
+    _check_full(spec, 800 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=True)
+
+
 @pytest.mark.parametrize("case", [(8, 256, 256, 8, 16, 1, 1, 0), (2, 515, 511, 5, 24, 3, 1, 1), (3, 420, 420, 16, 64, 1, 1, 0)],
                          ids=lambda c: "x".join(map(str, c)))
 def test_narrow_outputs_over_very_many_pixels(case):
