@@ -62,8 +62,11 @@ def short(name: str) -> str:
     return n.replace("pt::", "")
 
 
+MAIN_FAMILIES = ("k_igemm_dl", "k_wgrad_dl", "k_igemm", "k_wgrad", "k_stem_fwd")
+
+
 def family(n: str) -> Optional[str]:
-    for f in ("k_igemm_dl", "k_igemm", "k_wgrad_dl", "k_wgrad_reduce", "k_wgrad", "k_zero_class"):
+    for f in ("k_igemm_dl", "k_igemm", "k_stem_fwd", "k_wgrad_dl", "k_wgrad_reduce", "k_wgrad", "k_zero_class"):
         if n.startswith(f + "<") or n == f or n.startswith(f + "4"):
             return "k_wgrad_reduce" if f == "k_wgrad_reduce" else f
     return None
@@ -275,7 +278,7 @@ def cmd_traffic(a) -> None:
                  % (k[4] / k[0] / 1e6, (k[2] + k[3]) / k[4]))
     k = per_kind["igemm"]
     if k[0]:
-        o.append("per k_igemm_dl launch (conv_fwd and conv_bwd_data calls, %d launches, the zero fill of empty parity classes included): fetch %.1f MB + write %.1f MB = %.1f MB of HBM traffic"
+        o.append("per k_igemm_dl launch (conv_fwd and conv_bwd_data calls, %d launches, the first layer's k_stem_fwd and the zero fill of empty parity classes included): fetch %.1f MB + write %.1f MB = %.1f MB of HBM traffic"
                  % (k[1], k[2] / k[1] / 1e6, k[3] / k[1] / 1e6, (k[2] + k[3]) / k[1] / 1e6))
         o.append("algorithmic bytes per launch: %.1f MB  -> traffic / algorithmic = %.2f" % (k[4] / k[1] / 1e6, (k[2] + k[3]) / k[4]))
     _write(a.out, o)
@@ -290,9 +293,9 @@ def cmd_mfma(a) -> None:
     for c, ts, ps in zip(man["calls"], tsegs, psegs):
         if c["net"] not in ("full", "pruned") or len(ts) != len(ps):
             continue
-        main = [r for r in ts if family(r["name"]) in ("k_igemm_dl", "k_wgrad_dl", "k_igemm", "k_wgrad")]
+        main = [r for r in ts if family(r["name"]) in MAIN_FAMILIES]
         for t, p in zip(ts, ps):
-            if family(t["name"]) not in ("k_igemm_dl", "k_wgrad_dl", "k_igemm", "k_wgrad"):
+            if family(t["name"]) not in MAIN_FAMILIES:
                 continue
             g = agg[(c["net"], t["name"])]
             g["n"] += 1
