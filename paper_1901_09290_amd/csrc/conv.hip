@@ -214,6 +214,46 @@ __global__ __launch_bounds__(256) void k_wgrad_reduce4(const float* __restrict__
     }
 }
 
+// The same for the slabs of k_stem_wgrad, [slab][r][64 output channels][8 taps x 4 channels]: one output per lane, the
+// slabs spread over eight wavefronts (four loads in flight each) and the eight sums added in ascending order.
+template <bool LASSO>
+__global__ __launch_bounds__(64 * kReduceWaves) void k_stem_wgrad_reduce(const float* __restrict__ part, int slabs, int K,
+                                                                          int R, int S, int C, int wpitch,
+                                                                          float* __restrict__ dw, const ReduceLasso rl) {
+    __shared__ float red[kReduceWaves][64];
+    const int64_t total = (int64_t)R * kSwSlabRow;  // a multiple of 64
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x * 64 + lane;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int i = wave;
+    for (; i + 3 * kReduceWaves < slabs; i += 4 * kReduceWaves) {
+        s0 += part[(int64_t)i * total + t];
+        s1 += part[(int64_t)(i + kReduceWaves) * total + t];
+        s2 += part[(int64_t)(i + 2 * kReduceWaves) * total + t];
+        s3 += part[(int64_t)(i + 3 * kReduceWaves) * total + t];
+    }
+    for (; i < slabs; i += kReduceWaves) s0 += part[(int64_t)i * total + t];
+    red[wave][lane] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (wave == 0) {
+        float s = 0.f;
+#pragma unroll
+        for (int v = 0; v < kReduceWaves; ++v) s += red[v][lane];
+        const int n = t & 31, k = (t >> 5) & 63, r = t >> 11;
+        const int fs = n >> 2, c = n & 3;
+        if (k < K && fs < S && c < C) {
+            const int64_t o = ((int64_t)(k * R + r) * S + fs) * wpitch + c;
+            if constexpr (LASSO) {
+                const float on = (rl.flags & PT_LASSO_OUT) ? rl.out_norm[k] : 0.f;
+                const float in = (rl.flags & PT_LASSO_IN) ? rl.in_norm[c] : 0.f;
+                const float inv_out = on > 0.f ? 1.0f / on : 0.f, inv_in = in > 0.f ? 1.0f / in : 0.f;
+                s += rl.lambda * (rl.w[o] * (inv_out + inv_in));
+            }
+            dw[o] = s;
+        }
+    }
+}
+
 }  // namespace pt
 
 #include "conv_host.h"
@@ -425,6 +465,17 @@ extern "C" int32_t pt_conv_bwd_weight_plan(const pt_conv_desc* d, int32_t aligne
     const int32_t rc = check_desc(d);
     if (rc != PT_OK) return rc;
     const bool vec = aligned != 0 && d->x_cpitch % 8 == 0 && d->y_cpitch % 8 == 0;
+    if (vec && stem_wgrad_ok(d)) {  // the first layer's own kernel: one slab per workgroup, always reduced
+        StemWgradArgs s = make_stem_wgrad_args(d, nullptr, nullptr, nullptr);
+        int slabs = 0;
+        plan_stem_wgrad(s, &slabs);
+        info->splits = slabs;
+        info->tiles = 1;
+        info->reduce_kind = PT_WGRAD_REDUCE_DEEP;
+        info->tile_m = 32;
+        info->tile_n = 64;
+        return PT_OK;
+    }
     const WgradPlan p = plan_wgrad(d, vec);
     info->splits = p.splits;
     info->tiles = p.tiles_m * p.tiles_n;
@@ -444,12 +495,33 @@ static int32_t bwd_weight_impl(const pt_conv_desc* d, const uint16_t* x, const u
     if (!x || !dy || !dw) return PT_ERR_NULL;
     // the direct kernel needs 16-byte aligned rows; it keeps one tile row block per filter tap
     const bool vec = d->x_cpitch % 8 == 0 && d->y_cpitch % 8 == 0 && aligned16(x) && aligned16(dy);
+    hipStream_t st = (hipStream_t)stream;
+    if (vec && stem_wgrad_ok(d)) {  // image-like first layer: its own kernel, one slab of partial sums per workgroup
+        const size_t need = stem_wgrad_ws(d);
+        if (!ws) return PT_ERR_NULL;
+        if (ws_bytes < need) return PT_ERR_WORKSPACE;
+        if (!aligned16(ws)) return PT_ERR_SHAPE;
+        StemWgradArgs s = make_stem_wgrad_args(d, x, dy, (float*)ws);
+        int slabs = 0;
+        plan_stem_wgrad(s, &slabs);
+        if (slabs <= 0) return PT_OK;
+        rc = hip_status(launch_stem_wgrad(s, slabs, d->stride_h, st));
+        if (rc != PT_OK) return rc;
+        const ReduceLasso none{};
+        const unsigned nb = (unsigned)(d->R * (kSwSlabRow / 64));
+        if (rl)
+            hipLaunchKernelGGL(k_stem_wgrad_reduce<true>, dim3(nb), dim3(64 * kReduceWaves), 0, st, (const float*)ws, slabs, d->K,
+                               d->R, d->S, d->C, d->w_cpitch, dw, *rl);
+        else
+            hipLaunchKernelGGL(k_stem_wgrad_reduce<false>, dim3(nb), dim3(64 * kReduceWaves), 0, st, (const float*)ws, slabs, d->K,
+                               d->R, d->S, d->C, d->w_cpitch, dw, none);
+        return launch_status();
+    }
     const WgradPlan p = plan_wgrad(d, vec);
     const size_t need = rl ? wgrad_lasso_ws_of(d, p) : p.ws_bytes;
     if (need > 0 && !ws) return PT_ERR_NULL;
     if (ws_bytes < need) return PT_ERR_WORKSPACE;
     if (need > 0 && !aligned16(ws)) return PT_ERR_SHAPE;
-    hipStream_t st = (hipStream_t)stream;
     WgradArgs a = make_wgrad_args(d, p, x, dy, dw, ws);
     if (rl && a.direct && p.dl && aligned16(rl->w)) {  // the direct kernel's own epilogue adds the term (vector loads of w)
         a.lw = rl->w;
@@ -500,7 +572,8 @@ extern "C" int32_t pt_conv_bwd_weight_lasso_workspace_bytes(const pt_conv_desc* 
     int32_t rc = check_desc(d);
     if (rc != PT_OK) return rc;
     const size_t a = wgrad_lasso_ws_of(d, plan_wgrad(d, true)), b = wgrad_lasso_ws_of(d, plan_wgrad(d, false));
-    *bytes = a > b ? a : b;
+    const size_t c = stem_wgrad_ok(d) ? stem_wgrad_ws(d) : 0;
+    *bytes = a > b ? (a > c ? a : c) : (b > c ? b : c);
     return PT_OK;
 }
 

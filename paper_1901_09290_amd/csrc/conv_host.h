@@ -210,9 +210,35 @@ inline WgradPlan plan_wgrad(const pt_conv_desc* d, bool dl) {
     return p;
 }
 
+// The first layer's own weight-gradient kernel takes image-like inputs: at most 4 channels at a pitch of 8, at most 64
+// output channels, a filter of at most 8 x 8 at stride 1 or 2, and sizes whose byte offsets fit its 32-bit addressing.
+inline bool stem_wgrad_ok(const pt_conv_desc* d) {
+    return d->C <= 4 && d->x_cpitch == 8 && d->y_cpitch % 8 == 0 && d->K <= 64 && d->stride_h == d->stride_w &&
+           d->stride_h >= 1 && d->stride_h <= 2 && d->R <= kStemMaxR && d->S <= 8 &&
+           (int64_t)d->H * d->W * 16 <= 0x7fffffff && ((int64_t)2 * d->Q + 64) * d->y_cpitch * 2 <= 0x7fffffff &&
+           (int64_t)d->N * ((d->P + 1) / 2) * ((d->Q + 63) / 64) <= 0x3fffffff;
+}
+
+inline StemWgradArgs make_stem_wgrad_args(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, float* part) {
+    StemWgradArgs s{};
+    s.X = x; s.DY = dy; s.PART = part;
+    s.N = d->N; s.H = d->H; s.W = d->W; s.P = d->P; s.Q = d->Q; s.K = d->K; s.KP = (int)round_up(d->K, 8);
+    s.R = d->R; s.S = d->S; s.pad_h = d->pad_h; s.pad_w = d->pad_w; s.ypitch = d->y_cpitch;
+    return s;
+}
+
+// one slab of [R][64][32] floats per workgroup of the launch
+inline size_t stem_wgrad_ws(const pt_conv_desc* d) {
+    StemWgradArgs s = make_stem_wgrad_args(d, nullptr, nullptr, nullptr);
+    int slabs = 0;
+    plan_stem_wgrad(s, &slabs);
+    return (size_t)round_up((int64_t)(slabs > 0 ? slabs : 1) * d->R * kSwSlabRow * 4, 256);
+}
+
 inline size_t wgrad_ws(const pt_conv_desc* d) {
     const size_t a = plan_wgrad(d, true).ws_bytes, b = plan_wgrad(d, false).ws_bytes;
-    return a > b ? a : b;
+    const size_t c = stem_wgrad_ok(d) ? stem_wgrad_ws(d) : 0;
+    return a > b ? (a > c ? a : c) : (b > c ? b : c);
 }
 
 // Workspace of the weight gradient with the regulariser folded into its reduction pass: at least one slab of partials

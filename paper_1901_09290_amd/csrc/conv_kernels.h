@@ -1757,5 +1757,228 @@ inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
     return launch_wgrad_dl_mode<BM, BN, BKP, WGM, WGN, STAGES, KSPLIT, MINB, 0>(a, st);
 }
 
-}  // namespace pt
+// ------------------------------------------------------------------------------------------- //
+// weight gradient of a network's first layer: image-like input, at most 4 channels at a pitch of 8
+// ------------------------------------------------------------------------------------------- //
+// dw[k][r][s][c] = sum over output pixels of dy[pixel][k] * x[pixel * stride + (r, s)][c] (Eq. 4).  As in k_stem_fwd
+// the unit of work is a tile of output pixels (2 x 64) whose input patch is loaded once; here the dy tile comes along
+// and both go to LDS by 16-byte global->LDS loads: dy rows of 64 channels = 128 bytes with the unit swizzle of
+// k_wgrad_dl's 128-byte rows, the patch in image order at 16 bytes per pixel (the 4 padding channels ride along).
+// The reduction runs over the tile's pixels, 16 per MFMA step: wave r of a group of eight owns filter row r and
+// accumulates 64 output channels (two 32 x 32 blocks) x 32 columns = 8 taps x 4 channels.  Both fragments are
+// transposing reads: of dy as in k_wgrad_dl; of the patch, a source lane points at the 4 channels of pixel
+// (q + row) * stride + tap, so the 16 columns of a read are 4 taps x 4 channels and its rows 4 consecutive output
+// pixels.  A workgroup has two such groups of eight waves working on alternate tiles of one run of tiles, each with
+// its own double-buffered LDS region; at the end the second group's sums are added to the first's through LDS and ONE
+// slab of fp32 partial sums per workgroup, [r][64][32], goes to the workspace.  One workgroup per CU: the slabs of a
+// launch are 256 x 57 KB, summed in a fixed order by k_stem_wgrad_reduce (which also adds the regulariser's term).
+struct StemWgradArgs {
+    const uint16_t* X;   // [N][H][W][8]
+    const uint16_t* DY;  // [N][P][Q][ypitch]
+    float* PART;         // [workgroup][R][64][32]
+    int N, H, W, P, Q, K, KP, R, S, pad_h, pad_w, ypitch;
+    int tiles_q, tiles_p;  // tiles per image along Q and P
+    int tiles, run;        // N * tiles_p * tiles_q, and how many consecutive tiles one workgroup takes
+};
+constexpr int kSwTH = 2, kSwTW = 64;
+constexpr int kSwSlots = 256;                 // one workgroup of 16 waves per CU
+constexpr int kSwSlabRow = 64 * 32;           // floats per filter row in a slab
 
+template <int STRIDE>
+__global__ __launch_bounds__(1024) void k_stem_wgrad(const StemWgradArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int PH = (kSwTH - 1) * STRIDE + kStemMaxR;   // patch rows (for the largest filter)
+    constexpr int PW = (kSwTW - 1) * STRIDE + 8;           // patch columns: 8 taps per filter row
+    constexpr int NXL = (PH * PW + 63) / 64;               // wave-level loads of a patch, 64 pixels each
+    constexpr int XL = (NXL + 7) / 8;                      // per wave
+    constexpr int YL = kSwTH * kSwTW / 8 / 8;              // dy: 8 pixels per wave-level load, 8 waves
+    constexpr int YB = kSwTH * kSwTW * 128, XB = NXL * 1024, STAGE = YB + XB, GROUP = 2 * STAGE;
+    constexpr uint32_t kBufOut = 0xffffffffu, kBufFlags = 0x00020000u;
+    static_assert(YL == 2 && 2 * GROUP <= 160 * 1024, "tile config");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_b[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hh = wave >> 3, w8 = wave & 7;     // group of eight waves, wave inside it = filter row
+    const int first = blockIdx.x * a.run, last = first + a.run < a.tiles ? first + a.run : a.tiles;
+    const int niter = (a.run + 1) >> 1;          // the same for every workgroup: tiles past `last` are fetched as zeros
+    const bool active = w8 < a.R;
+    const int ph_used = (kSwTH - 1) * STRIDE + a.R;
+    uint8_t* gbase = smem_b + hh * GROUP;
+
+    // ---- loader state ---------------------------------------------------------------------------------------------
+    // dy: wave-level load d = w8 + 8 i covers pixels 8 d .. 8 d + 7 of the tile (i = tile row), a lane one 16-byte chunk;
+    // the chunk a lane fetches is the logical one that belongs at its physical place in the swizzled row
+    const int yq = 8 * w8 + (lane >> 3);         // output column inside the tile
+    uint32_t y_v[YL];
+    {
+        const int pc = lane & 7, sw = (yq >> 1) & 1;         // (the pixel row's swizzle bit: rows i * 64 + yq)
+        const int qq = (pc >> 1) ^ sw;
+        const int lc = ((((qq & 1) << 1) | (qq >> 1)) << 1) | (pc & 1);
+#pragma unroll
+        for (int i = 0; i < YL; ++i) y_v[i] = lc * 8 < a.KP ? (uint32_t)(((i * a.Q + yq) * a.ypitch + lc * 8) * 2) : kBufOut;
+    }
+    // patch: wave-level load idx covers pixels 64 idx .. 64 idx + 63 of the patch in row-major order; loads past the
+    // last one repeat it (same data to the same place), so that every wave issues the same number
+    int x_rc[XL];          // row << 16 | column, or -1
+    uint32_t x_rel[XL];    // byte offset of the pixel from the patch's first pixel
+    int x_idx[XL];
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+        x_idx[i] = w8 + 8 * i < NXL ? w8 + 8 * i : NXL - 1;
+        const int slot = x_idx[i] * 64 + lane;
+        const int prow = slot / PW, pcol = slot - prow * PW;
+        x_rc[i] = prow < ph_used && prow < PH ? (prow << 16) | pcol : -1;
+        x_rel[i] = (uint32_t)(prow * a.W + pcol) * 16u;
+    }
+    const uint32_t img_bytes = (uint32_t)(a.H * a.W) * 16u;
+
+    auto issue = [&](int tile, int stage) {
+        const bool tv = tile < last;  // uniform
+        const int tq = tile % a.tiles_q;
+        const int tp = (tile / a.tiles_q) % a.tiles_p;
+        const int img = tile / (a.tiles_q * a.tiles_p);
+        const int p0 = tp * kSwTH, q0 = tq * kSwTW;
+        uint8_t* sbase = gbase + stage * STAGE;
+        const __amdgpu_buffer_rsrc_t y_srd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(a.DY) + ((int64_t)(img * a.P + p0) * a.Q + q0) * a.ypitch, 0, 0xffffff00u, kBufFlags);
+        const bool q_ok = tv && q0 + yq < a.Q;
+#pragma unroll
+        for (int i = 0; i < YL; ++i) {
+            const uint32_t v = q_ok && p0 + i < a.P ? y_v[i] : kBufOut;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(y_srd, (lds_void_ptr)(sbase + (w8 + 8 * i) * 1024), 16, v, 0, 0, 0);
+        }
+        const __amdgpu_buffer_rsrc_t x_srd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(a.X) + (int64_t)img * a.H * a.W * 8, 0, img_bytes, kBufFlags);
+        const int ih0 = p0 * STRIDE - a.pad_h, iw0 = q0 * STRIDE - a.pad_w;
+        const uint32_t xs = (uint32_t)((ih0 * a.W + iw0) * 16);
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int ih = ih0 + (x_rc[i] >> 16), iw = iw0 + (x_rc[i] & 0xffff);
+            const bool ok = tv && x_rc[i] >= 0 && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_srd, (lds_void_ptr)(sbase + YB + x_idx[i] * 1024), 16,
+                                                     ok ? x_rel[i] + xs : kBufOut, 0, 0, 0);
+        }
+    };
+
+    // ---- MFMA state -----------------------------------------------------------------------------------------------
+    // transpose-read geometry: 16-lane group g16, lane t16; source lane t16 points at pixel row (t16 >> 2) and 8-byte
+    // quad (t16 & 3); the result is 4 consecutive pixels for column 16 * (g16 & 1) + t16
+    const int g16 = lane >> 4, t16 = lane & 15;
+    const int tr_row = (g16 >> 1) * 8 + (t16 >> 2);   // + 4 h + 16 (step inside the tile row)
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_ptr)gbase;
+    uint32_t ay[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        const int u = 2 * kb + (g16 & 1);              // 32-byte unit (16 channels) of the 128-byte row
+        const int up = (((u & 1) << 1) | (u >> 1)) ^ ((tr_row >> 1) & 1);
+        ay[kb] = lds0 + (uint32_t)(tr_row * 128 + (up << 5) + (t16 & 3) * 8);
+    }
+    // patch: filter row w8, pixel (tile column tr_row) * STRIDE + tap, tap = 4 (g16 & 1) + (t16 & 3)
+    const uint32_t ax = lds0 + (uint32_t)(YB + (w8 * PW + tr_row * STRIDE + 4 * (g16 & 1) + (t16 & 3)) * 16);
+    f32x16 acc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[kb][v] = 0.f;
+
+    // One tile: 8 steps of 16 pixels (tile row pl = step / 4); the reads of step st + 1 are in flight during the MFMAs of st.
+    auto compute = [&](int stage) {
+        const uint32_t sb = (uint32_t)(stage * STAGE);
+        const uint32_t by0 = ay[0] + sb, by1 = ay[1] + sb, bx = ax + sb;
+        s16x4 fy[2][2][2], fx[2][2];
+        auto issue_reads = [&](auto st_c) {
+            constexpr int ST = decltype(st_c)::value, PL = ST >> 2, KQ = ST & 3, B = ST & 1;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (h == 0) {
+                    fy[B][0][0] = lds_read_tr16_b64<(PL * 64 + 16 * KQ) * 128>(by0);
+                    fy[B][1][0] = lds_read_tr16_b64<(PL * 64 + 16 * KQ) * 128>(by1);
+                    fx[B][0] = lds_read_tr16_b64<(PL * STRIDE * PW + 16 * KQ * STRIDE) * 16>(bx);
+                } else {
+                    fy[B][0][1] = lds_read_tr16_b64<(PL * 64 + 16 * KQ + 4) * 128>(by0);
+                    fy[B][1][1] = lds_read_tr16_b64<(PL * 64 + 16 * KQ + 4) * 128>(by1);
+                    fx[B][1] = lds_read_tr16_b64<(PL * STRIDE * PW + (16 * KQ + 4) * STRIDE) * 16>(bx);
+                }
+            }
+        };
+        issue_reads(std::integral_constant<int, 0>{});
+        static_for<0, 8>([&](auto st_c) {
+            constexpr int ST = decltype(st_c)::value, B = ST & 1;
+            if constexpr (ST + 1 < 8) {
+                issue_reads(std::integral_constant<int, ST + 1>{});
+                lds_wait<6>(fy[B][0][0]);
+            } else {
+                lds_wait<0>(fy[B][0][0]);
+            }
+            lds_tie(fy[B][0][1]); lds_tie(fy[B][1][0]); lds_tie(fy[B][1][1]); lds_tie(fx[B][0]); lds_tie(fx[B][1]);
+            const bf16x8 vx = join_halves(fx[B][0], fx[B][1]);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+                acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(join_halves(fy[B][kb][0], fy[B][kb][1]), vx, acc[kb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
+    // ---- tiles first + hh, first + hh + 2, ...: loads one tile ahead, one barrier per tile ------------------------------
+    issue(first + hh, 0);
+    for (int it = 0; it < niter; ++it) {
+        wait_vmcnt<0>();      // this wave's loads of tile `it` have landed ...
+        barrier_nofence();    // ... and everybody's; everybody is also done reading the other stage
+        if (it + 1 < niter) issue(first + hh + 2 * (it + 1), (it + 1) & 1);
+        if (active) compute(it & 1);
+    }
+
+    // ---- the second group's sums join the first's through LDS; one slab per workgroup ---------------------------------
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem_b);
+    if (hh == 1 && active) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[((w8 * 2 + kb) * 16 + v) * 64 + lane] = acc[kb][v];
+    }
+    __syncthreads();
+    if (hh == 0 && active) {
+        const int l32 = lane & 31, h = lane >> 5;
+        float* slab = a.PART + ((int64_t)blockIdx.x * a.R + w8) * kSwSlabRow;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = kb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                slab[k * 32 + l32] = acc[kb][v] + red[((w8 * 2 + kb) * 16 + v) * 64 + lane];
+            }
+    }
+#endif
+}
+
+inline size_t stem_wgrad_lds(int stride) {
+    const int ph = (kSwTH - 1) * stride + kStemMaxR, pw = (kSwTW - 1) * stride + 8;
+    return (size_t)4 * (kSwTH * kSwTW * 128 + (ph * pw + 63) / 64 * 1024);
+}
+
+// Fills in the tiling; `slabs` = workgroups of the launch = slabs of partial sums written.
+inline void plan_stem_wgrad(StemWgradArgs& a, int* slabs) {
+    a.tiles_q = (a.Q + kSwTW - 1) / kSwTW;
+    a.tiles_p = (a.P + kSwTH - 1) / kSwTH;
+    const int64_t tiles = (int64_t)a.N * a.tiles_p * a.tiles_q;
+    a.tiles = (int)tiles;
+    a.run = (int)((tiles + kSwSlots - 1) / kSwSlots);
+    if (a.run < 1) a.run = 1;
+    *slabs = (int)((tiles + a.run - 1) / a.run);
+}
+
+inline hipError_t launch_stem_wgrad(const StemWgradArgs& a, int slabs, int stride, hipStream_t st) {
+    const size_t lds = stem_wgrad_lds(stride);
+    static LdsOptIn opt_in[2];
+    if (stride == 1) {
+        if (hipError_t e = opt_in[0].ensure(reinterpret_cast<const void*>(k_stem_wgrad<1>), lds); e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_stem_wgrad<1>, dim3((unsigned)slabs), dim3(1024), lds, st, a);
+    } else {
+        if (hipError_t e = opt_in[1].ensure(reinterpret_cast<const void*>(k_stem_wgrad<2>), lds); e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_stem_wgrad<2>, dim3((unsigned)slabs), dim3(1024), lds, st, a);
+    }
+    return hipSuccess;
+}
+
+}  // namespace pt
