@@ -170,6 +170,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep the weight gradients on the same stream as the input-gradient chain")
+    ap.add_argument("--no-branch-overlap", action="store_true",
+                    help="input gradients of the shortcut convolutions in line instead of on a side stream")
     ap.add_argument("--no-fused-lasso", action="store_true",
                     help="add the regulariser's gradient in a pass of its own after the weight gradients")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -220,6 +222,7 @@ def main():
     pruned = hz.Network(hz.build_network(pruned_specs, seed=3))
     full.overlap_wgrad = pruned.overlap_wgrad = not args.no_overlap
     full.fuse_lasso = pruned.fuse_lasso = not args.no_fused_lasso
+    full.overlap_branches = pruned.overlap_branches = not args.no_branch_overlap
     rng = np.random.Generator(np.random.PCG64(10 + int(round(args.sparsity * 10))))
     zero_sets = wl.zeroed_channel_sets(pruned_edges, args.sparsity, rng)
     rweights = wl.network_weights(pruned_specs, pruned_edges, zero_sets, rng)
@@ -445,6 +448,7 @@ def main():
                                "train step at ragged pruned widths (cfg4)",
                    "lambda": LAMBDA, "threshold": THRESHOLD, "hip_graphs": use_graph,
                    "wgrad_side_streams": 0 if args.no_overlap else hz.WGRAD_STREAMS,
+                   "shortcut_input_gradients_on_side_streams": bool(full.overlap_branches and full.overlap_wgrad),
                    "lasso_in_wgrad_reduce": bool(full.fuse_lasso and full.overlap_wgrad),
                    "kernel_sources": pr.source_digest()},
         "roofline": roofline,

@@ -159,10 +159,11 @@ def test_cfg4_pruned_shapes_batch2_whole_tensors():
         _check_layer_whole(_at_batch(spec, 2), seed=3500 + i)
 
 
-@pytest.mark.parametrize("norms_head", [11, None], ids=["norms_split_over_two_streams", "norms_before_forward"])
-def test_cfg2_resnet32_train_step_on_side_streams_against_oracle(norms_head, monkeypatch):
+@pytest.mark.parametrize("norms_head,branches", [(11, True), (None, True), (None, False)],
+                         ids=["norms_split_over_two_streams", "norms_before_forward", "shortcuts_on_the_main_stream"])
+def test_cfg2_resnet32_train_step_on_side_streams_against_oracle(norms_head, branches, monkeypatch):
     """Network.train_step as the benchmark runs it (norms split over two streams or all ahead of the forward pass,
-    k-innermost filter copies, weight
+    k-innermost filter copies, the input gradients of the blocks' shortcut convolutions on a side stream or in line, weight
     gradients with the regulariser folded in on four side streams, zero padding vouched for) on the whole ResNet-32
     stack at batch 128: every layer's norms, y, dx and dw against the oracle.  Then the weights change (one optimizer
     step) and a second step must see the new weights everywhere, the k-innermost copies of the first layers too."""
@@ -175,6 +176,11 @@ def test_cfg2_resnet32_train_step_on_side_streams_against_oracle(norms_head, mon
         monkeypatch.setattr(hz, "NORMS_HEAD_LAYERS", norms_head)
     net = hz.Network([hz.ConvLayer(s, host=t) for s, t in zip(specs, host)])
     assert net.overlap_wgrad and net.fuse_lasso and (net.norm_jobs_tail is not None) == (norms_head is not None)
+    # the two stride-2 stages have a shortcut convolution each, forking where their first block starts
+    names = [s.name for s in specs]
+    assert net.overlap_branches and {names[j]: names[i] for j, i in net.fork.items()} == {
+        "stage2_b0_a": "stage2_proj", "stage3_b0_a": "stage3_proj"}
+    net.overlap_branches = branches
     lam = 50.0
 
     def check(weights):
