@@ -62,13 +62,14 @@ def short(name: str) -> str:
     return n.replace("pt::", "")
 
 
-MAIN_FAMILIES = ("k_igemm_dl", "k_wgrad_dl", "k_igemm", "k_wgrad", "k_stem_fwd")
+MAIN_FAMILIES = ("k_igemm_dl", "k_wgrad_dl", "k_igemm", "k_wgrad", "k_stem_fwd", "k_stem_wgrad")
 
 
 def family(n: str) -> Optional[str]:
-    for f in ("k_igemm_dl", "k_igemm", "k_stem_fwd", "k_wgrad_dl", "k_wgrad_reduce", "k_wgrad", "k_zero_class"):
+    for f in ("k_igemm_dl", "k_igemm", "k_stem_fwd", "k_stem_wgrad_reduce", "k_stem_wgrad", "k_wgrad_dl", "k_wgrad_reduce", "k_wgrad",
+              "k_zero_class"):
         if n.startswith(f + "<") or n == f or n.startswith(f + "4"):
-            return "k_wgrad_reduce" if f == "k_wgrad_reduce" else f
+            return "k_wgrad_reduce" if f in ("k_wgrad_reduce", "k_stem_wgrad_reduce") else f
     return None
 
 
