@@ -87,7 +87,10 @@ int32_t pt_conv_bwd_data_workspace_bytes(const pt_conv_desc* d, size_t* bytes);
 int32_t pt_conv_bwd_weight_workspace_bytes(const pt_conv_desc* d, size_t* bytes);
 
 /* y[n,p,q,k] = sum_{r,s,c} x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c] * w[k,r,s,c].
- * x, w bf16; y bf16 (fp32 accumulator rounded once). ws: device scratch of ws_bytes (256-byte aligned). */
+ * x, w bf16; y bf16 (fp32 accumulator rounded once). ws: device scratch of ws_bytes (256-byte aligned).
+ * An image-like first layer under PT_CONV_PAD_ZERO (C <= 4 at x_cpitch = w_cpitch = 8, y_cpitch a multiple of 8,
+ * filter <= 8 x 8, stride 1 or 2, 16-byte aligned tensors) takes a kernel of its own; same results to the same
+ * tolerance. */
 int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, uint16_t* y, void* ws,
                     size_t ws_bytes, void* stream);
 
@@ -115,13 +118,17 @@ int32_t pt_conv_bwd_data_crsk(const pt_conv_desc* d, const uint16_t* dy, const u
 
 /* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c]  (Eq. 4;
  * plain sum over the mini-batch).  x, dy bf16; dw fp32 [K][R][S][w_cpitch].  The reduction is split
- * over workgroups into ws and combined in a fixed order: results are run-to-run identical. */
+ * over workgroups into ws and combined in a fixed order: results are run-to-run identical.  An image-like first
+ * layer (C <= 4 at x_cpitch 8, K <= 64, filter <= 8 x 8, stride 1 or 2, 16-byte aligned x and dy) takes a kernel of
+ * its own, which always writes one slab of partial sums per workgroup: ws must not be NULL there (the workspace query
+ * says how much). */
 int32_t pt_conv_bwd_weight(const pt_conv_desc* d, const uint16_t* x, const uint16_t* dy, float* dw, void* ws,
                            size_t ws_bytes, void* stream);
 
 /* Host-only: how pt_conv_bwd_weight[_lasso] would run this descriptor on 16-byte aligned tensors (aligned != 0) or
  * on unaligned ones: the number of workgroup slices of the pixel reduction (1 = the main kernel writes dw itself),
- * output tiles per slice, and which pass combines the slices (PT_WGRAD_REDUCE_*).  For tests and tuning: lets a
+ * output tiles per slice, and which pass combines the slices (PT_WGRAD_REDUCE_*).  The first layer's own kernel
+ * reports its workgroups as slices of one tile, always combined by the deep pass.  For tests and tuning: lets a
  * caller assert that a problem size reaches the code path it is meant to cover. */
 #define PT_WGRAD_REDUCE_NONE 0 /* unsplit: no second pass (with the regulariser: added in the main kernel's epilogue, or
                                   by a pass over one slab when the main kernel cannot) */

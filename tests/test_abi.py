@@ -82,6 +82,26 @@ def test_workspace_queries_validate_descriptor(lib):
     assert lib.pt_conv_fwd_workspace_bytes(C.byref(huge), C.byref(n)) == -4
 
 
+def test_first_layer_weight_gradient_plan_and_workspace(lib):
+    """An image-like first layer (at most 4 channels at a pitch of 8, at most 64 filters of at most 8 x 8, stride 1 or 2)
+    takes its own weight-gradient kernel: one slab of [R][64][32] fp32 partial sums per workgroup, at most one
+    workgroup per CU, always reduced.  Anything outside those limits keeps the general plan."""
+    d = B.conv_desc(64, 224, 224, 3, 64, 7, 7, 2, 3, x_cpitch=8, y_cpitch=64, w_cpitch=8)
+    info = B.conv_bwd_weight_plan(d, True)
+    tiles = 64 * (112 // 2) * 2                      # tiles of 2 x 64 output pixels
+    assert tiles == 7168 and info.splits == 256 and info.tiles == 1 and info.reduce_kind == B.WGRAD_REDUCE_DEEP
+    assert B.conv_bwd_weight_workspace_bytes(d) >= 256 * 7 * 64 * 32 * 4
+    assert B.conv_bwd_weight_lasso_workspace_bytes(d) >= 256 * 7 * 64 * 32 * 4
+    small = B.conv_desc(2, 18, 18, 3, 16, 7, 7, 2, 3, x_cpitch=8, y_cpitch=16, w_cpitch=8)
+    info = B.conv_bwd_weight_plan(small, True)
+    assert info.splits == 2 * 5 * 1 and info.tiles == 1      # 9 x 9 outputs: five tile rows, one tile column
+    # unaligned operands, a dense 3-channel pitch, or more than 64 filters: the general kernels
+    assert B.conv_bwd_weight_plan(d, False).tiles > 1
+    assert B.conv_bwd_weight_plan(B.conv_desc(64, 224, 224, 3, 64, 7, 7, 2, 3), True).tiles > 1
+    wide = B.conv_desc(8, 64, 64, 3, 96, 3, 3, 1, 1, x_cpitch=8, y_cpitch=96, w_cpitch=8)
+    assert B.conv_bwd_weight_plan(wide, True).tiles > 1
+
+
 def test_null_and_shape_errors_are_reported_before_launch(lib):
     d = B.conv_desc(1, 4, 4, 8, 8, 1, 1, 1, 0)
     assert lib.pt_conv_fwd(C.byref(d), None, None, None, None, 0, None) == -1
