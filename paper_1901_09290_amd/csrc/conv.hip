@@ -329,6 +329,18 @@ static int32_t bwd_data_classes(const pt_conv_desc* d, const uint16_t* dy, const
     const bool vec_all = d->x_cpitch % 8 == 0 && d->y_cpitch % 8 == 0 && aligned16(dx) && aligned16(dy);
     const bool fuse_zero = with_taps == 1 && c00.TR > 0 && c00.TS > 0 && d->stride_h * d->stride_w > 1 && vec_all &&
                            (d->C % 8 == 0 || (d->flags & PT_CONV_PAD_ZERO)) && c00.TR * c00.TS <= 64;
+    // Classes that the direct kernel takes are collected and sent out together: those that chose the same instantiation
+    // share a launch (a 3 x 3 filter at stride 2 has four classes of 1, 2, 2 and 4 taps: four short launches one after
+    // the other otherwise).
+    IgemmArgs pend_a[kIgemmMaxProblems];
+    IgemmDlPlan pend_p[kIgemmMaxProblems];
+    int n_pend = 0;
+    auto flush = [&]() -> int32_t {
+        if (n_pend == 0) return PT_OK;
+        const int32_t r = hip_status(launch_igemm_dl_planned(pend_a, pend_p, n_pend, st));
+        n_pend = 0;
+        return r;
+    };
     for (int ca = 0; ca < d->stride_h; ++ca) {
         for (int cb = 0; cb < d->stride_w; ++cb) {
             BwdClass c = bwd_data_class(d, ca, cb);
@@ -348,12 +360,17 @@ static int32_t bwd_data_classes(const pt_conv_desc* d, const uint16_t* dy, const
                     a.zf_h = d->stride_h;
                     a.zf_w = d->stride_w;
                 }
-                rc = hip_status(launch_igemm(a, d->y_cpitch % 8 == 0 && aligned16(dy), st));
+                bool planned = false;
+                rc = hip_status(launch_igemm(a, d->y_cpitch % 8 == 0 && aligned16(dy), st, &pend_p[n_pend], &planned));
+                if (rc == PT_OK && planned) {
+                    pend_a[n_pend++] = a;
+                    if (n_pend == kIgemmMaxProblems) rc = flush();
+                }
             }
             if (rc != PT_OK) return rc;
         }
     }
-    return PT_OK;
+    return flush();
 }
 
 // Forward convolution with the statistics epilogue: only the direct kernel has it.

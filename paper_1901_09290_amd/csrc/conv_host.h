@@ -107,7 +107,11 @@ inline IgemmArgs make_bwd_data_args(const pt_conv_desc* d, const BwdClass& c, in
 // elements) - then the direct global->LDS kernel is used, with a tall pixel tile for narrow outputs.
 // Unaligned pitches, and filters with more than 64 taps per launch (the direct kernel keeps one validity
 // bit per tap in a 64-bit mask), take the register-staged kernel.
-inline hipError_t launch_igemm(IgemmArgs& a, bool vec, hipStream_t st) {
+// `plan` == nullptr: the problem is launched.  Otherwise, when the direct kernel takes it, nothing is launched yet: the
+// plan is filled in and *planned set, for launch_igemm_dl_planned to send it out together with other problems (the
+// register-staged kernel is launched at once either way, *planned cleared).
+inline hipError_t launch_igemm(IgemmArgs& a, bool vec, hipStream_t st, IgemmDlPlan* plan = nullptr, bool* planned = nullptr) {
+    if (planned) *planned = false;
     if (!vec) return launch_igemm_cfg<128, 128, 32, 2, 2, 2, 2, false>(a, st);
     // Small dense channel counts (an image-like input): fold the S taps of a filter row into one run
     if (a.CredP < 64 && a.TS > 1 && a.ts_step == 1 && a.apitch == a.CredP && a.bpitch == a.CredP && a.b_ts_stride == 1 &&
@@ -123,9 +127,18 @@ inline hipError_t launch_igemm(IgemmArgs& a, bool vec, hipStream_t st) {
     // 128x128 tiles when they still fill the chip, else 128x64 tiles (more workgroups, deeper pipeline)
     const int64_t tiles128 = ceil_div(a.M, 128) * ceil_div(a.Nout, 128);
     // very many pixel tiles and a narrow output (the stem): tall tiles, so half as many workgroups pay set-up and fill
-    if (a.Nout <= 64 && tiles128 >= 4096 && !a.stats) return launch_igemm_dl_cfg<256, 64, 4, 2, 2>(a, st);
-    if (a.Nout <= 64 || tiles128 < 256) return launch_igemm_dl_cfg<128, 64, 4, 2, 3>(a, st);
-    return launch_igemm_dl_cfg<128, 128, 2, 4, 2>(a, st);
+    IgemmDlPlan own;
+    IgemmDlPlan& p = plan ? *plan : own;
+    hipError_t e;
+    if (a.Nout <= 64 && tiles128 >= 4096 && !a.stats) e = plan_igemm_dl_cfg<256, 64, 4, 2, 2>(a, p);
+    else if (a.Nout <= 64 || tiles128 < 256) e = plan_igemm_dl_cfg<128, 64, 4, 2, 3>(a, p);
+    else e = plan_igemm_dl_cfg<128, 128, 2, 4, 2>(a, p);
+    if (e != hipSuccess) return e;
+    if (plan) {
+        *planned = true;
+        return hipSuccess;
+    }
+    return launch_igemm_dl_planned(&a, &p, 1, st);
 }
 
 inline size_t bwd_data_ws(const pt_conv_desc* d) {

@@ -139,6 +139,14 @@ struct IgemmArgs {
     // input gradient, which is meant to run beside weight gradients of other layers, keeps its set-up and its stores
     // ahead of them too.
     int edge_prio;
+    int grid_x;  // direct kernel: workgroups (tiles) of this problem inside a launch that may hold several problems
+};
+
+// The direct kernel takes up to four problems per launch, one per blockIdx.y (the stride-parity classes of a strided
+// input gradient: disjoint output pixels, the same operands): workgroups past a problem's own tile count leave at once.
+constexpr int kIgemmMaxProblems = 4;
+struct IgemmArgsN {
+    IgemmArgs a[kIgemmMaxProblems];
 };
 
 // Fills tail_kv / tail_nvalid (see IgemmArgs) for the direct kernel's 64-channel blocks.
@@ -416,8 +424,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 // STATS = also reduce the stored outputs to per-channel sums and sums of squares (see IgemmArgs::stats).
 // AV = the caller has established that every tap of every row lies inside the source image (no validity tests).
 template <int BM, int BN, int WGM, int WGN, int STAGES, bool RAGGED, bool TAIL = RAGGED, bool STATS = false, bool AV = false>
-__global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs a) {
+__global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgsN problems) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
+    const IgemmArgs a = problems.a[blockIdx.y];  // (a copy: the fields then live in scalar registers as kernel arguments do)
+    if (blockIdx.x >= (unsigned)a.grid_x) return;  // the whole workgroup: the launch is as wide as its largest problem
     if (a.edge_prio == 2) __builtin_amdgcn_s_setprio(2);
     else if (a.edge_prio == 1) __builtin_amdgcn_s_setprio(1);
     constexpr int NW = WGM * WGN, BK = 64;
@@ -433,7 +443,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int tile = xcd_remap(blockIdx.x, a.grid_x);
     const int n0 = (tile % a.tiles_n) * BN;
     const int m0 = (tile / a.tiles_n) * BM;
 
@@ -811,8 +821,60 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void k_igemm_dl(const IgemmArgs 
 #endif
 }
 
+// What the host has decided for one problem of the direct kernel: which instantiation, and its launch shape.
+typedef void (*igemm_dl_kern_t)(const IgemmArgsN);
+struct IgemmDlPlan {
+    igemm_dl_kern_t kern;
+    LdsOptIn* opt_in;
+    // the same instantiation with the tap validity tests (== kern unless the problem is free of them): what a group of
+    // problems falls back to when only some of them could do without
+    igemm_dl_kern_t kern_tests;
+    LdsOptIn* opt_in_tests;
+    size_t lds, lds_used;
+    int threads;
+};
+
+// Problems that chose the same instantiation go out as ONE launch (blockIdx.y = problem): the tail of one overlaps the
+// head of the next, and a group of short launches pays the fixed cost of a launch once.
+inline hipError_t launch_igemm_dl_planned(const IgemmArgs* as, const IgemmDlPlan* ps, int n, hipStream_t st) {
+    bool done[kIgemmMaxProblems] = {false, false, false, false};
+    if (n > kIgemmMaxProblems) return hipErrorInvalidValue;
+    IgemmDlPlan local[kIgemmMaxProblems];
+    bool same = true, same_tests = true;
+    for (int i = 1; i < n; ++i) {
+        same = same && ps[i].kern == ps[0].kern;
+        same_tests = same_tests && ps[i].kern_tests == ps[0].kern_tests;
+    }
+    if (!same && same_tests) {  // one launch with the validity tests rather than two without and with
+        for (int i = 0; i < n; ++i) {
+            local[i] = ps[i];
+            local[i].kern = ps[i].kern_tests;
+            local[i].opt_in = ps[i].opt_in_tests;
+        }
+        ps = local;
+    }
+    for (int i = 0; i < n; ++i) {
+        if (done[i]) continue;
+        IgemmArgsN m{};
+        int cnt = 0, gx = 0;
+        size_t lds_used = 0;
+        for (int j = i; j < n; ++j) {
+            if (done[j] || ps[j].kern != ps[i].kern) continue;
+            done[j] = true;
+            m.a[cnt++] = as[j];
+            gx = as[j].grid_x > gx ? as[j].grid_x : gx;
+            lds_used = ps[j].lds_used > lds_used ? ps[j].lds_used : lds_used;
+        }
+        if (hipError_t e = ps[i].opt_in->ensure(reinterpret_cast<const void*>(ps[i].kern), ps[i].lds); e != hipSuccess) return e;
+        // (several problems: a width that is a multiple of the 8 XCDs keeps every problem's tile -> XCD assignment)
+        const unsigned gxr = cnt > 1 ? (unsigned)((gx + 7) / 8 * 8) : (unsigned)gx;
+        hipLaunchKernelGGL(ps[i].kern, dim3(gxr, (unsigned)cnt), dim3((unsigned)ps[i].threads), lds_used, st, m);
+    }
+    return hipSuccess;
+}
+
 template <int BM, int BN, int WGM, int WGN, int STAGES>
-inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
+inline hipError_t plan_igemm_dl_cfg(IgemmArgs& a, IgemmDlPlan& plan) {
     constexpr int NT = 64 * WGM * WGN;
     constexpr size_t lds = (size_t)STAGES * (BM + BN) * 128;
     static_assert(lds <= 160 * 1024, "LDS capacity");
@@ -844,7 +906,7 @@ inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
     a.a_all_valid = inside(h_first, h_last, a.srcH) && inside(h_first + rr, h_last + rr, a.srcH) &&
                     inside(w_first, w_last, a.srcW) && inside(w_first + ss, w_last + ss, a.srcW);
     const bool av = a.a_all_valid && variant != 2;
-    typedef void (*kern_t)(const IgemmArgs);
+    typedef igemm_dl_kern_t kern_t;
     const kern_t kerns[2][5] = {{k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, false, false>,
                                  k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, false, false>,
                                  k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, true, false, false>,
@@ -855,16 +917,28 @@ inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
                                  nullptr,
                                  k_igemm_dl<BM, BN, WGM, WGN, STAGES, false, false, true, true>,
                                  k_igemm_dl<BM, BN, WGM, WGN, STAGES, true, false, true, true>}};
-    const kern_t kern = kerns[av ? 1 : 0][variant];
     static LdsOptIn opt_in[2][5];
-    if (hipError_t e = opt_in[av ? 1 : 0][variant].ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
-    const dim3 grid((unsigned)(ceil_div(a.M, BM) * a.tiles_n)), block(NT);
+    plan.kern = kerns[av ? 1 : 0][variant];
+    plan.opt_in = &opt_in[av ? 1 : 0][variant];
+    plan.kern_tests = kerns[0][variant];
+    plan.opt_in_tests = &opt_in[0][variant];
+    plan.lds = lds;
+    plan.threads = NT;
+    const int64_t tiles = ceil_div(a.M, BM) * a.tiles_n;
+    if (tiles > 0x7fffffff) return hipErrorInvalidValue;
+    a.grid_x = (int)tiles;
     // A reduction of fewer steps than the pipeline has stages touches only the first nk stage buffers (and the
     // statistics epilogue a few KB of the first): the launch asks for no more LDS than that, which leaves room on the
     // CU for workgroups of kernels running beside it (train step at pruned widths -0.6 %, full -0.2 %).
-    const size_t lds_used = (size_t)(a.nk < STAGES ? (a.nk < 1 ? 1 : a.nk) : STAGES) * (BM + BN) * 128;
-    hipLaunchKernelGGL(kern, grid, block, lds_used, st, a);
+    plan.lds_used = (size_t)(a.nk < STAGES ? (a.nk < 1 ? 1 : a.nk) : STAGES) * (BM + BN) * 128;
     return hipSuccess;
+}
+
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+inline hipError_t launch_igemm_dl_cfg(IgemmArgs& a, hipStream_t st) {
+    IgemmDlPlan plan;
+    if (hipError_t e = plan_igemm_dl_cfg<BM, BN, WGM, WGN, STAGES>(a, plan); e != hipSuccess) return e;
+    return launch_igemm_dl_planned(&a, &plan, 1, st);
 }
 
 // ------------------------------------------------------------------------------------------- //
