@@ -367,9 +367,8 @@ def main():
     dom_kernel = max(kernels, key=lambda k: sum(tot[f] for f in kernels[k]))
     fams = kernels[dom_kernel]
 
-    def launches(s, f):  # the input gradient is one launch per stride-parity class that holds a filter tap
-        return min(s.stride, s.R) * min(s.stride, s.S) if f == "bwd_data" else 1
-    n_launch = sum(launches(l.spec, f) for f in fams for net in nets.values() for l in net.layers if has_call(l.spec, f))
+    # one launch per call: the stride-parity classes of a strided input gradient share a launch
+    n_launch = sum(1 for f in fams for net in nets.values() for l in net.layers if has_call(l.spec, f))
     dom_flops = sum(fl[t][f] for f in fams for t in nets)
     dom_bytes = sum(by[t][f] for f in fams for t in nets)
     dom_s = sum(tot[f] for f in fams) * 1e-3
