@@ -223,6 +223,7 @@ def main():
     full.overlap_wgrad = pruned.overlap_wgrad = not args.no_overlap
     full.fuse_lasso = pruned.fuse_lasso = not args.no_fused_lasso
     full.overlap_branches = pruned.overlap_branches = not args.no_branch_overlap
+    full.batch_branches_fwd = pruned.batch_branches_fwd = not args.no_branch_overlap and os.environ.get('PT_NOPAIR') is None
     rng = np.random.Generator(np.random.PCG64(10 + int(round(args.sparsity * 10))))
     zero_sets = wl.zeroed_channel_sets(pruned_edges, args.sparsity, rng)
     rweights = wl.network_weights(pruned_specs, pruned_edges, zero_sets, rng)

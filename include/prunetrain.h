@@ -94,6 +94,15 @@ int32_t pt_conv_bwd_weight_workspace_bytes(const pt_conv_desc* d, size_t* bytes)
 int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, uint16_t* y, void* ws,
                     size_t ws_bytes, void* stream);
 
+/* n independent forward convolutions in one call (Sec. 2.1: e.g. the first convolution of a residual block and the
+ * block's shortcut convolution, which read the same input and meet only at the block's output).  Same results as n
+ * calls of pt_conv_fwd; problems that the direct kernel takes with the same instantiation share a launch, so the
+ * tail of one overlaps the head of the next.  descs: host array of n descriptors; x, w, y: host arrays of n device
+ * pointers each.  n <= 0 is an error (PT_ERR_SHAPE); any invalid descriptor or NULL pointer fails the whole call
+ * before anything is launched. */
+int32_t pt_conv_fwd_batched(const pt_conv_desc* descs, const uint16_t* const* x, const uint16_t* const* w,
+                            uint16_t* const* y, int32_t n, void* stream);
+
 /* dx = adjoint of the forward map in x applied to dy:
  * dx[n,h,w,c] = sum over (p,q,k,r,s) with p*stride_h - pad_h + r == h, q*stride_w - pad_w + s == w
  *               of dy[n,p,q,k] * w[k,r,s,c].   dy, w bf16; dx bf16, every logical element written

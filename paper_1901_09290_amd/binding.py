@@ -24,7 +24,7 @@ CONV_PAD_ZERO = 1  # pt_conv_desc.flags: padding channels of the input tensors a
 EXPORTS = [
     "pt_version", "pt_last_hip_error",
     "pt_conv_fwd_workspace_bytes", "pt_conv_bwd_data_workspace_bytes", "pt_conv_bwd_weight_workspace_bytes",
-    "pt_conv_fwd", "pt_conv_bwd_data", "pt_conv_bwd_weight",
+    "pt_conv_fwd", "pt_conv_fwd_batched", "pt_conv_bwd_data", "pt_conv_bwd_weight",
     "pt_group_norms_workspace_bytes", "pt_group_norms", "pt_group_lasso_grad",
     "pt_group_norms_batched_workspace_bytes", "pt_group_norms_batched", "pt_group_lasso_grad_batched",
     "pt_group_norms_detect_batched_workspace_bytes", "pt_group_norms_detect_batched", "pt_conv_bwd_weight_plan",
@@ -139,6 +139,7 @@ def lib() -> C.CDLL:
             "pt_conv_bwd_data_workspace_bytes": [dp, C.POINTER(sz)],
             "pt_conv_bwd_weight_workspace_bytes": [dp, C.POINTER(sz)],
             "pt_conv_fwd": [dp, vp, vp, vp, vp, sz, vp],
+            "pt_conv_fwd_batched": [dp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i32, vp],
             "pt_conv_bwd_data": [dp, vp, vp, vp, vp, sz, vp],
             "pt_conv_bwd_weight": [dp, vp, vp, vp, vp, sz, vp],
             "pt_conv_bwd_weight_lasso_workspace_bytes": [dp, C.POINTER(sz)],
@@ -244,6 +245,18 @@ def _ws(ws):
 def conv_fwd(d: ConvDesc, x, w, y, ws=None, stream=None) -> None:
     p, n = _ws(ws)
     _ck("pt_conv_fwd", lib().pt_conv_fwd(C.byref(d), _ptr(x), _ptr(w), _ptr(y), p, n, _stream(stream)))
+
+
+def conv_fwd_jobs(descs: Sequence[ConvDesc], xs, ws, ys):
+    """Argument arrays of conv_fwd_batched, built once for a fixed set of layers."""
+    n = len(descs)
+    return ((ConvDesc * n)(*descs), (C.c_void_p * n)(*[_ptr(t) for t in xs]), (C.c_void_p * n)(*[_ptr(t) for t in ws]),
+            (C.c_void_p * n)(*[_ptr(t) for t in ys]), n)
+
+
+def conv_fwd_batched(jobs, stream=None) -> None:
+    d, x, w, y, n = jobs
+    _ck("pt_conv_fwd_batched", lib().pt_conv_fwd_batched(d, x, w, y, n, _stream(stream)))
 
 
 def conv_bwd_data(d: ConvDesc, dy, w, dx, ws=None, stream=None) -> None:

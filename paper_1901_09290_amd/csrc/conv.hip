@@ -292,6 +292,13 @@ static int32_t hip_status(hipError_t e) {
     return launch_status();
 }
 
+// image-like first layer (at most 4 channels at a pitch of 8, zero padding vouched for): its own kernel
+static bool stem_fwd_ok(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, const uint16_t* y) {
+    return d->C <= 4 && d->x_cpitch == 8 && d->w_cpitch == 8 && (d->flags & PT_CONV_PAD_ZERO) && d->y_cpitch % 8 == 0 &&
+           aligned16(x) && aligned16(w) && aligned16(y) && d->stride_h == d->stride_w && d->stride_h <= 2 &&
+           d->R <= kStemMaxR && d->S <= 8 && (int64_t)d->H * d->W * 16 <= 0x7fffffff;
+}
+
 extern "C" int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, uint16_t* y, void* ws,
                                size_t ws_bytes, void* stream) {
     (void)ws;
@@ -299,16 +306,52 @@ extern "C" int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const u
     int32_t rc = check_desc(d);
     if (rc != PT_OK) return rc;
     if (!x || !w || !y) return PT_ERR_NULL;
-    // image-like first layer (at most 4 channels at a pitch of 8, zero padding vouched for): its own kernel
-    if (d->C <= 4 && d->x_cpitch == 8 && d->w_cpitch == 8 && (d->flags & PT_CONV_PAD_ZERO) && d->y_cpitch % 8 == 0 &&
-        aligned16(x) && aligned16(w) && aligned16(y) && d->stride_h == d->stride_w && d->stride_h <= 2 && d->R <= kStemMaxR &&
-        d->S <= 8 && (int64_t)d->H * d->W * 16 <= 0x7fffffff) {
+    if (stem_fwd_ok(d, x, w, y)) {
         StemArgs s{x, w, y, d->N, d->H, d->W, d->P, d->Q, d->K, d->R, d->S, d->pad_h, d->pad_w, d->y_cpitch, 0, 0, 0, 0};
         return hip_status(launch_stem_fwd(s, d->stride_h, kStemSlots, (hipStream_t)stream));
     }
     IgemmArgs a = make_fwd_args(d, x, w, y);
     const bool vec = d->x_cpitch % 8 == 0 && d->w_cpitch % 8 == 0 && aligned16(x) && aligned16(w);
     return hip_status(launch_igemm(a, vec, (hipStream_t)stream));
+}
+
+extern "C" int32_t pt_conv_fwd_batched(const pt_conv_desc* descs, const uint16_t* const* x, const uint16_t* const* w,
+                                       uint16_t* const* y, int32_t n, void* stream) {
+    if (n <= 0) return PT_ERR_SHAPE;
+    if (!descs || !x || !w || !y) return PT_ERR_NULL;
+    for (int i = 0; i < n; ++i) {
+        const int32_t rc = check_desc(&descs[i]);
+        if (rc != PT_OK) return rc;
+        if (!x[i] || !w[i] || !y[i]) return PT_ERR_NULL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    IgemmArgs pend_a[kIgemmMaxProblems];
+    IgemmDlPlan pend_p[kIgemmMaxProblems];
+    int n_pend = 0;
+    auto flush = [&]() -> int32_t {
+        if (n_pend == 0) return PT_OK;
+        const int32_t r = hip_status(launch_igemm_dl_planned(pend_a, pend_p, n_pend, st));
+        n_pend = 0;
+        return r;
+    };
+    for (int i = 0; i < n; ++i) {
+        const pt_conv_desc* d = &descs[i];
+        if (stem_fwd_ok(d, x[i], w[i], y[i])) {  // an image-like first layer keeps its own kernel
+            const int32_t rc = pt_conv_fwd(d, x[i], w[i], y[i], nullptr, 0, stream);
+            if (rc != PT_OK) return rc;
+            continue;
+        }
+        IgemmArgs a = make_fwd_args(d, x[i], w[i], y[i]);
+        const bool vec = d->x_cpitch % 8 == 0 && d->w_cpitch % 8 == 0 && aligned16(x[i]) && aligned16(w[i]);
+        bool planned = false;
+        int32_t rc = hip_status(launch_igemm(a, vec, st, &pend_p[n_pend], &planned));
+        if (rc == PT_OK && planned) {
+            pend_a[n_pend++] = a;
+            if (n_pend == kIgemmMaxProblems) rc = flush();
+        }
+        if (rc != PT_OK) return rc;
+    }
+    return flush();
 }
 
 // Input gradient from weights already in [C][RS][round_up(K,8)] order: one implicit GEMM per stride-parity class.

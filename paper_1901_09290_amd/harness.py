@@ -195,6 +195,13 @@ class Network:
         # sixth stream on four hardware queues - the step gets 11 % slower; the shortcut's forward convolution beside
         # the residual branch's changes nothing measurable and stays in line.
         self.overlap_branches = True
+        # In the forward pass the shortcut convolution and the first convolution of the residual branch (same input,
+        # independent outputs) go out in one call: where both take the same instantiation of the direct kernel they
+        # share a launch, with no stream of their own and no cross-stream dependency.
+        self.batch_branches_fwd = True
+        self.fwd_pairs = {j: B.conv_fwd_jobs([self.layers[k].desc for k in (j, i)], [self.layers[k].x for k in (j, i)],
+                                             [self.layers[k].w_bf16 for k in (j, i)], [self.layers[k].y for k in (j, i)])
+                          for j, i in self.fork.items()}
         # weight gradients run on a second stream, off the critical path of the input-gradient chain
         self.sides = [torch.cuda.Stream() for _ in range(WGRAD_STREAMS)]
         self.ws_sides = [self.ws] + [torch.empty_like(self.ws) for _ in range(WGRAD_STREAMS - 1)]
@@ -237,10 +244,14 @@ class Network:
                 if self.crsk_jobs is not None:
                     side.wait_event(head_ready)    # the copies read every layer's bf16 weights, the head layers' too
                     B.weights_to_crsk_batched(self.crsk_jobs)
+            pairs = self.batch_branches_fwd and all(i < self.norm_head for i in self.branch_of)
             for i, l in enumerate(self.layers):
                 if i == self.norm_head:
                     main.wait_event(tail_ready)
-                l.fwd(self.ws)
+                if pairs and i in self.fork:
+                    B.conv_fwd_batched(self.fwd_pairs[i])
+                elif not (pairs and i in self.branch_of):
+                    l.fwd(self.ws)
             main.wait_stream(side)                 # the k-innermost weight copies are final
         if not self.overlap_wgrad:
             for l in reversed(self.layers):

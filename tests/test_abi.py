@@ -102,6 +102,21 @@ def test_first_layer_weight_gradient_plan_and_workspace(lib):
     assert B.conv_bwd_weight_plan(wide, True).tiles > 1
 
 
+def test_batched_forward_validates_every_problem_before_launching(lib):
+    d = B.conv_desc(2, 8, 8, 16, 16, 1, 1, 1, 0)
+    bad = B.conv_desc(2, 8, 8, 16, 16, 1, 1, 1, 0)
+    bad.P = 99
+    two = (B.ConvDesc * 2)(d, bad)
+    ptrs = (C.c_void_p * 2)(256, 256)       # never dereferenced: validation comes first
+    assert lib.pt_conv_fwd_batched(two, ptrs, ptrs, ptrs, 2, None) == -2         # second descriptor inconsistent
+    assert lib.pt_conv_fwd_batched(two, ptrs, ptrs, ptrs, 0, None) == -2         # no problems
+    assert lib.pt_conv_fwd_batched(None, ptrs, ptrs, ptrs, 1, None) == -1
+    assert lib.pt_conv_fwd_batched(two, None, ptrs, ptrs, 1, None) == -1
+    holes = (C.c_void_p * 2)(256, None)
+    good = (B.ConvDesc * 2)(d, d)
+    assert lib.pt_conv_fwd_batched(good, ptrs, holes, ptrs, 2, None) == -1       # a NULL pointer in the second problem
+
+
 def test_null_and_shape_errors_are_reported_before_launch(lib):
     d = B.conv_desc(1, 4, 4, 8, 8, 1, 1, 1, 0)
     assert lib.pt_conv_fwd(C.byref(d), None, None, None, None, 0, None) == -1

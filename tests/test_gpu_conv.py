@@ -164,6 +164,43 @@ def test_narrow_outputs_over_very_many_pixels(case):
     _check_full(spec, 700 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=True)
 
 
+BATCHED_FWD = [
+    # independent forward convolutions in one call: pairs that share a launch of the direct kernel (same tile shape and
+    # variant: a block's first convolution and its strided shortcut), pairs that do not, and the other kernels mixed in
+    [(4, 28, 28, 128, 64, 1, 1, 0), (4, 28, 28, 128, 256, 1, 2, 0)],          # 1x1 and strided 1x1 shortcut, same input shape
+    [(6, 56, 56, 256, 128, 1, 1, 0), (6, 56, 56, 256, 512, 1, 2, 0)],         # both 128 x 128 tiles: one launch, two problems
+    [(6, 56, 56, 209, 87, 1, 1, 0), (6, 56, 56, 209, 371, 1, 2, 0)],          # ragged widths
+    [(2, 14, 14, 64, 64, 3, 1, 1), (2, 14, 14, 64, 256, 1, 1, 0), (2, 14, 14, 64, 64, 1, 1, 0)],   # three problems, mixed shapes
+    [(2, 18, 18, 3, 16, 7, 2, 3), (2, 12, 12, 24, 40, 3, 1, 1)],               # an image-like first layer beside a 3 x 3 layer
+    [(2, 9, 9, 16, 24, 1, 1, 0)] * 5,                                          # more problems than one launch holds
+]
+
+
+@pytest.mark.parametrize("cases", BATCHED_FWD, ids=lambda cs: "+".join("x".join(map(str, c)) for c in cs)[:60])
+def test_batched_forward_against_oracle_and_single_calls(cases):
+    """pt_conv_fwd_batched: every problem's output against the oracle and bit for bit against pt_conv_fwd alone."""
+    from gpu_util import CONV_TOL, DEV, dev_bf16, host_bf16, pitch8, rel_err
+    from paper_1901_09290_amd import binding as B
+    specs = [_spec(*c) for c in cases]
+    rng = np.random.Generator(np.random.PCG64(900 + sum(map(sum, cases))))
+    descs, xs, ws, ys, singles, refs = [], [], [], [], [], []
+    for spec in specs:
+        t = wl.conv_tensors(spec, rng, want=("x", "w"))
+        xp, yp, wp = pitch8(spec.C), pitch8(spec.K), pitch8(spec.C)
+        d = B.desc_of(spec, xp, yp, wp, B.CONV_PAD_ZERO)
+        x, w = dev_bf16(t["x"], xp, pad=0), dev_bf16(t["w"], wp, pad=0)   # zero padding, as vouched for
+        y = torch.full((spec.N, spec.P, spec.Q, yp), -1, dtype=torch.int16, device=DEV)
+        y1 = torch.full_like(y, -1)
+        B.conv_fwd(d, x, w, y1)
+        descs.append(d); xs.append(x); ws.append(w); ys.append(y); singles.append(y1)
+        refs.append(oracle.conv_fwd(oracle.shape_of(spec), t["x"], t["w"]))
+    B.conv_fwd_batched(B.conv_fwd_jobs(descs, xs, ws, ys))
+    torch.cuda.synchronize()
+    for spec, y, y1, ref in zip(specs, ys, singles, refs):
+        assert torch.equal(y, y1), spec
+        assert rel_err(host_bf16(y, spec.K), ref) <= CONV_TOL, spec
+
+
 FUSED_LASSO = [
     # N  H   W   C    K   R st pad   flags  path    reductions split over many workgroups, and single-slab ones
     ((2, 12, 12, 64, 64, 3, 1, 1), 3, None),

@@ -180,7 +180,7 @@ def test_cfg2_resnet32_train_step_on_side_streams_against_oracle(norms_head, bra
     names = [s.name for s in specs]
     assert net.overlap_branches and {names[j]: names[i] for j, i in net.fork.items()} == {
         "stage2_b0_a": "stage2_proj", "stage3_b0_a": "stage3_proj"}
-    net.overlap_branches = branches
+    net.overlap_branches = net.batch_branches_fwd = branches   # (forward: shortcut and first convolution in one call)
     lam = 50.0
 
     def check(weights):
