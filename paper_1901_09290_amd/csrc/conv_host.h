@@ -166,9 +166,13 @@ constexpr int kWgDlBKPBig = 32;
 // slots on purpose: weight gradients of different layers are independent and are meant to run side by side on
 // several streams, so one launch need not fill the chip, and every split costs a tile of fp32 partial sums written
 // and read again.  Measured on the ResNet-50 step with four side streams: 512/256 -> 245, 256/96 -> 264 TFLOP/s
-// (run one after the other on a single stream the same launches are ~25 % slower than with 512/256).
+// (run one after the other on a single stream the same launches are ~25 % slower than with 512/256).  Later, with
+// the first layer on a kernel of its own, A/B in one process (train step at full + pruned width, two runs each):
+// 256/96 6.29 ms, 192/96 6.24, 160/96 6.23, 128/96 6.26, 192/112 6.29, 160/112 6.28, 320/96 6.37, 256/80 6.40,
+// 256/128 6.39 - although the weight-gradient family called one after the other is fastest at 256/128 (1.79 vs
+// 2.09 ms at full width): fewer, longer workgroups leave the input-gradient chain more of the chip.
 #ifndef PT_WG_TARGET_SMALL
-#define PT_WG_TARGET_SMALL 256
+#define PT_WG_TARGET_SMALL 160
 #endif
 #ifndef PT_WG_TARGET_BIG
 #define PT_WG_TARGET_BIG 96
