@@ -89,8 +89,9 @@ int32_t pt_conv_bwd_weight_workspace_bytes(const pt_conv_desc* d, size_t* bytes)
 /* y[n,p,q,k] = sum_{r,s,c} x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c] * w[k,r,s,c].
  * x, w bf16; y bf16 (fp32 accumulator rounded once). ws: device scratch of ws_bytes (256-byte aligned).
  * An image-like first layer under PT_CONV_PAD_ZERO (C <= 4 at x_cpitch = w_cpitch = 8, y_cpitch a multiple of 8,
- * filter <= 8 x 8, stride 1 or 2, 16-byte aligned tensors) takes a kernel of its own; same results to the same
- * tolerance. */
+ * filter <= 8 x 8, stride 1 or 2, 16-byte aligned tensors) takes a kernel of its own, and so does a 3 x 3 filter at
+ * stride 1 and padding 1 with at most 64 channels on either side (pitches multiples of 8, channel counts multiples
+ * of 8 or PT_CONV_PAD_ZERO); same results to the same tolerance. */
 int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, uint16_t* y, void* ws,
                     size_t ws_bytes, void* stream);
 

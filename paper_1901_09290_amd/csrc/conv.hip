@@ -310,6 +310,11 @@ extern "C" int32_t pt_conv_fwd(const pt_conv_desc* d, const uint16_t* x, const u
         StemArgs s{x, w, y, d->N, d->H, d->W, d->P, d->Q, d->K, d->R, d->S, d->pad_h, d->pad_w, d->y_cpitch, 0, 0, 0, 0};
         return hip_status(launch_stem_fwd(s, d->stride_h, kStemSlots, (hipStream_t)stream));
     }
+    if (res3_fwd_ok(d, x, w, y)) {  // early 3 x 3 layer: the filter bank stays in LDS
+        const int cinp = (int)round_up(d->C, 8);
+        Res3Args r{x, w, y, d->N, d->H, d->W, d->C, cinp, d->x_cpitch, d->K, d->w_cpitch, d->y_cpitch, 0, 0, 0, 0, 0};
+        return hip_status(launch_conv3x3_res(r, false, (hipStream_t)stream));
+    }
     IgemmArgs a = make_fwd_args(d, x, w, y);
     const bool vec = d->x_cpitch % 8 == 0 && d->w_cpitch % 8 == 0 && aligned16(x) && aligned16(w);
     return hip_status(launch_igemm(a, vec, (hipStream_t)stream));
@@ -336,7 +341,7 @@ extern "C" int32_t pt_conv_fwd_batched(const pt_conv_desc* descs, const uint16_t
     };
     for (int i = 0; i < n; ++i) {
         const pt_conv_desc* d = &descs[i];
-        if (stem_fwd_ok(d, x[i], w[i], y[i])) {  // an image-like first layer keeps its own kernel
+        if (stem_fwd_ok(d, x[i], w[i], y[i]) || res3_fwd_ok(d, x[i], w[i], y[i])) {  // layers with a kernel of their own
             const int32_t rc = pt_conv_fwd(d, x[i], w[i], y[i], nullptr, 0, stream);
             if (rc != PT_OK) return rc;
             continue;
@@ -358,6 +363,11 @@ extern "C" int32_t pt_conv_fwd_batched(const pt_conv_desc* descs, const uint16_t
 static int32_t bwd_data_classes(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* wt, uint16_t* dx,
                                 hipStream_t st) {
     int32_t rc = PT_OK;
+    if (res3_bwd_ok(d, dy, wt, dx)) {  // the same kernel on dy with the k-innermost filter copy and mirrored taps
+        const int kp = (int)round_up(d->K, 8);
+        Res3Args r{dy, wt, dx, d->N, d->H, d->W, d->K, kp, d->y_cpitch, d->C, kp, d->x_cpitch, 0, 0, 0, 0, 0};
+        return hip_status(launch_conv3x3_res(r, true, st));
+    }
     // A filter no larger than the stride reaches only some stride-parity classes of input pixels.  When class
     // (0, 0) is the only one with taps, its launch also clears the other classes (they tile into cells anchored at
     // its pixels), which saves up to stride_h * stride_w - 1 small launches; this needs the vector store path and a

@@ -227,6 +227,32 @@ inline WgradPlan plan_wgrad(const pt_conv_desc* d, bool dl) {
     return p;
 }
 
+// The resident-weights kernel takes 3 x 3 filters at stride 1 and padding 1 with at most 64 channels on either side,
+// 16-byte aligned rows, and channel counts that are multiples of 8 or the caller's PT_CONV_PAD_ZERO (the padding of the
+// operand it reduces over must be zero, and it writes the output's last chunk whole, zeros in its padding).
+// PT_RES3: bit 0 = forward calls, bit 1 = input-gradient calls, bit 2 = those of any filter bank size.
+#ifndef PT_RES3
+#define PT_RES3 3
+#endif
+constexpr int kRes3BwdMaxBank = 3072;  // K * C up to which an input-gradient call takes the kernel
+inline bool res3_shape_ok(const pt_conv_desc* d) {
+    return d->R == 3 && d->S == 3 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 1 && d->pad_w == 1 && d->C <= 64 &&
+           d->K <= 64 && d->x_cpitch % 8 == 0 && d->y_cpitch % 8 == 0 &&
+           (int64_t)d->H * d->W * (d->x_cpitch > d->y_cpitch ? d->x_cpitch : d->y_cpitch) * 2 <= 0x7fffffff;
+}
+inline bool res3_fwd_ok(const pt_conv_desc* d, const uint16_t* x, const uint16_t* w, const uint16_t* y) {
+    return (PT_RES3 & 1) && res3_shape_ok(d) && d->w_cpitch % 8 == 0 && aligned16(x) && aligned16(w) && aligned16(y) &&
+           ((d->C % 8 == 0 && d->K % 8 == 0) || (d->flags & PT_CONV_PAD_ZERO));
+}
+inline bool res3_bwd_ok(const pt_conv_desc* d, const uint16_t* dy, const uint16_t* wt, const uint16_t* dx) {
+    // (input-gradient launches share the chip with weight gradients on other streams, and a workgroup that holds a CU's
+    // whole LDS for the length of the launch shuts those out: with the full 64 x 64 filter bank the train step gets
+    // 25 us slower, with the smaller banks of a pruned network 25 us faster - so only those take it here)
+    return (PT_RES3 & 2) && res3_shape_ok(d) && (PT_RES3 & 4 || d->C * d->K <= kRes3BwdMaxBank) && aligned16(dy) &&
+           aligned16(wt) && aligned16(dx) &&
+           ((d->C % 8 == 0 && d->K % 8 == 0) || (d->flags & PT_CONV_PAD_ZERO));
+}
+
 // The first layer's own weight-gradient kernel takes image-like inputs: at most 4 channels at a pitch of 8, at most 64
 // output channels, a filter of at most 8 x 8 at stride 1 or 2, and sizes whose byte offsets fit its 32-bit addressing.
 inline bool stem_wgrad_ok(const pt_conv_desc* d) {

@@ -1832,6 +1832,233 @@ inline hipError_t launch_wgrad_dl_cfg(WgradArgs& a, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------------------- //
+// 3 x 3 convolution at stride 1, padding 1, with at most 64 channels on either side: weights resident in LDS
+// ------------------------------------------------------------------------------------------- //
+// The early 3 x 3 layers of a network (many pixels, few channels) have nine reduction steps per tile in the
+// implicit-GEMM kernel, and a workgroup there spends as long on its set-up, its first loads and its stores as on the
+// steps.  Here ONE workgroup per CU keeps the whole filter bank in LDS ([64 outputs][9 taps][64 channels] bf16, rows
+// padded by 16 bytes so that the 32 rows a fragment read touches spread over all banks) and walks over a run of tiles of
+// 4 x 8*nb output pixels (nb <= 7 column blocks of 8).  Per tile the input patch with its halo, 6 x (8*nb + 2) pixels x
+// 128 bytes, goes to one of two LDS buffers by 16-byte global->LDS loads (out-of-image pixels and channels past the
+// count fetch zeros), the next tile's patch while the current one is multiplied.  Wave b of the eight owns column block
+// b: 4 x 8 pixels x 64 outputs, two accumulator blocks; per (tap, 16 channels) one 16-byte patch read and two weight
+// reads feed two MFMAs.  The nine taps are nine windows of the same patch: nothing is fetched twice.  The 16-byte
+// chunks of a patch pixel are XOR-ed with ((column >> 1) & 3) | ((row & 1) << 2): the 16 lanes one LDS cycle serves
+// (two rows of eight pixels) then read 16 different bank groups, for every tap.  FLIP: the weights are indexed by the
+// mirrored tap (input gradient: the same kernel on dy with the k-innermost filter copy).
+struct Res3Args {
+    const uint16_t* X;   // [N][H][W][ip]
+    const uint16_t* Wt;  // [Mout][9][wp], reduction channel innermost
+    uint16_t* Y;         // [N][H][W][op]
+    int N, H, W, Cin, CinP, ip, Mout, wp, op;  // CinP = Cin rounded up to 8
+    int nb;                                  // column blocks of 8 pixels per tile
+    int tiles_x, tiles_y, tiles, run;
+};
+constexpr int kR3TH = 4, kR3MaxNB = 7, kR3PH = kR3TH + 2, kR3PW = 8 * kR3MaxNB + 2;
+constexpr int kR3WRow = 9 * 128 + 16, kR3WBytes = 64 * kR3WRow;
+constexpr int kR3PatchSlots = kR3PH * kR3PW * 8, kR3PatchBytes = kR3PatchSlots * 16;
+constexpr int kR3Lds = kR3WBytes + 2 * kR3PatchBytes;
+constexpr int kR3Slots = 256;  // one workgroup per CU
+static_assert(kR3Lds <= 160 * 1024 && (64 * (kR3WRow / 16)) % 64 == 0, "LDS plan");
+
+// NCB: 16-channel steps per tap (CinP / 16 rounded up); KB1: more than 32 outputs (the second accumulator block is live).
+// Compile-time so that the 9 * NCB steps of a tile are one straight line of code: with a branch per step every fragment
+// read is waited out before its MFMA (27 us against 34 us for the implicit-GEMM kernel on 56 x 56 x 64 -> 64;
+// straight-line with the reads of step s + 1 issued before the MFMAs of step s: see the numbers in the notes).
+template <bool FLIP, int NCB, bool KB1>
+__global__ __launch_bounds__(512) void k_conv3x3_res(const Res3Args a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr uint32_t kBufOut = 0xffffffffu, kBufFlags = 0x00020000u;
+    constexpr int WSLOTS = kR3WRow / 16;                       // 16-byte slots per weight row (73, the last one padding)
+    constexpr int NWL = 64 * WSLOTS / 64, WL = (NWL + 7) / 8;  // wave-level loads of the weights, per wave
+    constexpr int NPL = (kR3PatchSlots + 63) / 64, PL = (NPL + 7) / 8;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_b[];
+    uint8_t* wl = smem_b;
+    uint8_t* pbuf = smem_b + kR3WBytes;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int first = blockIdx.x * a.run, last = first + a.run < a.tiles ? first + a.run : a.tiles;
+    if (first >= last) return;  // whole workgroup
+
+    // ---- filter bank -> LDS, once ---------------------------------------------------------------------------------
+    {
+        const __amdgpu_buffer_rsrc_t w_srd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(a.Wt), 0, (uint32_t)(a.Mout * 9 * a.wp) * 2u, kBufFlags);
+#pragma unroll
+        for (int i = 0; i < WL; ++i) {
+            const int idx = wave + 8 * i < NWL ? wave + 8 * i : NWL - 1;  // (past the end: the last one again)
+            const int sl = idx * 64 + lane;
+            const int m = sl / WSLOTS, wi = sl - m * WSLOTS;
+            const int t = wi >> 3, j = wi & 7;
+            const bool ok = wi < 72 && m < a.Mout && j * 8 < a.CinP;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_srd, (lds_void_ptr)(wl + idx * 1024), 16,
+                                                     ok ? (uint32_t)(((m * 9 + t) * a.wp + j * 8) * 2) : kBufOut, 0, 0, 0);
+        }
+    }
+    // ---- this lane's slots of a patch: the same places in every tile ---------------------------------------------------
+    int p_rc[PL];        // row << 16 | column, or -1
+    uint32_t p_rel[PL];  // byte offset of the chunk from the patch's first pixel
+    int p_idx[PL];
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+        p_idx[i] = wave + 8 * i < NPL ? wave + 8 * i : NPL - 1;
+        const int sl = p_idx[i] * 64 + lane;
+        const int pr = sl / (kR3PW * 8), rem = sl - pr * (kR3PW * 8);
+        const int pc = rem >> 3, pj = rem & 7;
+        const int j = pj ^ (((pc >> 1) & 3) | ((pr & 1) << 2));  // the logical chunk that belongs at this place
+        const bool ok = sl < kR3PatchSlots && j * 8 < a.CinP && pc < 8 * a.nb + 2;
+        p_rc[i] = ok ? (pr << 16) | pc : (sl < kR3PatchSlots ? -1 : -2);
+        p_rel[i] = (uint32_t)(((pr * a.W + pc) * a.ip + j * 8) * 2);
+    }
+    const uint32_t in_bytes = (uint32_t)(a.H * a.W * a.ip) * 2u, out_bytes = (uint32_t)(a.H * a.W * a.op) * 2u;
+    auto decode = [&](int tile, int& tx, int& ty, int& img) {
+        tx = tile % a.tiles_x;
+        ty = (tile / a.tiles_x) % a.tiles_y;
+        img = tile / (a.tiles_x * a.tiles_y);
+    };
+    auto issue = [&](int tile, int buf) {
+        int tx, ty, img;
+        decode(tile, tx, ty, img);
+        const int ih0 = ty * kR3TH - 1, iw0 = tx * 8 * a.nb - 1;
+        const __amdgpu_buffer_rsrc_t x_srd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(a.X) + (int64_t)img * a.H * a.W * a.ip, 0, in_bytes, kBufFlags);
+        const uint32_t xs = (uint32_t)((ih0 * a.W + iw0) * a.ip * 2);
+        uint8_t* dst = pbuf + buf * kR3PatchBytes;
+#pragma unroll
+        for (int i = 0; i < PL; ++i) {
+            const int ih = ih0 + (p_rc[i] >> 16), iw = iw0 + (p_rc[i] & 0xffff);
+            const bool ok = p_rc[i] >= 0 && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            // (slots past the buffer's end belong to lanes of the last load that must not write at all)
+            if (p_rc[i] != -2)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(x_srd, (lds_void_ptr)(dst + p_idx[i] * 1024), 16,
+                                                         ok ? p_rel[i] + xs : kBufOut, 0, 0, 0);
+        }
+    };
+
+    // ---- MFMA state -----------------------------------------------------------------------------------------------
+    const int l32 = lane & 31, h = lane >> 5;
+    const int pr0 = l32 >> 3, pc0 = wave * 8 + (l32 & 7);  // this lane's output pixel inside the tile
+    const bool active = wave < a.nb;
+    uint32_t pb[9], pk[9];  // per tap: byte offset of the pixel under it in a patch, and its chunk swizzle (<< 4)
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        const int pr = pr0 + t / 3, pc = pc0 + t % 3;
+        pb[t] = (uint32_t)((pr * kR3PW + pc) * 128);
+        pk[t] = (uint32_t)((((pc >> 1) & 3) | ((pr & 1) << 2)) << 4);
+    }
+    const uint8_t* wa = wl + l32 * kR3WRow + h * 16;
+    const uint32_t hc = (uint32_t)(h << 4);
+
+    issue(first, 0);
+    int buf = 0;
+    for (int tile = first; tile < last; ++tile, buf ^= 1) {
+        const bool more = tile + 1 < last;  // uniform
+        // the patch of this tile (and at first the weights) has landed; this wave's stores of the previous tile, which
+        // were issued after those loads, may still be in flight (every active wave issues exactly four)
+        if (active && tile != first) wait_vmcnt<4>();
+        else wait_vmcnt<0>();
+        barrier_nofence();
+        if (more) issue(tile + 1, buf ^ 1);
+        // the loads stay here, ahead of the multiply and of the stores: the wait at the top of the next tile counts on
+        // the stores being the last four memory instructions of the wave, and the loads need the multiply's time to land
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        if (active) {
+            int tx, ty, img;
+            decode(tile, tx, ty, img);
+            f32x16 acc[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[kb][v] = 0.f;
+            const uint8_t* pp = pbuf + buf * kR3PatchBytes;
+            bf16x8 xb[2], w0[2], w1[2];
+            auto read_frags = [&](auto s_c) {
+                constexpr int S = decltype(s_c)::value, t = S / NCB, cb = S % NCB, B = S & 1, tw = FLIP ? 8 - t : t;
+                xb[B] = *reinterpret_cast<const bf16x8*>(pp + pb[t] + (((uint32_t)(cb << 5) | hc) ^ pk[t]));
+                w0[B] = *reinterpret_cast<const bf16x8*>(wa + tw * 128 + cb * 32);
+                if constexpr (KB1) w1[B] = *reinterpret_cast<const bf16x8*>(wa + 32 * kR3WRow + tw * 128 + cb * 32);
+            };
+            read_frags(std::integral_constant<int, 0>{});
+            static_for<0, 9 * NCB>([&](auto s_c) {
+                constexpr int S = decltype(s_c)::value, B = S & 1;
+                if constexpr (S + 1 < 9 * NCB) read_frags(std::integral_constant<int, S + 1>{});
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0[B], xb[B], acc[0], 0, 0, 0);
+                if constexpr (KB1) acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1[B], xb[B], acc[1], 0, 0, 0);
+            });
+            // ---- store: the lane-pair exchange of k_igemm_dl (64 contiguous bytes per pixel pair and output block) -----
+            const __amdgpu_buffer_rsrc_t y_srd = __builtin_amdgcn_make_buffer_rsrc(
+                a.Y + (int64_t)img * a.H * a.W * a.op, 0, out_bytes, kBufFlags);
+            const int oh = ty * kR3TH + pr0, ow = tx * 8 * a.nb + pc0;
+            const bool odd = (lane & 1) != 0;
+            const int chl = (odd ? 16 : 0) + 8 * h;
+            const bool row_ok = oh < a.H;
+            const bool ok0 = row_ok && (ow & ~1) < a.W, ok1 = row_ok && (ow | 1) < a.W;
+            const uint32_t pix0 = (uint32_t)((oh * a.W + (ow & ~1)) * a.op) * 2u;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const int ch = kb * 32 + chl;
+                const f32x16& c = acc[kb];
+                uint32_t v[2][4];
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp) {
+                    const uint32_t x0 = cvt_pk_bf16(c[8 * gp + 0], c[8 * gp + 1]), y0 = cvt_pk_bf16(c[8 * gp + 2], c[8 * gp + 3]);
+                    const uint32_t x1 = cvt_pk_bf16(c[8 * gp + 4], c[8 * gp + 5]), y1 = cvt_pk_bf16(c[8 * gp + 6], c[8 * gp + 7]);
+                    const auto ps = __builtin_amdgcn_permlane32_swap(x0, x1, false, false);
+                    const auto qs = __builtin_amdgcn_permlane32_swap(y0, y1, false, false);
+                    v[gp][0] = ps[0]; v[gp][1] = qs[0]; v[gp][2] = ps[1]; v[gp][3] = qs[1];
+                }
+                uint32_t s0[4], s1[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t give = odd ? v[0][e] : v[1][e];
+                    const uint32_t got = (uint32_t)__shfl_xor((int)give, 1, 64);
+                    s0[e] = odd ? got : v[0][e];
+                    s1[e] = odd ? v[1][e] : got;
+                }
+                uint4 o0 = make_uint4(s0[0], s0[1], s0[2], s0[3]), o1 = make_uint4(s1[0], s1[1], s1[2], s1[3]);
+                const bool ch_ok = ch < a.Mout;
+                if (ch_ok && ch + 7 >= a.Mout) {  // last chunk: zeros in its padding
+                    const Mask8 k = make_mask8(a.Mout - ch);
+                    o0 = mask8(o0, true, k);
+                    o1 = mask8(o1, true, k);
+                }
+                const uint32_t off0 = pix0 + (uint32_t)ch * 2u;
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o0), y_srd, ok0 && ch_ok ? off0 : kBufOut, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o1), y_srd,
+                                                       ok1 && ch_ok ? off0 + (uint32_t)a.op * 2u : kBufOut, 0, 0);
+            }
+        }
+    }
+#endif
+}
+
+inline hipError_t launch_conv3x3_res(Res3Args& a, bool flip, hipStream_t st) {
+    const int nbw = (a.W + 7) / 8;
+    a.nb = nbw < kR3MaxNB ? nbw : kR3MaxNB;
+    a.tiles_x = (a.W + 8 * a.nb - 1) / (8 * a.nb);
+    a.tiles_y = (a.H + kR3TH - 1) / kR3TH;
+    const int64_t tiles = (int64_t)a.N * a.tiles_x * a.tiles_y;
+    if (tiles <= 0 || tiles > 0x3fffffff) return hipErrorInvalidValue;
+    a.tiles = (int)tiles;
+    a.run = (int)((tiles + kR3Slots - 1) / kR3Slots);
+    const unsigned grid = (unsigned)((tiles + a.run - 1) / a.run);
+    typedef void (*kern_t)(const Res3Args);
+    static const kern_t kerns[2][4][2] = {
+        {{k_conv3x3_res<false, 1, false>, k_conv3x3_res<false, 1, true>}, {k_conv3x3_res<false, 2, false>, k_conv3x3_res<false, 2, true>},
+         {k_conv3x3_res<false, 3, false>, k_conv3x3_res<false, 3, true>}, {k_conv3x3_res<false, 4, false>, k_conv3x3_res<false, 4, true>}},
+        {{k_conv3x3_res<true, 1, false>, k_conv3x3_res<true, 1, true>}, {k_conv3x3_res<true, 2, false>, k_conv3x3_res<true, 2, true>},
+         {k_conv3x3_res<true, 3, false>, k_conv3x3_res<true, 3, true>}, {k_conv3x3_res<true, 4, false>, k_conv3x3_res<true, 4, true>}}};
+    static LdsOptIn opt_in[2][4][2];
+    const int ncb = (a.CinP + 15) / 16, kb1 = a.Mout > 32 ? 1 : 0;
+    if (ncb < 1 || ncb > 4) return hipErrorInvalidValue;
+    const kern_t kern = kerns[flip ? 1 : 0][ncb - 1][kb1];
+    if (hipError_t e = opt_in[flip ? 1 : 0][ncb - 1][kb1].ensure(reinterpret_cast<const void*>(kern), kR3Lds); e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), kR3Lds, st, a);
+    return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------------- //
 // weight gradient of a network's first layer: image-like input, at most 4 channels at a pitch of 8
 // ------------------------------------------------------------------------------------------- //
 // dw[k][r][s][c] = sum over output pixels of dy[pixel][k] * x[pixel * stride + (r, s)][c] (Eq. 4).  As in k_stem_fwd

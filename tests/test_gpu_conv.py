@@ -164,6 +164,29 @@ def test_narrow_outputs_over_very_many_pixels(case):
     _check_full(spec, 700 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=True)
 
 
+EARLY_3X3 = [
+    # 3 x 3, stride 1, padding 1, at most 64 channels on either side: the kernel that keeps the filter bank in LDS
+    # (forward and input gradient); tiles are 4 rows x up to 56 columns
+    ((2, 56, 56, 64, 64, 3, 1, 1), False),     # the shape it is for: one tile column of seven 8-pixel blocks
+    ((3, 30, 70, 64, 64, 3, 1, 1), False),     # two tile columns (the second partial), a partial last tile row
+    ((2, 13, 21, 40, 24, 3, 1, 1), False),     # three column blocks, 24 outputs: one accumulator block, 40 inputs: 2.5 steps
+    ((2, 9, 5, 8, 8, 3, 1, 1), False),         # narrower than one block, a single 8-channel chunk
+    ((2, 17, 33, 45, 38, 3, 1, 1), True),      # ragged counts, zero padding vouched for
+    ((2, 20, 20, 26, 40, 3, 1, 1), True),
+    ((2, 6, 60, 33, 56, 3, 1, 1), True),
+    ((20, 56, 56, 32, 64, 3, 1, 1), False),    # 280 tiles: runs of two tiles per workgroup, the last run of one
+    ((37, 28, 28, 16, 48, 3, 1, 1), False),    # 259 tiles of four blocks
+    ((2, 20, 20, 48, 64, 3, 1, 1), False),     # input gradient: four 16-channel steps per tap and two accumulator blocks
+]
+
+
+@pytest.mark.parametrize("case,pad_zero", EARLY_3X3, ids=lambda c: "x".join(map(str, c)) if isinstance(c, tuple) else str(c))
+def test_early_3x3_layers_with_resident_weights(case, pad_zero):
+    from gpu_util import pitch8
+    spec = _spec(*case)
+    _check_full(spec, 950 + sum(case), pitch8(spec.C), pitch8(spec.K), pitch8(spec.C), pad_zero=pad_zero)
+
+
 BATCHED_FWD = [
     # independent forward convolutions in one call: pairs that share a launch of the direct kernel (same tile shape and
     # variant: a block's first convolution and its strided shortcut), pairs that do not, and the other kernels mixed in
