@@ -363,7 +363,7 @@ def main():
     # dominant kernel of the step: k_igemm_dl serves conv_fwd and conv_bwd_data, k_wgrad_dl (+ its reduction pass)
     # conv_bwd_weight; the one with the larger time over both widths is reported against its roof
     tot = {k: fam["full"][k] + fam["pruned"][k] for k in CONV_KINDS}
-    kernels = {"k_igemm_dl (conv_fwd + conv_bwd_data launches; the first layer's forward is k_stem_fwd)": ("fwd", "bwd_data"),
+    kernels = {"k_igemm_dl (conv_fwd + conv_bwd_data launches; the first layer's forward is k_stem_fwd, early 3x3 layers take k_conv3x3_res)": ("fwd", "bwd_data"),
                "k_wgrad_dl + k_wgrad_reduce (conv_bwd_weight launches)": ("bwd_weight",)}
     dom_kernel = max(kernels, key=lambda k: sum(tot[f] for f in kernels[k]))
     fams = kernels[dom_kernel]

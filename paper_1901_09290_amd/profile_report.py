@@ -62,11 +62,11 @@ def short(name: str) -> str:
     return n.replace("pt::", "")
 
 
-MAIN_FAMILIES = ("k_igemm_dl", "k_wgrad_dl", "k_igemm", "k_wgrad", "k_stem_fwd", "k_stem_wgrad")
+MAIN_FAMILIES = ("k_igemm_dl", "k_wgrad_dl", "k_igemm", "k_wgrad", "k_stem_fwd", "k_stem_wgrad", "k_conv3x3_res")
 
 
 def family(n: str) -> Optional[str]:
-    for f in ("k_igemm_dl", "k_igemm", "k_stem_fwd", "k_stem_wgrad_reduce", "k_stem_wgrad", "k_wgrad_dl", "k_wgrad_reduce", "k_wgrad",
+    for f in ("k_igemm_dl", "k_igemm", "k_conv3x3_res", "k_stem_fwd", "k_stem_wgrad_reduce", "k_stem_wgrad", "k_wgrad_dl", "k_wgrad_reduce", "k_wgrad",
               "k_zero_class"):
         if n.startswith(f + "<") or n == f or n.startswith(f + "4"):
             return "k_wgrad_reduce" if f in ("k_wgrad_reduce", "k_stem_wgrad_reduce") else f
@@ -279,7 +279,7 @@ def cmd_traffic(a) -> None:
                  % (k[4] / k[0] / 1e6, (k[2] + k[3]) / k[4]))
     k = per_kind["igemm"]
     if k[0]:
-        o.append("per k_igemm_dl launch (conv_fwd and conv_bwd_data calls, %d launches, the first layer's k_stem_fwd and the zero fill of empty parity classes included): fetch %.1f MB + write %.1f MB = %.1f MB of HBM traffic"
+        o.append("per k_igemm_dl launch (conv_fwd and conv_bwd_data calls, %d launches, the first layer's k_stem_fwd, the early 3x3 layers' k_conv3x3_res and the zero fill of empty parity classes included): fetch %.1f MB + write %.1f MB = %.1f MB of HBM traffic"
                  % (k[1], k[2] / k[1] / 1e6, k[3] / k[1] / 1e6, (k[2] + k[3]) / k[1] / 1e6))
         o.append("algorithmic bytes per launch: %.1f MB  -> traffic / algorithmic = %.2f" % (k[4] / k[1] / 1e6, (k[2] + k[3]) / k[4]))
     _write(a.out, o)
