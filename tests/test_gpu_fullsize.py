@@ -297,9 +297,17 @@ def test_hip_graph_replays_equal_eager():
         wl.ConvSpec("g1", 8, 32, 32, 24, 40, 3, 3, 2, 1, 0, 1),
         wl.ConvSpec("g2", 8, 16, 16, 40, 72, 1, 1, 1, 0, 1, 2),
         wl.ConvSpec("g3", 8, 16, 16, 72, 72, 3, 3, 1, 1, 2, None),
+        # a residual block with a shortcut convolution: the pair (b_a, b_proj) goes out as one batched forward call, the
+        # shortcut's input gradient runs on a side stream, and b_b takes the kernel with the filter bank in LDS
+        wl.ConvSpec("b_a", 8, 16, 16, 72, 32, 1, 1, 1, 0, 2, 3),
+        wl.ConvSpec("b_b", 8, 16, 16, 32, 32, 3, 3, 1, 1, 3, 4),
+        wl.ConvSpec("b_c", 8, 16, 16, 32, 96, 1, 1, 1, 0, 4, 5),
+        wl.ConvSpec("b_proj", 8, 16, 16, 72, 96, 1, 1, 1, 0, 2, 5),
     ]
-    edges = [wl.Edge("e0", 24, [0], [1]), wl.Edge("e1", 40, [1], [2]), wl.Edge("e2", 72, [2], [3])]
+    edges = [wl.Edge("e0", 24, [0], [1]), wl.Edge("e1", 40, [1], [2]), wl.Edge("e2", 72, [2], [3, 4, 7]),
+             wl.Edge("e3", 32, [4], [5]), wl.Edge("e4", 32, [5], [6]), wl.Edge("e5", 96, [6, 7], [])]
     net = hz.Network(hz.build_network(specs, seed=5))
+    assert net.fork == {4: 7} and net.overlap_branches and net.batch_branches_fwd
     rng = np.random.Generator(np.random.PCG64(5))
     zero_sets = wl.zeroed_channel_sets(edges, 0.25, rng)
     model = hz.ReconfigModel(specs, edges, wl.network_weights(specs, edges, zero_sets, rng), seed=6)
